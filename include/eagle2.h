@@ -1,0 +1,222 @@
+/*
+ * eagle2.h -- C ABI of the MI355X (gfx950) hot path for one draft-plus-verify
+ * round of the context-aware dynamic draft tree of EAGLE-2 (arXiv 2406.16858).
+ *
+ * One round = depth x eagle2_expand, eagle2_rerank, eagle2_tree_attn (once per
+ * attention layer of the verifying model), eagle2_accept.
+ *
+ * Common rules for every entry point
+ *   - Every pointer is caller-owned DEVICE memory on the current HIP device,
+ *     16-byte aligned, unless the parameter is documented as a host value.  The
+ *     library never allocates, frees or keeps a pointer after the call returns.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  No entry point synchronises with the host; outputs are
+ *     valid once the stream reaches that point.
+ *   - `workspace` is scratch owned by the caller, at least
+ *     eagle2_workspace_bytes() long, 256-byte aligned.  Its contents carry nothing
+ *     from one call to the next.  Calls that share a workspace must be ordered on
+ *     one stream.
+ *   - Return value: EAGLE2_OK, or a negative error code; on error nothing has
+ *     been enqueued and eagle2_last_error() describes the problem.
+ *   - Inputs must be finite.  NaN/Inf give unspecified results but never an
+ *     out-of-bounds access.
+ *   - Batched arrays are [batch, ...] contiguous.
+ *
+ * Notation (the paper's, Section 4): V vocabulary size, Hd hidden size, D tree
+ * depth, k nodes expanded per layer (= children kept per node), N rows of the
+ * flattened tree including the root, C = k + (D-1) k^2 candidate nodes of a
+ * round, R = 1 + (D-1) k LM-head rows of a round, P length of a sequence's KV
+ * prefix.
+ *
+ * Candidate ids.  Pass d (0-based) expands the layer-d frontier into layer d+1.
+ * Layer 1 holds ids 0..k-1 (by rank); layer L >= 2 holds
+ * k + (L-2) k^2 + slot*k + rank, where slot is the parent's position in its
+ * frontier and rank the child's rank in the parent's distribution.  A larger id
+ * is never shallower, so "lower id first" implements the paper's "prefer the
+ * shallower node" rule for equal values (Section 4.2).
+ */
+#ifndef EAGLE2_H
+#define EAGLE2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EAGLE2_OK             0
+#define EAGLE2_ERR_ARG       (-1)  /* null, misaligned or out-of-range argument        */
+#define EAGLE2_ERR_SHAPE     (-2)  /* shape outside the supported set (see eagle2_cfg) */
+#define EAGLE2_ERR_WORKSPACE (-3)  /* workspace null or too small                      */
+#define EAGLE2_ERR_HIP       (-4)  /* a HIP call failed; see eagle2_last_error()       */
+
+#define EAGLE2_DTYPE_F32  0
+#define EAGLE2_DTYPE_BF16 1
+
+#define EAGLE2_MODE_GREEDY 0
+#define EAGLE2_MODE_SAMPLE 1
+
+#define EAGLE2_MAX_TOPK    16
+#define EAGLE2_MAX_TREE    128
+#define EAGLE2_MAX_CAND    2048
+
+/*
+ * Shape of a round.  Supported: 1 <= topk <= 16 <= vocab; depth >= 1;
+ * 2 <= n_tree <= 128 and n_tree - 1 <= C <= 2048; hidden * sizeof(dtype) a
+ * multiple of 1024 bytes; batch >= 1.
+ */
+typedef struct eagle2_cfg {
+    int32_t batch;   /* B: sequences, each with its own tree                     */
+    int32_t vocab;   /* V                                                         */
+    int32_t hidden;  /* Hd                                                        */
+    int32_t depth;   /* D: LM-head passes per round = deepest layer              */
+    int32_t topk;    /* k                                                         */
+    int32_t n_tree;  /* N: flattened rows including the root                     */
+    int32_t dtype;   /* EAGLE2_DTYPE_*: element type of H, W, Q, K, V and O      */
+} eagle2_cfg;
+
+/* Attention geometry.  Supported: head_dim 64 or 128; n_q_heads a multiple of
+ * n_kv_heads. */
+typedef struct eagle2_attn_cfg {
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    float   scale;         /* multiplies q.k; 0 selects 1/sqrt(head_dim)           */
+    int64_t total_prefix;  /* host value: rows of K_prefix/V_prefix = kv_offsets[B] */
+} eagle2_attn_cfg;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int eagle2_version(void);
+
+/* Text of the last error raised on the calling thread ("" if none). */
+const char* eagle2_last_error(void);
+
+/* Bytes of workspace that is enough for any of the four calls with these shapes
+ * (attn may be NULL if eagle2_tree_attn is not used).  0 on invalid shapes. */
+size_t eagle2_workspace_bytes(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn);
+
+/*
+ * Expansion phase, pass d (Section 4.1).
+ *
+ * For every sequence b and frontier slot s (F_d rows: F_0 = 1, else k) the draft
+ * model's token distribution is softmax(H[b,s,:] . W^T); its k most probable
+ * tokens (ties: lower token id) become children of the node in frontier[b,d,s]
+ * with joint score = parent score + log-probability (the value equation of
+ * Section 4.1, kept as a sum of logs; the root's score is 0).  Children are
+ * appended to the candidate arrays at ids base_d + s*k + rank.  If d+1 < D the k
+ * new candidates of highest score (ties: lower id) are written to
+ * frontier[b,d+1,:], best first (Section 4.1, last paragraph).
+ *
+ *   H            [B, F_d, Hd] dtype; sequence b starts at element b*h_seq_stride
+ *                (h_seq_stride = 0 means F_d*Hd, i.e. contiguous).
+ *   W            [V, Hd] dtype, row-major: the LM head.
+ *   cand_token   [B, C] int32   in/out: pass d writes ids base_d .. base_d+F_d*k-1
+ *   cand_score   [B, C] float64 in/out: reads the parents' scores
+ *   cand_parent  [B, C] int32   in/out: candidate id of the parent, -1 = root
+ *   frontier     [B, D, k] int32 in/out: row d is read (d >= 1), row d+1 written;
+ *                row 0 is never touched.
+ *   draft_logits nullable; [B, R, V] float32.  Row (d == 0 ? 0 : 1 + (d-1)k + s)
+ *                receives the raw logits of slot s; needed later only by
+ *                eagle2_accept in sampling mode.
+ */
+int eagle2_expand(const eagle2_cfg* cfg, int32_t d,
+                  const void* H, int64_t h_seq_stride, const void* W,
+                  int32_t* cand_token, double* cand_score, int32_t* cand_parent,
+                  int32_t* frontier, float* draft_logits,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Reranking phase and flattening (Section 4.2).
+ *
+ * Selects the N-1 candidates of highest score (ties: lower id = shallower),
+ * lays them out behind the root in increasing id order (parents precede
+ * children) and builds, per row, the ancestor bitmask under which the row sees
+ * exactly itself and its ancestors (Section 4.2, second paragraph).
+ *
+ *   root_token   [B] int32: token of the root (the last committed token)
+ *   prefix_len   [B] int32: P_b, used for position_ids = P_b + depth
+ *   tree_token, tree_parent (flat row of the parent, -1 for the root), tree_depth,
+ *   tree_cand (candidate id, -1 for the root), position_ids: [B, N] int32 outputs
+ *   mask_bits    [B, N, ceil(N/64)] uint64 output: bit (j % 64) of word j / 64 of
+ *                row i is set iff j == i or row j is an ancestor of row i.
+ * The candidate arrays must come from D completed eagle2_expand passes (scores
+ * non-increasing from parent to child); otherwise tree_parent is unspecified.
+ */
+int eagle2_rerank(const eagle2_cfg* cfg,
+                  const int32_t* cand_token, const double* cand_score, const int32_t* cand_parent,
+                  const int32_t* root_token, const int32_t* prefix_len,
+                  int32_t* tree_token, int32_t* tree_parent, int32_t* tree_depth,
+                  int32_t* tree_cand, int32_t* position_ids, uint64_t* mask_bits,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Tree attention of the verification pass (Section 4.2, second paragraph).
+ *
+ * Row i of sequence b, query head h, attends to all P_b prefix keys and to the
+ * tree keys j whose bit is set in mask_bits[b,i]; KV head = h / (Hq / Hkv).
+ * O = softmax(scale * q.k) v with the softmax taken in float32 (float32 inputs:
+ * everything in float32).  No rotary embedding is applied inside.
+ *
+ *   Q            [B, N, Hq, dh] dtype
+ *   K_prefix, V_prefix  [total_prefix, Hkv, dh] dtype; sequence b owns rows
+ *                kv_offsets[b] .. kv_offsets[b+1]-1
+ *   kv_offsets   [B+1] int64 (device), non-decreasing, kv_offsets[0] = 0
+ *   K_tree, V_tree      [B, N, Hkv, dh] dtype
+ *   mask_bits    as written by eagle2_rerank
+ *   O            [B, N, Hq, dh] dtype output
+ *   lse          nullable; [B, N, Hq] float32: log-sum-exp of the scaled scores
+ */
+int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn,
+                     const void* Q, const void* K_prefix, const void* V_prefix,
+                     const int64_t* kv_offsets, const void* K_tree, const void* V_tree,
+                     const uint64_t* mask_bits, void* O, float* lse,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Acceptance (Sections 2.1 and 2.2).
+ *
+ * mode[b] = EAGLE2_MODE_GREEDY: the target's choice after a row is the arg-max of
+ * its logits (ties: lower id); starting at the root the walk moves to the child
+ * whose token equals the choice while there is one; bonus_token is the choice at
+ * the last accepted row.
+ * mode[b] = EAGLE2_MODE_SAMPLE: speculative sampling along the tree.  At the
+ * current row p = softmax(target_logits / temperature[b]) and q = softmax of the
+ * draft logits its children were taken from.  Children are tried in flat order;
+ * child c with token x is accepted iff u_accept[b,c] < p(x)/q(x) (Section 2.1);
+ * after a rejection p <- norm(max(0, p - q)), x is removed from q and q
+ * renormalised, and the next sibling is tried (Section 2.2).  With no child left
+ * bonus_token is drawn from p by inverse CDF with u_bonus[b, current row].  The
+ * sampling arithmetic is carried out in float64.
+ *
+ *   target_logits [B, N, V] float32
+ *   draft_logits  [B, R, V] float32 (may be NULL if no sequence samples)
+ *   temperature   [B] float32 (> 0; read for sampling sequences only)
+ *   u_accept, u_bonus [B, N] float32 in [0, 1) (sampling only; may be NULL otherwise)
+ *   tree_token, tree_parent, tree_cand  [B, N] int32 from eagle2_rerank
+ *   accept_len    [B] int32 output: number of accepted draft tokens
+ *   accept_path   [B, D+1] int32 output: flat rows root..last accepted, -1 padded
+ *   bonus_token   [B] int32 output
+ */
+int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
+                  const float* target_logits, const float* draft_logits,
+                  const float* temperature, const float* u_accept, const float* u_bonus,
+                  const int32_t* tree_token, const int32_t* tree_parent, const int32_t* tree_cand,
+                  int32_t* accept_len, int32_t* accept_path, int32_t* bonus_token,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Kernel timing for benchmarks (not part of the method).  While enabled, every
+ * eagle2_expand records a HIP event pair around its LM-head streaming kernel and
+ * every eagle2_tree_attn around its split-KV kernel, on the caller's stream.
+ * eagle2_kernel_timing_read synchronises those events (host-blocking), returns
+ * the summed milliseconds and launch counts since the last read, and resets.
+ * which: 0 = LM-head kernel, 1 = tree-attention kernel.
+ */
+int eagle2_kernel_timing_enable(int32_t enable);
+int eagle2_kernel_timing_read(int32_t which, double* total_ms, int32_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EAGLE2_H */

@@ -1,0 +1,177 @@
+"""ctypes binding of libeagle2_hip.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "_lib", "libeagle2_hip.so")
+_lib = None
+
+DTYPE_F32, DTYPE_BF16 = 0, 1
+MODE_GREEDY, MODE_SAMPLE = 0, 1
+
+
+class Eagle2Error(RuntimeError):
+    pass
+
+
+class RoundCfg(C.Structure):
+    """Mirror of eagle2_cfg."""
+    _fields_ = [("batch", C.c_int32), ("vocab", C.c_int32), ("hidden", C.c_int32), ("depth", C.c_int32),
+                ("topk", C.c_int32), ("n_tree", C.c_int32), ("dtype", C.c_int32)]
+
+    @property
+    def n_cand(self) -> int:
+        return self.topk + (self.depth - 1) * self.topk * self.topk
+
+    @property
+    def n_draft_rows(self) -> int:
+        return 1 + (self.depth - 1) * self.topk
+
+
+class AttnCfg(C.Structure):
+    """Mirror of eagle2_attn_cfg."""
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("scale", C.c_float), ("total_prefix", C.c_int64)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads the built library; raises if it is missing (there is no other code path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise Eagle2Error(f"{_LIB_PATH} not found: build it with `python -m paper_2406_16858_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    lib.eagle2_version.restype = C.c_int
+    lib.eagle2_last_error.restype = C.c_char_p
+    lib.eagle2_workspace_bytes.restype = sz
+    lib.eagle2_workspace_bytes.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg)]
+    lib.eagle2_expand.restype = C.c_int
+    lib.eagle2_expand.argtypes = [C.POINTER(RoundCfg), i32, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.eagle2_rerank.restype = C.c_int
+    lib.eagle2_rerank.argtypes = [C.POINTER(RoundCfg)] + [vp] * 11 + [vp, sz, vp]
+    lib.eagle2_tree_attn.restype = C.c_int
+    lib.eagle2_tree_attn.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg)] + [vp] * 9 + [vp, sz, vp]
+    lib.eagle2_accept.restype = C.c_int
+    lib.eagle2_accept.argtypes = [C.POINTER(RoundCfg)] + [vp] * 12 + [vp, sz, vp]
+    lib.eagle2_kernel_timing_enable.restype = C.c_int
+    lib.eagle2_kernel_timing_enable.argtypes = [i32]
+    lib.eagle2_kernel_timing_read.restype = C.c_int
+    lib.eagle2_kernel_timing_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(i32)]
+    _lib = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor], dtype: Optional[torch.dtype] = None, name: str = "tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise Eagle2Error(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise Eagle2Error(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise Eagle2Error(f"{name} must be {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise Eagle2Error(f"eagle2 error {rc}: {load_library().eagle2_last_error().decode()}")
+
+
+def _ws(workspace: Optional[torch.Tensor]):
+    if workspace is None:
+        return None, 0
+    return C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def _elem(cfg: RoundCfg) -> torch.dtype:
+    return torch.float32 if cfg.dtype == DTYPE_F32 else torch.bfloat16
+
+
+def eagle2_version() -> int:
+    return load_library().eagle2_version()
+
+
+def eagle2_workspace_bytes(cfg: RoundCfg, attn: Optional[AttnCfg] = None) -> int:
+    return int(load_library().eagle2_workspace_bytes(C.byref(cfg), C.byref(attn) if attn is not None else None))
+
+
+def eagle2_expand(cfg: RoundCfg, d: int, H: torch.Tensor, W: torch.Tensor, cand_token, cand_score, cand_parent,
+                  frontier, draft_logits, workspace, h_seq_stride: int = 0, stream=None):
+    lib = load_library()
+    el = _elem(cfg)
+    # H may be a strided view over sequences; only its first element's address and the stride are passed
+    if not H.is_cuda or H.dtype != el:
+        raise Eagle2Error("H must be a device tensor of the configured dtype")
+    wp, wb = _ws(workspace)
+    _check(lib.eagle2_expand(C.byref(cfg), d, C.c_void_p(H.data_ptr()), h_seq_stride, _ptr(W, el, "W"),
+                             _ptr(cand_token, torch.int32, "cand_token"), _ptr(cand_score, torch.float64, "cand_score"),
+                             _ptr(cand_parent, torch.int32, "cand_parent"), _ptr(frontier, torch.int32, "frontier"),
+                             _ptr(draft_logits, torch.float32, "draft_logits"), wp, wb, _stream(stream)))
+
+
+def eagle2_rerank(cfg: RoundCfg, cand_token, cand_score, cand_parent, root_token, prefix_len,
+                  tree_token, tree_parent, tree_depth, tree_cand, position_ids, mask_bits, workspace=None, stream=None):
+    lib = load_library()
+    wp, wb = _ws(workspace)
+    i32 = torch.int32
+    _check(lib.eagle2_rerank(C.byref(cfg), _ptr(cand_token, i32, "cand_token"), _ptr(cand_score, torch.float64, "cand_score"),
+                             _ptr(cand_parent, i32, "cand_parent"), _ptr(root_token, i32, "root_token"),
+                             _ptr(prefix_len, i32, "prefix_len"), _ptr(tree_token, i32, "tree_token"),
+                             _ptr(tree_parent, i32, "tree_parent"), _ptr(tree_depth, i32, "tree_depth"),
+                             _ptr(tree_cand, i32, "tree_cand"), _ptr(position_ids, i32, "position_ids"),
+                             _ptr(mask_bits, torch.int64, "mask_bits"), wp, wb, _stream(stream)))
+
+
+def eagle2_tree_attn(cfg: RoundCfg, attn: AttnCfg, Q, K_prefix, V_prefix, kv_offsets, K_tree, V_tree, mask_bits,
+                     O, lse, workspace, stream=None):
+    lib = load_library()
+    el = _elem(cfg)
+    wp, wb = _ws(workspace)
+    _check(lib.eagle2_tree_attn(C.byref(cfg), C.byref(attn), _ptr(Q, el, "Q"), _ptr(K_prefix, el, "K_prefix"),
+                                _ptr(V_prefix, el, "V_prefix"), _ptr(kv_offsets, torch.int64, "kv_offsets"),
+                                _ptr(K_tree, el, "K_tree"), _ptr(V_tree, el, "V_tree"),
+                                _ptr(mask_bits, torch.int64, "mask_bits"), _ptr(O, el, "O"),
+                                _ptr(lse, torch.float32, "lse"), wp, wb, _stream(stream)))
+
+
+def eagle2_accept(cfg: RoundCfg, mode, target_logits, draft_logits, temperature, u_accept, u_bonus,
+                  tree_token, tree_parent, tree_cand, accept_len, accept_path, bonus_token, workspace, stream=None):
+    lib = load_library()
+    wp, wb = _ws(workspace)
+    i32, f32 = torch.int32, torch.float32
+    _check(lib.eagle2_accept(C.byref(cfg), _ptr(mode, i32, "mode"), _ptr(target_logits, f32, "target_logits"),
+                             _ptr(draft_logits, f32, "draft_logits"), _ptr(temperature, f32, "temperature"),
+                             _ptr(u_accept, f32, "u_accept"), _ptr(u_bonus, f32, "u_bonus"),
+                             _ptr(tree_token, i32, "tree_token"), _ptr(tree_parent, i32, "tree_parent"),
+                             _ptr(tree_cand, i32, "tree_cand"), _ptr(accept_len, i32, "accept_len"),
+                             _ptr(accept_path, i32, "accept_path"), _ptr(bonus_token, i32, "bonus_token"),
+                             wp, wb, _stream(stream)))
+
+
+def eagle2_kernel_timing_enable(enable: bool):
+    _check(load_library().eagle2_kernel_timing_enable(1 if enable else 0))
+
+
+def eagle2_kernel_timing_read(which: int):
+    ms, n = C.c_double(0.0), C.c_int32(0)
+    _check(load_library().eagle2_kernel_timing_read(which, C.byref(ms), C.byref(n)))
+    return ms.value, n.value

@@ -1,0 +1,129 @@
+// Reranking phase and flattening (Section 4.2 of the EAGLE-2 paper): global top-(N-1)
+// of all candidates by joint score (ties to the lower id, i.e. the shallower node),
+// flattening in increasing id order behind the root, parent rows, depths, position ids
+// and the ancestor bitmask ("each token can only see its ancestor nodes").
+//
+// One workgroup per sequence.  The C <= 2048 (score, id) pairs are sorted by a bitonic
+// network in LDS; the rest is a handful of LDS look-ups.
+
+#include "common.h"
+
+namespace eagle2 {
+
+constexpr int RR_THREADS = 1024;
+
+__global__ __launch_bounds__(RR_THREADS)
+void rerank_kernel(int C, int n2, int N, int k, int words,
+                   const int* __restrict__ cand_token, const double* __restrict__ cand_score,
+                   const int* __restrict__ cand_parent, const int* __restrict__ root_token,
+                   const int* __restrict__ prefix_len,
+                   int* __restrict__ tree_token, int* __restrict__ tree_parent, int* __restrict__ tree_depth,
+                   int* __restrict__ tree_cand, int* __restrict__ position_ids,
+                   unsigned long long* __restrict__ mask_bits) {
+    __shared__ double s_key[EAGLE2_MAX_CAND];
+    __shared__ int s_id[EAGLE2_MAX_CAND];
+    __shared__ int s_row_of[EAGLE2_MAX_CAND];      // flat row of a candidate, -1 if not selected
+    __shared__ int s_sel[EAGLE2_MAX_TREE];         // selected candidate ids (sorted order)
+    __shared__ int s_par[EAGLE2_MAX_TREE];         // flat parent row per flat row
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const double* score = cand_score + (size_t)b * C;
+    const int* ctok = cand_token + (size_t)b * C;
+    const int* cpar = cand_parent + (size_t)b * C;
+
+    for (int i = tid; i < n2; i += RR_THREADS) {
+        s_key[i] = i < C ? score[i] : -INFINITY;
+        s_id[i] = i < C ? i : INT_MAX;
+        if (i < C) s_row_of[i] = -1;
+    }
+    // bitonic sort, best candidate first
+    for (int size = 2; size <= n2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int t = tid; t < (n2 >> 1); t += RR_THREADS) {
+                const int i = 2 * t - (t & (stride - 1));
+                const int j = i + stride;
+                const bool fwd = (i & size) == 0;
+                const double ka = s_key[i], kb = s_key[j];
+                const int ia = s_id[i], ib = s_id[j];
+                const bool b_first = ranks_before(kb, ib, ka, ia);
+                if (b_first == fwd) {
+                    s_key[i] = kb; s_key[j] = ka;
+                    s_id[i] = ib; s_id[j] = ia;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const int nsel = N - 1;
+    if (tid < nsel) s_sel[tid] = s_id[tid];
+    __syncthreads();
+    int my_row = -1, my_id = -1;
+    if (tid < nsel) {
+        my_id = s_sel[tid];
+        int below = 0;
+        for (int j = 0; j < nsel; ++j) below += s_sel[j] < my_id ? 1 : 0;
+        my_row = 1 + below;                          // flat order = increasing candidate id
+        if (my_id >= 0 && my_id < C) s_row_of[my_id] = my_row;
+    }
+    __syncthreads();
+    const size_t ob = (size_t)b * N;
+    if (tid < nsel && my_id >= 0 && my_id < C) {
+        const int par = cpar[my_id];
+        const int prow = par < 0 ? 0 : (par < C ? s_row_of[par] : -1);
+        const int depth = my_id < k ? 1 : 2 + (my_id - k) / (k * k);
+        s_par[my_row] = prow;
+        tree_token[ob + my_row] = ctok[my_id];
+        tree_parent[ob + my_row] = prow;
+        tree_depth[ob + my_row] = depth;
+        tree_cand[ob + my_row] = my_id;
+        position_ids[ob + my_row] = prefix_len[b] + depth;
+    }
+    if (tid == 0) {
+        s_par[0] = -1;
+        tree_token[ob] = root_token[b];
+        tree_parent[ob] = -1;
+        tree_depth[ob] = 0;
+        tree_cand[ob] = -1;
+        position_ids[ob] = prefix_len[b];
+    }
+    __syncthreads();
+    if (tid < N) {
+        unsigned long long wbits[EAGLE2_MAX_TREE / 64] = {0ull, 0ull};
+        int cur = tid;
+        for (int step = 0; step < N && cur >= 0; ++step) {   // a path has at most N rows
+            wbits[cur >> 6] |= 1ull << (cur & 63);
+            const int p = s_par[cur];
+            cur = p < cur ? p : -1;                 // parents precede children; stops on bad input
+        }
+        for (int wi = 0; wi < words; ++wi) mask_bits[(ob + tid) * words + wi] = wbits[wi];
+    }
+}
+
+size_t rerank_workspace(const eagle2_cfg*) { return 0; }
+
+}  // namespace eagle2
+
+using namespace eagle2;
+
+extern "C" int eagle2_rerank(const eagle2_cfg* cfg,
+                             const int32_t* cand_token, const double* cand_score, const int32_t* cand_parent,
+                             const int32_t* root_token, const int32_t* prefix_len,
+                             int32_t* tree_token, int32_t* tree_parent, int32_t* tree_depth,
+                             int32_t* tree_cand, int32_t* position_ids, uint64_t* mask_bits,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    int rc = validate_cfg(cfg);
+    if (rc != EAGLE2_OK) return rc;
+    E2_REQUIRE(cand_token && cand_score && cand_parent && root_token && prefix_len && tree_token && tree_parent &&
+               tree_depth && tree_cand && position_ids && mask_bits, EAGLE2_ERR_ARG, "eagle2_rerank: null pointer argument");
+    const int C = n_cand(cfg);
+    int n2 = 2;
+    while (n2 < C) n2 <<= 1;
+    const int words = (cfg->n_tree + 63) / 64;
+    hipLaunchKernelGGL(rerank_kernel, dim3(cfg->batch), dim3(RR_THREADS), 0, static_cast<hipStream_t>(stream),
+                       C, n2, cfg->n_tree, cfg->topk, words, cand_token, cand_score, cand_parent, root_token, prefix_len,
+                       tree_token, tree_parent, tree_depth, tree_cand, position_ids,
+                       reinterpret_cast<unsigned long long*>(mask_bits));
+    E2_HIP(hipGetLastError());
+    return EAGLE2_OK;
+}

@@ -1,0 +1,415 @@
+// Tree attention of the verification pass (Section 4.2 of the EAGLE-2 paper: every tree
+// row sees the whole KV prefix plus exactly its ancestors and itself among the tree keys).
+//
+// bf16 path: split-KV attention on the matrix cores.  The keys of a sequence are cut into
+// chunks (prefix chunks of `chunk` keys, plus one chunk holding the N tree keys); a
+// workgroup handles one chunk for one KV head and one block of query rows.  All
+// Hq/Hkv * N query rows of a KV head share each K/V tile.  Both products are computed
+// transposed so that every lane keeps a single query row:
+//     S^T = K . Q^T   (A = K tile from LDS, B = Q fragments held in registers)
+//     O^T = V^T . P^T (A = V^T tile from LDS, B = the probabilities just computed)
+// The output registers of the first product are, lane for lane, the B operand of the
+// second (the contraction index of an MFMA may be permuted freely as long as A and B
+// agree), so P never goes through LDS.  The ancestor bitmask is applied to the tree
+// chunk only.  A second kernel combines the chunks' (max, sum, O) triples.
+//
+// fp32 path: a plain one-query-row-per-workgroup kernel in float32 (small shapes only).
+
+#include "common.h"
+
+namespace eagle2 {
+
+constexpr int TA_THREADS = 256;
+constexpr int TA_KEYS = 64;              // keys per tile
+constexpr float NEG_BIG = -1.0e30f;
+
+struct SeqChunk { int b; int c; int nc; long long off; long long P; int first; };
+
+// Maps a flat chunk index to (sequence, chunk); chunks of sequence b are
+// ceil(P_b / chunk) prefix chunks followed by the tree chunk.
+__device__ __forceinline__ bool locate_chunk(int flat, int B, int chunk, const long long* kv_offsets, SeqChunk& sc) {
+    int rem = flat, first = 0;
+    for (int b = 0; b < B; ++b) {
+        const long long off = kv_offsets[b];
+        const long long P = kv_offsets[b + 1] - off;
+        const int nc = (int)((P + chunk - 1) / chunk) + 1;
+        if (rem < nc) { sc.b = b; sc.c = rem; sc.nc = nc; sc.off = off; sc.P = P; sc.first = first; return true; }
+        rem -= nc;
+        first += nc;
+    }
+    return false;
+}
+__device__ __forceinline__ void locate_seq(int b, int chunk, const long long* kv_offsets, int& first, int& nc) {
+    first = 0;
+    for (int i = 0; i < b; ++i) first += (int)((kv_offsets[i + 1] - kv_offsets[i] + chunk - 1) / chunk) + 1;
+    nc = (int)((kv_offsets[b + 1] - kv_offsets[b] + chunk - 1) / chunk) + 1;
+}
+
+template <int DH> __device__ __forceinline__ int k_swz(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
+__device__ __forceinline__ int v_swz(int row) { return (row & 15) ^ (((row >> 4) & 7) << 1); }
+
+template <int DH, int RBW>
+__global__ __launch_bounds__(TA_THREADS)
+void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kp, const uint16_t* __restrict__ Vp,
+                           const long long* __restrict__ kv_offsets, const uint16_t* __restrict__ Kt,
+                           const uint16_t* __restrict__ Vt, const unsigned long long* __restrict__ mask_bits,
+                           int B, int N, int Hq, int Hkv, int chunk, int words, int nmblk, int rows_pad,
+                           float scale_log2e, float* __restrict__ part_o, float* __restrict__ part_ml) {
+    constexpr int SLOTS = DH / 8;                  // 16-byte slots per K row
+    constexpr int BM = 64 * RBW;                   // query rows per workgroup
+    __shared__ __align__(16) uint8_t s_k[TA_KEYS * DH * 2];
+    __shared__ __align__(16) uint8_t s_vt[DH * TA_KEYS * 2];
+
+    SeqChunk sc;
+    if (!locate_chunk(blockIdx.x, B, chunk, kv_offsets, sc)) return;
+    const int kvh = blockIdx.y / nmblk, mblk = blockIdx.y - kvh * nmblk;
+    const int grp = Hq / Hkv, rows = grp * N;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int m16 = lane & 15, g4 = lane >> 4;
+    const bool is_tree = sc.c == sc.nc - 1;
+    const int count = is_tree ? N : (int)min((long long)chunk, sc.P - (long long)sc.c * chunk);
+    const size_t kv_stride = (size_t)Hkv * DH;     // elements between consecutive keys
+    const uint16_t* kbase = is_tree ? Kt + ((size_t)sc.b * N * Hkv + kvh) * DH
+                                    : Kp + ((size_t)(sc.off + (long long)sc.c * chunk) * Hkv + kvh) * DH;
+    const uint16_t* vbase = is_tree ? Vt + ((size_t)sc.b * N * Hkv + kvh) * DH
+                                    : Vp + ((size_t)(sc.off + (long long)sc.c * chunk) * Hkv + kvh) * DH;
+
+    // query fragments: lane (m16, g4) holds, for its row, dh elements 32t + 8*g4 .. +7
+    u32x4 qf[RBW][DH / 32];
+    unsigned long long mrow[RBW][2];
+    int rho[RBW];
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+        rho[rb] = mblk * BM + (w * RBW + rb) * 16 + m16;
+        const bool ok = rho[rb] < rows;
+        const int n = ok ? rho[rb] / grp : 0, j = ok ? rho[rb] - n * grp : 0;
+        const uint16_t* qrow = Q + (((size_t)sc.b * N + n) * Hq + kvh * grp + j) * DH;
+#pragma unroll
+        for (int t = 0; t < DH / 32; ++t)
+            qf[rb][t] = ok ? *reinterpret_cast<const u32x4*>(qrow + t * 32 + g4 * 8) : u32x4{0u, 0u, 0u, 0u};
+        mrow[rb][0] = (ok && is_tree) ? mask_bits[((size_t)sc.b * N + n) * words] : 0ull;
+        mrow[rb][1] = (ok && is_tree && words > 1) ? mask_bits[((size_t)sc.b * N + n) * words + 1] : 0ull;
+    }
+
+    floatx4 acc[RBW][DH / 16];
+    float m_run[RBW], l_run[RBW];
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+        m_run[rb] = NEG_BIG;
+        l_run[rb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < DH / 16; ++db) acc[rb][db] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int ntile = (count + TA_KEYS - 1) / TA_KEYS;
+    for (int tile = 0; tile < ntile; ++tile) {
+        const int key0 = tile * TA_KEYS;
+        __syncthreads();                           // previous tile fully consumed
+        // K tile -> LDS, row-major, 16-byte slots swizzled by the row
+        for (int p = tid; p < TA_KEYS * SLOTS; p += TA_THREADS) {
+            const int key = p / SLOTS, c = p - key * SLOTS;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (key0 + key < count) v = *reinterpret_cast<const u32x4*>(kbase + (size_t)(key0 + key) * kv_stride + c * 8);
+            *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + ((c ^ k_swz<DH>(key)) << 4)) = v;
+        }
+        // V tile -> LDS transposed: thread takes 4 keys x 8 dh, writes 8 dh rows x 4 keys (8 bytes each)
+        for (int u = tid; u < 16 * SLOTS; u += TA_THREADS) {
+            const int c = u % SLOTS, kg = u / SLOTS;
+            u32x4 r[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int key = key0 + kg * 4 + i;
+                r[i] = key < count ? *reinterpret_cast<const u32x4*>(vbase + (size_t)key * kv_stride + c * 8)
+                                   : u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                u32x2 lo, hi;                      // dh 2*e2 and 2*e2+1, keys 0..3
+                lo[0] = (r[0][e2] & 0xffffu) | (r[1][e2] << 16);
+                lo[1] = (r[2][e2] & 0xffffu) | (r[3][e2] << 16);
+                hi[0] = (r[0][e2] >> 16) | (r[1][e2] & 0xffff0000u);
+                hi[1] = (r[2][e2] >> 16) | (r[3][e2] & 0xffff0000u);
+                const int row0 = c * 8 + e2 * 2, row1 = row0 + 1;
+                *reinterpret_cast<u32x2*>(s_vt + row0 * (TA_KEYS * 2) + ((kg ^ v_swz(row0)) << 3)) = lo;
+                *reinterpret_cast<u32x2*>(s_vt + row1 * (TA_KEYS * 2) + ((kg ^ v_swz(row1)) << 3)) = hi;
+            }
+        }
+        __syncthreads();
+
+        // S^T = K Q^T : s[rb][kb][i] = score(query row of this lane, key kb*16 + 4*g4 + i)
+        floatx4 s[RBW][4];
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) s[rb][kb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+#pragma unroll
+            for (int t = 0; t < DH / 32; ++t) {
+                const int row = kb * 16 + m16;
+                const u32x4 kf = *reinterpret_cast<const u32x4*>(s_k + row * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>(row)) << 4));
+#pragma unroll
+                for (int rb = 0; rb < RBW; ++rb)
+                    s[rb][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, kf), __builtin_bit_cast(bf16x8, qf[rb][t]), s[rb][kb], 0, 0, 0);
+            }
+        }
+
+        bf16x8 pf[RBW][2];
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) {
+            float mx = NEG_BIG;
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int key = key0 + kb * 16 + g4 * 4 + i;
+                    bool vis = key < count;
+                    if (is_tree) vis = vis && (((key < 64 ? mrow[rb][0] : mrow[rb][1]) >> (key & 63)) & 1ull);
+                    const float v = vis ? s[rb][kb][i] * scale_log2e : -INFINITY;
+                    s[rb][kb][i] = v;
+                    mx = fmaxf(mx, v);
+                }
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run[rb], mx);
+            const float alpha = exp2f(m_run[rb] - m_new);
+            m_run[rb] = m_new;
+            float psum = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p = exp2f(s[rb][kb][i] - m_new);
+                    psum += p;
+                    pf[rb][kb >> 1][(kb & 1) * 4 + i] = (__bf16)p;
+                }
+            }
+            l_run[rb] = l_run[rb] * alpha + psum;
+#pragma unroll
+            for (int db = 0; db < DH / 16; ++db) acc[rb][db] *= alpha;
+        }
+
+        // O^T += V^T P^T : keys of MFMA u for lane group g4 are {32u + 4g4 + i} and {32u + 16 + 4g4 + i}
+#pragma unroll
+        for (int db = 0; db < DH / 16; ++db) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int row = db * 16 + m16;
+                const u32x2 va = *reinterpret_cast<const u32x2*>(s_vt + row * (TA_KEYS * 2) + (((8 * u + g4) ^ v_swz(row)) << 3));
+                const u32x2 vb = *reinterpret_cast<const u32x2*>(s_vt + row * (TA_KEYS * 2) + (((8 * u + 4 + g4) ^ v_swz(row)) << 3));
+                const u32x4 vf = {va[0], va[1], vb[0], vb[1]};
+#pragma unroll
+                for (int rb = 0; rb < RBW; ++rb)
+                    acc[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, vf), pf[rb][u], acc[rb][db], 0, 0, 0);
+            }
+        }
+    }
+
+    // partial results of this chunk: un-normalised O (lane holds dh db*16 + 4*g4 + i of its row), max, sum
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+        float l = l_run[rb];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        if (rho[rb] < rows) {
+            const size_t prow = ((size_t)blockIdx.x * Hkv + kvh) * rows_pad + rho[rb];
+#pragma unroll
+            for (int db = 0; db < DH / 16; ++db)
+                *reinterpret_cast<floatx4*>(part_o + prow * DH + db * 16 + g4 * 4) = acc[rb][db];
+            if (g4 == 0) { part_ml[prow * 2] = m_run[rb]; part_ml[prow * 2 + 1] = l; }
+        }
+    }
+}
+
+// grid (B*N, Hq / 4), 4 waves: one wave per (row, head), lanes over dh
+template <int DH>
+__global__ __launch_bounds__(256)
+void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, int N, int Hq, int Hkv, int chunk, int rows_pad,
+                              const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                              uint16_t* __restrict__ O, float* __restrict__ lse) {
+    const int bn = blockIdx.x, b = bn / N, n = bn - b * N;
+    const int h = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (h >= Hq) return;
+    const int grp = Hq / Hkv, kvh = h / grp, rho = n * grp + (h - kvh * grp);
+    int first, nc;
+    locate_seq(b, chunk, kv_offsets, first, nc);
+    float mx = NEG_BIG;
+    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, part_ml[(((size_t)(first + c) * Hkv + kvh) * rows_pad + rho) * 2]);
+    float l = 0.f, o[DH / 64];
+#pragma unroll
+    for (int e = 0; e < DH / 64; ++e) o[e] = 0.f;
+    for (int c = 0; c < nc; ++c) {
+        const size_t prow = ((size_t)(first + c) * Hkv + kvh) * rows_pad + rho;
+        const float wgt = exp2f(part_ml[prow * 2] - mx);
+        l += wgt * part_ml[prow * 2 + 1];
+#pragma unroll
+        for (int e = 0; e < DH / 64; ++e) o[e] += wgt * part_o[prow * DH + e * 64 + lane];
+    }
+    const float inv = 1.f / l;
+    uint16_t* orow = O + ((size_t)bn * Hq + h) * DH;
+#pragma unroll
+    for (int e = 0; e < DH / 64; ++e) {
+        const __bf16 v = (__bf16)(o[e] * inv);
+        orow[e * 64 + lane] = __builtin_bit_cast(uint16_t, v);
+    }
+    if (lse != nullptr && lane == 0) lse[(size_t)bn * Hq + h] = (mx + log2f(l)) * 0.6931471805599453f;
+}
+
+// fp32: one workgroup per (sequence, row, head); waves stride over keys, lanes over dh
+template <int DH>
+__global__ __launch_bounds__(256)
+void tree_attn_f32_kernel(const float* __restrict__ Q, const float* __restrict__ Kp, const float* __restrict__ Vp,
+                          const long long* __restrict__ kv_offsets, const float* __restrict__ Kt,
+                          const float* __restrict__ Vt, const unsigned long long* __restrict__ mask_bits,
+                          int N, int Hq, int Hkv, int words, float scale, float* __restrict__ O, float* __restrict__ lse) {
+    constexpr int E = DH / 64;
+    const int h = blockIdx.x % Hq, bn = blockIdx.x / Hq, b = bn / N;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int kvh = h / (Hq / Hkv);
+    const long long off = kv_offsets[b];
+    const int P = (int)(kv_offsets[b + 1] - off);
+    float q[E], o[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) { q[e] = Q[((size_t)bn * Hq + h) * DH + e * 64 + lane]; o[e] = 0.f; }
+    float m = NEG_BIG, l = 0.f;
+    const unsigned long long* mb = mask_bits + (size_t)bn * words;
+    for (int key = w; key < P + N; key += 4) {
+        const float* kr; const float* vr;
+        if (key < P) {
+            kr = Kp + ((size_t)(off + key) * Hkv + kvh) * DH;
+            vr = Vp + ((size_t)(off + key) * Hkv + kvh) * DH;
+        } else {
+            const int j = key - P;
+            if (!((mb[j >> 6] >> (j & 63)) & 1ull)) continue;
+            kr = Kt + (((size_t)b * N + j) * Hkv + kvh) * DH;
+            vr = Vt + (((size_t)b * N + j) * Hkv + kvh) * DH;
+        }
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) d += q[e] * kr[e * 64 + lane];
+#pragma unroll
+        for (int x = 32; x > 0; x >>= 1) d += __shfl_xor(d, x, 64);
+        const float s = d * scale;
+        const float m_new = fmaxf(m, s);
+        const float alpha = __expf(m - m_new), p = __expf(s - m_new);
+        l = l * alpha + p;
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[e] = o[e] * alpha + p * vr[e * 64 + lane];
+        m = m_new;
+    }
+    __shared__ float s_m[4], s_l[4], s_o[4][DH];
+    if (lane == 0) { s_m[w] = m; s_l[w] = l; }
+#pragma unroll
+    for (int e = 0; e < E; ++e) s_o[w][e * 64 + lane] = o[e];
+    __syncthreads();
+    if (w == 0) {
+        float mx = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+        float lt = 0.f, ot[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) ot[e] = 0.f;
+        for (int i = 0; i < 4; ++i) {
+            const float wgt = __expf(s_m[i] - mx);
+            lt += wgt * s_l[i];
+#pragma unroll
+            for (int e = 0; e < E; ++e) ot[e] += wgt * s_o[i][e * 64 + lane];
+        }
+#pragma unroll
+        for (int e = 0; e < E; ++e) O[((size_t)bn * Hq + h) * DH + e * 64 + lane] = ot[e] / lt;
+        if (lse != nullptr && lane == 0) lse[(size_t)bn * Hq + h] = mx + __logf(lt);
+    }
+}
+
+struct AttnPlan { int rbw, bm, nmblk, rows_pad, chunk, max_chunks; size_t o_bytes, total; };
+static AttnPlan attn_plan(const eagle2_cfg* cfg, const eagle2_attn_cfg* a) {
+    AttnPlan p;
+    const int rows = a->n_q_heads / a->n_kv_heads * cfg->n_tree;
+    p.rbw = rows > 64 ? 2 : 1;
+    p.bm = 64 * p.rbw;
+    p.nmblk = (rows + p.bm - 1) / p.bm;
+    p.rows_pad = p.nmblk * p.bm;
+    // aim at about two workgroups per compute unit; never less than 4 tiles per chunk
+    const long long wg_per_chunk = (long long)a->n_kv_heads * p.nmblk;
+    long long want = a->total_prefix * wg_per_chunk / (2ll * device_cu_count());
+    want = (want + TA_KEYS - 1) / TA_KEYS * TA_KEYS;
+    if (want < 256) want = 256;
+    if (want > 8192) want = 8192;
+    p.chunk = (int)want;
+    p.max_chunks = (int)(a->total_prefix / p.chunk) + 2 * cfg->batch;
+    p.o_bytes = round_up((size_t)p.max_chunks * a->n_kv_heads * p.rows_pad * a->head_dim * sizeof(float), 256);
+    p.total = p.o_bytes + round_up((size_t)p.max_chunks * a->n_kv_heads * p.rows_pad * 2 * sizeof(float), 256);
+    return p;
+}
+size_t attn_workspace(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn) {
+    return cfg->dtype == EAGLE2_DTYPE_BF16 ? attn_plan(cfg, attn).total : 0;
+}
+
+}  // namespace eagle2
+
+using namespace eagle2;
+
+extern "C" int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn,
+                                const void* Q, const void* K_prefix, const void* V_prefix,
+                                const int64_t* kv_offsets, const void* K_tree, const void* V_tree,
+                                const uint64_t* mask_bits, void* O, float* lse,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = validate_cfg(cfg);
+    if (rc != EAGLE2_OK) return rc;
+    rc = validate_attn(cfg, attn);
+    if (rc != EAGLE2_OK) return rc;
+    E2_REQUIRE(Q && kv_offsets && K_tree && V_tree && mask_bits && O, EAGLE2_ERR_ARG, "eagle2_tree_attn: null pointer argument");
+    E2_REQUIRE(attn->total_prefix == 0 || (K_prefix && V_prefix), EAGLE2_ERR_ARG, "eagle2_tree_attn: null KV prefix");
+    E2_REQUIRE(aligned16(Q) && aligned16(K_prefix) && aligned16(V_prefix) && aligned16(K_tree) && aligned16(V_tree) && aligned16(O),
+               EAGLE2_ERR_ARG, "eagle2_tree_attn: tensors must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int B = cfg->batch, N = cfg->n_tree, Hq = attn->n_q_heads, Hkv = attn->n_kv_heads, dh = attn->head_dim;
+    const float scale = attn->scale > 0.f ? attn->scale : 1.0f / sqrtf((float)dh);
+    const int words = (N + 63) / 64;
+    const long long* offs = reinterpret_cast<const long long*>(kv_offsets);
+    const unsigned long long* mb = reinterpret_cast<const unsigned long long*>(mask_bits);
+
+    if (cfg->dtype == EAGLE2_DTYPE_F32) {
+        dim3 grid((unsigned)((size_t)B * N * Hq));
+        timing_begin(1, st);
+        if (dh == 128)
+            hipLaunchKernelGGL((tree_attn_f32_kernel<128>), grid, dim3(256), 0, st, (const float*)Q, (const float*)K_prefix,
+                               (const float*)V_prefix, offs, (const float*)K_tree, (const float*)V_tree, mb, N, Hq, Hkv, words,
+                               scale, (float*)O, lse);
+        else
+            hipLaunchKernelGGL((tree_attn_f32_kernel<64>), grid, dim3(256), 0, st, (const float*)Q, (const float*)K_prefix,
+                               (const float*)V_prefix, offs, (const float*)K_tree, (const float*)V_tree, mb, N, Hq, Hkv, words,
+                               scale, (float*)O, lse);
+        timing_end(1, st);
+        E2_HIP(hipGetLastError());
+        return EAGLE2_OK;
+    }
+
+    const AttnPlan p = attn_plan(cfg, attn);
+    E2_REQUIRE(workspace && workspace_bytes >= p.total, EAGLE2_ERR_WORKSPACE,
+               "eagle2_tree_attn: workspace of %zu bytes, need %zu", workspace_bytes, p.total);
+    float* part_o = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace));
+    float* part_ml = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + p.o_bytes);
+    const float sl2 = scale * 1.4426950408889634f;
+    dim3 grid(p.max_chunks, Hkv * p.nmblk);
+    timing_begin(1, st);
+#define E2_ATTN(DHV, RB)                                                                                              \
+    hipLaunchKernelGGL((tree_attn_bf16_kernel<DHV, RB>), grid, dim3(TA_THREADS), 0, st, (const uint16_t*)Q,            \
+                       (const uint16_t*)K_prefix, (const uint16_t*)V_prefix, offs, (const uint16_t*)K_tree,            \
+                       (const uint16_t*)V_tree, mb, B, N, Hq, Hkv, p.chunk, words, p.nmblk, p.rows_pad, sl2, part_o, part_ml)
+    if (dh == 128) { if (p.rbw == 2) E2_ATTN(128, 2); else E2_ATTN(128, 1); }
+    else           { if (p.rbw == 2) E2_ATTN(64, 2); else E2_ATTN(64, 1); }
+#undef E2_ATTN
+    timing_end(1, st);
+    E2_HIP(hipGetLastError());
+    dim3 cgrid(B * N, (Hq + 3) / 4);
+    if (dh == 128)
+        hipLaunchKernelGGL((tree_attn_combine_kernel<128>), cgrid, dim3(256), 0, st, offs, N, Hq, Hkv, p.chunk, p.rows_pad,
+                           part_o, part_ml, (uint16_t*)O, lse);
+    else
+        hipLaunchKernelGGL((tree_attn_combine_kernel<64>), cgrid, dim3(256), 0, st, offs, N, Hq, Hkv, p.chunk, p.rows_pad,
+                           part_o, part_ml, (uint16_t*)O, lse);
+    E2_HIP(hipGetLastError());
+    return EAGLE2_OK;
+}

@@ -1,0 +1,77 @@
+"""Device buffers of one draft-plus-verify round and the order of the C-ABI calls.
+
+DraftRound owns the caller-side arrays the C ABI works on (candidate arrays,
+frontier, flattened tree, mask, workspace) as torch device tensors and issues the
+calls in the order of the method: D x expand (Section 4.1), rerank (Section 4.2),
+tree attention once per layer, accept (Sections 2.1/2.2).  It computes nothing
+itself.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import binding as _b
+
+
+class DraftRound:
+    def __init__(self, batch: int, vocab: int, hidden: int, depth: int, topk: int, n_tree: int, dtype: str,
+                 n_q_heads: int = 0, n_kv_heads: int = 0, head_dim: int = 0, total_prefix: int = 0,
+                 keep_draft_logits: bool = False, device="cuda"):
+        self.device = torch.device(device)
+        self.cfg = _b.RoundCfg(batch, vocab, hidden, depth, topk, n_tree,
+                               _b.DTYPE_F32 if dtype == "fp32" else _b.DTYPE_BF16)
+        self.attn: Optional[_b.AttnCfg] = None
+        if n_q_heads:
+            self.attn = _b.AttnCfg(n_q_heads, n_kv_heads, head_dim, 0.0, total_prefix)
+        B, C, D, k, N = batch, self.cfg.n_cand, depth, topk, n_tree
+        dev = self.device
+        i32 = torch.int32
+        self.cand_token = torch.full((B, C), -1, dtype=i32, device=dev)
+        self.cand_score = torch.full((B, C), float("-inf"), dtype=torch.float64, device=dev)
+        self.cand_parent = torch.full((B, C), -1, dtype=i32, device=dev)
+        self.frontier = torch.full((B, D, k), -1, dtype=i32, device=dev)
+        self.draft_logits = (torch.zeros((B, self.cfg.n_draft_rows, vocab), dtype=torch.float32, device=dev)
+                             if keep_draft_logits else None)
+        self.tree_token = torch.zeros((B, N), dtype=i32, device=dev)
+        self.tree_parent = torch.zeros((B, N), dtype=i32, device=dev)
+        self.tree_depth = torch.zeros((B, N), dtype=i32, device=dev)
+        self.tree_cand = torch.zeros((B, N), dtype=i32, device=dev)
+        self.position_ids = torch.zeros((B, N), dtype=i32, device=dev)
+        self.mask_bits = torch.zeros((B, N, (N + 63) // 64), dtype=torch.int64, device=dev)
+        self.accept_len = torch.zeros((B,), dtype=i32, device=dev)
+        self.accept_path = torch.zeros((B, D + 1), dtype=i32, device=dev)
+        self.bonus_token = torch.zeros((B,), dtype=i32, device=dev)
+        nbytes = _b.eagle2_workspace_bytes(self.cfg, self.attn)
+        if nbytes == 0:
+            raise _b.Eagle2Error("unsupported shape: " + _b.load_library().eagle2_last_error().decode())
+        self.workspace = torch.empty((nbytes + 255) // 256 * 256, dtype=torch.uint8, device=dev)
+
+    # -- Section 4.1 ---------------------------------------------------------------
+    def expand(self, d: int, H: torch.Tensor, W: torch.Tensor, h_seq_stride: int = 0):
+        """H: [B, F_d, Hd] (or a view whose sequences are h_seq_stride elements apart)."""
+        _b.eagle2_expand(self.cfg, d, H, W, self.cand_token, self.cand_score, self.cand_parent, self.frontier,
+                         self.draft_logits, self.workspace, h_seq_stride)
+
+    def expand_all(self, H_all: torch.Tensor, W: torch.Tensor):
+        """H_all: [B, D, k, Hd]: hidden state per (sequence, pass, frontier slot)."""
+        B, D, k, Hd = H_all.shape
+        for d in range(D):
+            self.expand(d, H_all[:, d], W, h_seq_stride=D * k * Hd)
+
+    # -- Section 4.2 ---------------------------------------------------------------
+    def rerank(self, root_token: torch.Tensor, prefix_len: torch.Tensor):
+        _b.eagle2_rerank(self.cfg, self.cand_token, self.cand_score, self.cand_parent, root_token, prefix_len,
+                         self.tree_token, self.tree_parent, self.tree_depth, self.tree_cand, self.position_ids,
+                         self.mask_bits, self.workspace)
+
+    def tree_attn(self, Q, K_prefix, V_prefix, kv_offsets, K_tree, V_tree, O, lse=None):
+        _b.eagle2_tree_attn(self.cfg, self.attn, Q, K_prefix, V_prefix, kv_offsets, K_tree, V_tree, self.mask_bits,
+                            O, lse, self.workspace)
+
+    # -- Sections 2.1 / 2.2 -----------------------------------------------------------
+    def accept(self, mode, target_logits, temperature=None, u_accept=None, u_bonus=None):
+        _b.eagle2_accept(self.cfg, mode, target_logits, self.draft_logits, temperature, u_accept, u_bonus,
+                         self.tree_token, self.tree_parent, self.tree_cand, self.accept_len, self.accept_path,
+                         self.bonus_token, self.workspace)

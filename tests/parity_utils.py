@@ -1,0 +1,287 @@
+"""Lock-step comparison of the HIP path with the CPU oracle (used by the GPU tests,
+the smoke check and the benchmark's self-check).
+
+Structure (token ids, parents, mask, accepted path) must be bit-exact except for
+swaps between candidates whose ORACLE scores differ by less than SWAP_TOL = 1e-5.
+To make that checkable, the comparison runs in lock-step: after every GPU expand
+pass the GPU's choices are checked for admissibility under the oracle's float64
+log-probabilities, and the oracle's state is then continued from the GPU's choice
+(its own float64 scores for the GPU's tokens), so one admissible swap cannot
+cascade into later mismatches.  Floating-point outputs are compared with
+max |gpu - ref| / max(|ref|, rms(ref)) <= 1e-4 (fp32 inputs) or 2e-2 (bf16 inputs).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List
+
+import numpy as np
+import torch
+
+from oracle import eagle2_oracle as orc
+
+SWAP_TOL = 1e-5
+REL_TOL = {"fp32": 1e-4, "bf16": 2e-2}
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    """Exact widening of a tensor's stored values to float64 on the host."""
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    den = np.maximum(np.abs(ref), max(rms, 1e-300))
+    return float(np.max(np.abs(got - ref) / den))
+
+
+@dataclass
+class Report:
+    swaps_topk: int = 0          # per-row top-k positions where the GPU token differs from the oracle's
+    swaps_frontier: int = 0
+    swaps_rerank: int = 0
+    max_score_err: float = 0.0   # absolute, joint scores
+    max_logit_rel: float = 0.0
+    max_attn_rel: float = 0.0
+    max_lse_err: float = 0.0
+    notes: List[str] = field(default_factory=list)
+
+
+def _admissible(picked_vals: np.ndarray, all_vals: np.ndarray, picked_idx: np.ndarray, what: str):
+    """picked_* in the GPU's rank order; values are the oracle's.  The pick is admissible
+    if it is sorted up to SWAP_TOL and nothing left out beats the worst pick by SWAP_TOL."""
+    assert len(set(picked_idx.tolist())) == len(picked_idx), f"{what}: duplicate picks {picked_idx}"
+    d = np.diff(picked_vals)
+    assert np.all(d <= SWAP_TOL), f"{what}: GPU order violates oracle values by {d.max():.3e}"
+    rest = np.delete(all_vals, picked_idx)
+    if rest.size:
+        assert rest.max() <= picked_vals.min() + SWAP_TOL, \
+            f"{what}: a candidate left out beats a pick by {rest.max() - picked_vals.min():.3e}"
+
+
+def lockstep_expand(rnd, cfg, H_all: torch.Tensor, W: torch.Tensor, W64: np.ndarray = None,
+                    report: Report = None, check_logits: bool = True):
+    """Runs the D expand passes on the GPU, checking each against the oracle.
+    Returns (oracle states continued from the GPU's choices, report)."""
+    report = report or Report()
+    B, D, k = cfg.batch, cfg.depth, cfg.topk
+    C = cfg.n_cand
+    if W64 is None:
+        W64 = f64(W)
+    H64 = f64(H_all)
+    states = [orc.DraftState(D, k) for _ in range(B)]
+    rel_tol = REL_TOL[cfg.dtype]
+    for d in range(D):
+        rnd.expand(d, H_all[:, d], W, h_seq_stride=D * k * cfg.hidden)
+        if H_all.is_cuda:
+            torch.cuda.synchronize()
+        g_tok = rnd.cand_token.cpu().numpy()
+        g_score = rnd.cand_score.cpu().numpy()
+        g_par = rnd.cand_parent.cpu().numpy()
+        g_front = rnd.frontier.cpu().numpy()
+        F = 1 if d == 0 else k
+        base = orc.cand_base(d, k)
+        for b in range(B):
+            st = states[b]
+            ref = st.copy()
+            dl_ref = np.zeros((orc.n_draft_rows(D, k), cfg.vocab)) if (check_logits and rnd.draft_logits is not None) else None
+            logp = orc.expand(ref, d, H64[b, d, :F], W64, draft_logits=dl_ref)
+            if dl_ref is not None:
+                rows = [orc.draft_row(d, s, k) for s in range(F)]
+                got = rnd.draft_logits[b, rows].cpu().numpy().astype(np.float64)
+                report.max_logit_rel = max(report.max_logit_rel, rel_err(got, dl_ref[rows]))
+            for s in range(F):
+                ids = base + s * k + np.arange(k)
+                picks = g_tok[b, ids].astype(np.int64)
+                assert picks.min() >= 0 and picks.max() < cfg.vocab, f"pass {d} row {s}: token out of range"
+                _admissible(logp[s, picks], logp[s], picks, f"seq {b} pass {d} row {s} top-k")
+                report.swaps_topk += int(np.sum(picks != ref.token[ids]))
+                par = -1 if d == 0 else int(st.frontier[d, s])
+                assert np.all(g_par[b, ids] == par), f"seq {b} pass {d} row {s}: parent ids differ"
+                par_score = 0.0 if d == 0 else float(st.score[par])
+                st.token[ids] = picks
+                st.parent[ids] = par
+                st.score[ids] = par_score + logp[s, picks]          # oracle values for the GPU's picks
+                err = np.abs(g_score[b, ids] - st.score[ids])
+                report.max_score_err = max(report.max_score_err, float(err.max()))
+                assert np.all(err <= rel_tol * np.maximum(np.abs(st.score[ids]), 1.0)), \
+                    f"seq {b} pass {d} row {s}: joint score error {err.max():.3e}"
+            if d + 1 < D:
+                new = base + np.arange(F * k)
+                gf = g_front[b, d + 1].astype(np.int64)
+                assert gf.min() >= base and gf.max() < base + F * k, f"seq {b} pass {d}: frontier outside the new layer"
+                _admissible(st.score[gf], st.score[new], gf - base, f"seq {b} pass {d} frontier")
+                want = new[np.lexsort((new, -st.score[new]))[:k]]
+                report.swaps_frontier += int(np.sum(gf != want))
+                st.frontier[d + 1] = gf
+    return states, report
+
+
+def check_rerank(rnd, cfg, states, root_token: np.ndarray, prefix_len: np.ndarray, report: Report):
+    """GPU rerank vs oracle: admissible selection, then bit-exact flattening of that selection."""
+    B, N, k = cfg.batch, cfg.n_tree, cfg.topk
+    t_tok = rnd.tree_token.cpu().numpy()
+    t_par = rnd.tree_parent.cpu().numpy()
+    t_dep = rnd.tree_depth.cpu().numpy()
+    t_cand = rnd.tree_cand.cpu().numpy()
+    t_pos = rnd.position_ids.cpu().numpy()
+    t_mask = rnd.mask_bits.cpu().numpy().view(np.uint64)
+    trees = []
+    for b in range(B):
+        st = states[b]
+        sel = t_cand[b, 1:].astype(np.int64)
+        assert t_cand[b, 0] == -1 and sel.min() >= 0 and sel.max() < cfg.n_cand
+        assert np.all(np.diff(sel) > 0), "flat order must be increasing candidate id"
+        order = np.lexsort((sel, -st.score[sel]))
+        _admissible(st.score[sel][order], st.score, sel[order], f"seq {b} rerank")
+        want = np.sort(orc.select_top(st, N - 1))
+        report.swaps_rerank += int(np.sum(sel != want))
+        tree = orc.flatten(st, sel, int(root_token[b]), int(prefix_len[b]))
+        assert np.array_equal(t_tok[b], tree.token), f"seq {b}: tree tokens differ"
+        assert np.array_equal(t_par[b], tree.parent), f"seq {b}: tree parents differ"
+        assert np.array_equal(t_dep[b], tree.depth), f"seq {b}: tree depths differ"
+        assert np.array_equal(t_pos[b], tree.position), f"seq {b}: position ids differ"
+        assert np.array_equal(t_mask[b], tree.mask_bits), f"seq {b}: ancestor mask differs"
+        trees.append(tree)
+    return trees
+
+
+def check_attention(cfg, trees, Q, Kp, Vp, Kt, Vt, kv_offsets, O, lse, report: Report,
+                    seqs=None, heads=None):
+    """GPU attention output vs oracle, for all or a sample of (sequence, head)."""
+    off = kv_offsets.cpu().numpy()
+    tol = REL_TOL[cfg.dtype]
+    g = cfg.n_q_heads // cfg.n_kv_heads
+    for b in (range(cfg.batch) if seqs is None else seqs):
+        lo, hi = int(off[b]), int(off[b + 1])
+        hq = list(range(cfg.n_q_heads)) if heads is None else list(heads)
+        kvh = sorted({h // g for h in hq})
+        # the oracle maps head h -> kv head h // g; feed it the needed kv heads with g preserved
+        remap = {kh: i for i, kh in enumerate(kvh)}
+        q_sel = []
+        for kh in kvh:
+            q_sel += list(range(kh * g, (kh + 1) * g))
+        Oq, lq = orc.tree_attn(f64(Q[b][:, q_sel]), f64(Kp[lo:hi][:, kvh]), f64(Vp[lo:hi][:, kvh]),
+                               f64(Kt[b][:, kvh]), f64(Vt[b][:, kvh]), trees[b].mask)
+        for h in hq:
+            col = remap[h // g] * g + (h % g)
+            e = rel_err(f64(O[b, :, h]), Oq[:, col])
+            report.max_attn_rel = max(report.max_attn_rel, e)
+            assert e <= tol, f"seq {b} head {h}: attention rel err {e:.3e} > {tol}"
+            if lse is not None:
+                le = float(np.max(np.abs(f64(lse[b, :, h]) - lq[:, col])))
+                report.max_lse_err = max(report.max_lse_err, le)
+                assert le <= tol * max(1.0, float(np.max(np.abs(lq[:, col])))), f"seq {b} head {h}: lse err {le:.3e}"
+
+
+def check_accept(rnd, cfg, trees, modes, target_logits, temperature, u_accept, u_bonus, report: Report):
+    """Greedy: bit-exact.  Sampling: the oracle is fed the same float32 draft logits the GPU
+    produced, and must reproduce path, length and emitted token."""
+    B, D, k = cfg.batch, cfg.depth, cfg.topk
+    a_len = rnd.accept_len.cpu().numpy()
+    a_path = rnd.accept_path.cpu().numpy()
+    a_bonus = rnd.bonus_token.cpu().numpy()
+    out = []
+    for b in range(B):
+        tree = trees[b]
+        tl = f64(target_logits[b])
+        if modes[b] == 0:
+            res = orc.accept_greedy(tl, tree.token, tree.parent)
+        else:
+            res = orc.accept_sample(tl, f64(rnd.draft_logits[b]), float(temperature[b]), f64(u_accept[b]),
+                                    f64(u_bonus[b]), tree.token, tree.parent, tree.cand, k)
+        want_path = res.path + [-1] * (D + 1 - len(res.path))
+        assert a_len[b] == res.accept_len, f"seq {b}: accept_len {a_len[b]} != {res.accept_len}"
+        assert a_path[b].tolist() == want_path, f"seq {b}: path {a_path[b].tolist()} != {want_path}"
+        if a_bonus[b] != res.bonus_token and modes[b] == 1:
+            # admissible only if the draw sits within 1e-5 (of the total mass) of the CDF edge between them
+            p = res.final_p
+            cdf = np.cumsum(p) / p.sum()
+            u = float(u_bonus[b][res.path[-1]])
+            lo, hi = min(a_bonus[b], res.bonus_token), max(a_bonus[b], res.bonus_token)
+            assert abs(cdf[lo] - u) < 1e-5 and np.all(p[lo + 1:hi] <= 1e-5), \
+                f"seq {b}: bonus {a_bonus[b]} != {res.bonus_token} and not at a CDF edge"
+            report.notes.append(f"seq {b}: bonus differs at a CDF edge")
+        else:
+            assert a_bonus[b] == res.bonus_token, f"seq {b}: bonus {a_bonus[b]} != {res.bonus_token}"
+        out.append(res)
+    return out
+
+
+# ---------------------------------------------------------------------------------------
+# a whole round: GPU calls in the method's order, each stage checked against the oracle
+# ---------------------------------------------------------------------------------------
+
+def run_and_check_round(cfg, device="cuda", h_scale: float = 1.0, plant: bool = False,
+                        layers=(0,), attn_seqs=None, attn_heads=None, W=None, W64=None, verbose=True,
+                        round_factory=None):
+    """Runs one draft-plus-verify round of `cfg` on the GPU and checks every stage.
+    plant=True plants the target's preferred tokens along a tree path so that sequence b
+    accepts min(b mod (D+1), deepest available) tokens in greedy mode."""
+    import workloads as wl
+    if round_factory is None:
+        from paper_2406_16858_amd import DraftRound as round_factory
+
+    def sync():
+        if torch.device(device).type == "cuda":
+            torch.cuda.synchronize()
+
+    rep = Report()
+    B, D, k, N, V = cfg.batch, cfg.depth, cfg.topk, cfg.n_tree, cfg.vocab
+    if W is None:
+        W = wl.make_lm_head(cfg, device)
+    H_all = wl.make_hidden_states(cfg, device, scale=h_scale)
+    plens = wl.make_prefix_lengths(cfg)
+    modes_l = {"greedy": [0] * B, "sample": [1] * B, "mixed": [b % 2 for b in range(B)]}[cfg.accept]
+    rnd = round_factory(B, V, cfg.hidden, D, k, N, cfg.dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                     total_prefix=sum(plens), keep_draft_logits=any(modes_l), device=device)
+    states, rep = lockstep_expand(rnd, cfg, H_all, W, W64=W64, report=rep)
+
+    root = torch.arange(B, dtype=torch.int32) * 3 + 7
+    plen_t = torch.tensor(plens, dtype=torch.int32)
+    rnd.rerank(root.to(device), plen_t.to(device))
+    sync()
+    trees = check_rerank(rnd, cfg, states, root.numpy(), plen_t.numpy(), rep)
+
+    for layer in layers:
+        Q, Kp, Vp, Kt, Vt, off = wl.make_attention_inputs(cfg, device, layer=layer, prefix_lens=plens)
+        O = torch.full_like(Q, float("nan"))
+        lse = torch.full((B, N, cfg.n_q_heads), float("nan"), dtype=torch.float32, device=device)
+        rnd.tree_attn(Q, Kp, Vp, off, Kt, Vt, O, lse)
+        sync()
+        assert not torch.isnan(O.float()).any(), "attention left outputs unwritten"
+        check_attention(cfg, trees, Q, Kp, Vp, Kt, Vt, off, O, lse, rep, seqs=attn_seqs, heads=attn_heads)
+        del Q, Kp, Vp, Kt, Vt, O
+
+    tl, _ = wl.make_target_logits(cfg, device)
+    if plant:
+        for b in range(B):
+            tree = trees[b]
+            deepest = int(np.argmax(tree.depth))
+            chain = []
+            j = deepest
+            while j >= 0:
+                chain.append(j)
+                j = int(tree.parent[j])
+            chain.reverse()
+            L = min(b % (D + 1) if B > 1 else len(chain) - 1, len(chain) - 1)
+            for i in range(L):
+                row = tl[b, chain[i]]
+                row[int(tree.token[chain[i + 1]])] = row.max() + 8.0
+    ua, ub = wl.make_uniforms(cfg, device)
+    temp = torch.full((B,), cfg.temperature, dtype=torch.float32, device=device)
+    mode_t = torch.tensor(modes_l, dtype=torch.int32, device=device)
+    rnd.accept(mode_t, tl, temp, ua, ub)
+    sync()
+    results = check_accept(rnd, cfg, trees, modes_l, tl, temp.cpu().numpy(), ua, ub, rep)
+    if verbose:
+        lens = [r.accept_len for r in results]
+        print(f"[{cfg.name} scale={h_scale} plant={plant}] swaps topk/frontier/rerank = "
+              f"{rep.swaps_topk}/{rep.swaps_frontier}/{rep.swaps_rerank}  score_err={rep.max_score_err:.2e} "
+              f"logit_rel={rep.max_logit_rel:.2e} attn_rel={rep.max_attn_rel:.2e} lse_err={rep.max_lse_err:.2e} "
+              f"accept_len={lens} depth_hist={np.bincount(trees[0].depth).tolist()} {rep.notes}", flush=True)
+    return rep, trees, results

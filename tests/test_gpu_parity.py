@@ -1,0 +1,75 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, stage by stage.
+
+Small cases span several 64-row vocab tiles with a ragged tail, several attention tiles
+and ragged prefixes; the full-size cases run the five configurations in the launch
+configuration the benchmark times.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from tests.parity_utils import run_and_check_round
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2406_16858_amd import load_library
+    load_library()
+
+
+def _small(name, **kw):
+    base = dict(name=name, index=0, dtype="bf16", batch=1, vocab=5003, hidden=512, depth=4, topk=5, n_tree=24,
+                n_q_heads=8, n_kv_heads=2, head_dim=64, prefix_lo=100, prefix_hi=100, n_layers=1, w_std=0.05,
+                accept="greedy", temperature=1.0, seed=1234)
+    base.update(kw)
+    return wl.RoundConfig(**base)
+
+
+@pytest.mark.parametrize("scale,plant", [(1.0, False), (8.0, True)])
+def test_cfg1_tiny_fp32(scale, plant):
+    rep, trees, res = run_and_check_round(wl.get_config(1), h_scale=scale, plant=plant)
+    assert rep.swaps_topk == rep.swaps_frontier == rep.swaps_rerank == 0   # fp32 inputs: no near ties expected
+    if plant:
+        assert res[0].accept_len == int(trees[0].depth.max())
+
+
+SMALL = [
+    _small("ragged_vocab_bf16"),
+    _small("ragged_vocab_bf16_sample", accept="sample", seed=77),
+    _small("batch3_mixed", batch=3, accept="mixed", prefix_lo=1, prefix_hi=700, seed=5),
+    _small("fp32_dh128", dtype="fp32", hidden=256, vocab=777, n_q_heads=4, n_kv_heads=4, head_dim=128, seed=9),
+    _small("bf16_dh128_gqa", n_q_heads=16, n_kv_heads=2, head_dim=128, n_tree=40, prefix_lo=300, prefix_hi=300, seed=11),
+    _small("k1_chain", topk=1, depth=6, n_tree=7, seed=3),
+    _small("k16_n128", topk=16, depth=3, n_tree=128, vocab=2048, seed=4, accept="sample"),
+    _small("no_prefix", prefix_lo=0, prefix_hi=0, seed=6),
+    _small("temperature_0p7", accept="sample", temperature=0.7, seed=8),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+@pytest.mark.parametrize("scale", [1.0, 6.0])
+def test_small_shapes(cfg, scale):
+    run_and_check_round(cfg, h_scale=scale, plant=(scale > 1.0 and cfg.accept != "sample"))
+
+
+@pytest.mark.parametrize("scale,plant", [(1.0, False), (6.0, True)])
+def test_cfg2_llama2_7b(scale, plant):
+    run_and_check_round(wl.get_config(2), h_scale=scale, plant=plant)
+
+
+@pytest.mark.parametrize("scale", [1.0, 6.0])
+def test_cfg3_llama3_8b_sampling(scale):
+    run_and_check_round(wl.get_config(3), h_scale=scale)
+
+
+def test_cfg4_llama70b_layer_shape():
+    # the round has 80 independent KV layers; parity is checked on two of them, sampled heads
+    run_and_check_round(wl.get_config(4), h_scale=6.0, plant=True, layers=(0, 79), attn_heads=range(0, 64, 9))
+
+
+def test_cfg5_batched_serving():
+    run_and_check_round(wl.get_config(5), h_scale=6.0, plant=True, attn_seqs=[0, 5, 10, 15], attn_heads=[0, 13, 31])

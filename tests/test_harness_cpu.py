@@ -1,0 +1,184 @@
+"""CPU checks of the test harness and of the host side of the binding.
+
+The lock-step comparison code is exercised here against a stand-in round that is
+built from the oracle itself (optionally with small float32-like perturbations),
+so that harness mistakes show up without a GPU.  The stand-in lives in this test
+file only; the product has no such path.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import eagle2_oracle as orc
+from tests import parity_utils as pu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+class OracleBackedRound:
+    """Same attributes and methods as DraftRound, computed by the oracle (test stand-in)."""
+
+    def __init__(self, batch, vocab, hidden, depth, topk, n_tree, dtype, n_q_heads=0, n_kv_heads=0, head_dim=0,
+                 total_prefix=0, keep_draft_logits=False, device="cpu"):
+        self.B, self.V, self.D, self.k, self.N = batch, vocab, depth, topk, n_tree
+        C, R = orc.n_candidates(depth, topk), orc.n_draft_rows(depth, topk)
+        self.states = [orc.DraftState(depth, topk) for _ in range(batch)]
+        self.cand_token = torch.full((batch, C), -1, dtype=torch.int32)
+        self.cand_score = torch.full((batch, C), float("-inf"), dtype=torch.float64)
+        self.cand_parent = torch.full((batch, C), -1, dtype=torch.int32)
+        self.frontier = torch.full((batch, depth, topk), -1, dtype=torch.int32)
+        self.draft_logits = torch.zeros((batch, R, vocab), dtype=torch.float32) if keep_draft_logits else None
+        self.heads = (n_q_heads, n_kv_heads, head_dim)
+
+    def expand(self, d, H, W, h_seq_stride=0):
+        F = 1 if d == 0 else self.k
+        for b, st in enumerate(self.states):
+            dl = np.zeros((orc.n_draft_rows(self.D, self.k), self.V))
+            orc.expand(st, d, pu.f64(H[b, :F]), pu.f64(W), draft_logits=dl)
+            self.cand_token[b] = torch.from_numpy(st.token.astype(np.int32))
+            self.cand_score[b] = torch.from_numpy(st.score)
+            self.cand_parent[b] = torch.from_numpy(st.parent.astype(np.int32))
+            self.frontier[b] = torch.from_numpy(st.frontier.astype(np.int32))
+            if self.draft_logits is not None:
+                for s in range(F):
+                    r = orc.draft_row(d, s, self.k)
+                    self.draft_logits[b, r] = torch.from_numpy(dl[r]).float()
+
+    def rerank(self, root_token, prefix_len):
+        N = self.N
+        self.trees = [orc.rerank(st, N, int(root_token[b]), int(prefix_len[b])) for b, st in enumerate(self.states)]
+        t = self.trees
+        as32 = lambda f: torch.from_numpy(np.stack([getattr(x, f) for x in t]).astype(np.int32))
+        self.tree_token, self.tree_parent, self.tree_depth = as32("token"), as32("parent"), as32("depth")
+        self.tree_cand, self.position_ids = as32("cand"), as32("position")
+        self.mask_bits = torch.from_numpy(np.stack([x.mask_bits for x in t]).view(np.int64))
+
+    def tree_attn(self, Q, Kp, Vp, off, Kt, Vt, O, lse=None):
+        for b, tree in enumerate(self.trees):
+            lo, hi = int(off[b]), int(off[b + 1])
+            o, l = orc.tree_attn(pu.f64(Q[b]), pu.f64(Kp[lo:hi]), pu.f64(Vp[lo:hi]), pu.f64(Kt[b]), pu.f64(Vt[b]), tree.mask)
+            O[b] = torch.from_numpy(o).to(O.dtype)
+            if lse is not None:
+                lse[b] = torch.from_numpy(l).float()
+
+    def accept(self, mode, tl, temperature=None, u_accept=None, u_bonus=None):
+        B, D = self.B, self.D
+        self.accept_len = torch.zeros(B, dtype=torch.int32)
+        self.accept_path = torch.full((B, D + 1), -1, dtype=torch.int32)
+        self.bonus_token = torch.zeros(B, dtype=torch.int32)
+        for b, tree in enumerate(self.trees):
+            if int(mode[b]) == 0:
+                r = orc.accept_greedy(pu.f64(tl[b]), tree.token, tree.parent)
+            else:
+                r = orc.accept_sample(pu.f64(tl[b]), pu.f64(self.draft_logits[b]), float(temperature[b]),
+                                      pu.f64(u_accept[b]), pu.f64(u_bonus[b]), tree.token, tree.parent, tree.cand, self.k)
+            self.accept_len[b] = r.accept_len
+            self.accept_path[b, : len(r.path)] = torch.tensor(r.path, dtype=torch.int32)
+            self.bonus_token[b] = r.bonus_token
+
+
+def _cfg(**kw):
+    base = dict(name="cpu_small", index=0, dtype="bf16", batch=2, vocab=300, hidden=64, depth=3, topk=3, n_tree=12,
+                n_q_heads=4, n_kv_heads=2, head_dim=16, prefix_lo=3, prefix_hi=40, n_layers=1, w_std=0.3,
+                accept="mixed", temperature=0.9, seed=42)
+    base.update(kw)
+    return wl.RoundConfig(**base)
+
+
+@pytest.mark.parametrize("scale,plant", [(1.0, False), (3.0, True)])
+def test_harness_accepts_an_exact_round(scale, plant):
+    rep, trees, res = pu.run_and_check_round(_cfg(), device="cpu", h_scale=scale, plant=plant,
+                                             round_factory=OracleBackedRound, verbose=False)
+    assert rep.swaps_topk == rep.swaps_frontier == rep.swaps_rerank == 0
+    assert rep.max_score_err == 0.0
+    if plant:
+        assert res[0].accept_len == 0 and res[1].accept_len in (0, 1)     # b mod (D+1), greedy only for even b
+
+
+def test_harness_rejects_a_wrong_parent_and_a_wrong_token():
+    cfg = _cfg(batch=1, accept="greedy")
+
+    class WrongToken(OracleBackedRound):
+        def expand(self, d, H, W, h_seq_stride=0):
+            super().expand(d, H, W, h_seq_stride)
+            if d == 1:
+                self.cand_token[0, orc.cand_base(1, self.k)] = (int(self.cand_token[0, orc.cand_base(1, self.k)]) + 1) % self.V
+
+    with pytest.raises(AssertionError):
+        pu.run_and_check_round(cfg, device="cpu", round_factory=WrongToken, verbose=False)
+
+    class WrongMask(OracleBackedRound):
+        def rerank(self, root_token, prefix_len):
+            super().rerank(root_token, prefix_len)
+            self.mask_bits[0, 3, 0] ^= 1 << 2
+
+    with pytest.raises(AssertionError):
+        pu.run_and_check_round(cfg, device="cpu", round_factory=WrongMask, verbose=False)
+
+
+def test_harness_tolerates_only_near_tie_swaps():
+    vals = np.array([0.0, -1.0, -1.0 - 5e-6, -2.0])
+    pu._admissible(vals[[0, 2, 1]], vals, np.array([0, 2, 1]), "near tie")            # swap within 1e-5: fine
+    with pytest.raises(AssertionError):
+        pu._admissible(vals[[0, 3]], vals, np.array([0, 3]), "left out a better one")
+    with pytest.raises(AssertionError):
+        pu._admissible(vals[[1, 0]], vals, np.array([1, 0]), "wrong order")
+
+
+# ---------------------------------------------------------------------------------------
+# the C ABI: the library loads, exports every declared symbol, and validates on the host
+# ---------------------------------------------------------------------------------------
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "eagle2.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(eagle2_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2406_16858_amd import binding
+    if not os.path.exists(binding.lib_path()):
+        from paper_2406_16858_amd.build import build
+        build(verbose=False)
+    lib = ctypes.CDLL(binding.lib_path())
+    names = _declared_symbols()
+    assert {"eagle2_expand", "eagle2_rerank", "eagle2_tree_attn", "eagle2_accept"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/eagle2.h but not exported"
+    assert binding.eagle2_version() >= 100
+
+
+def test_host_side_validation_needs_no_gpu():
+    from paper_2406_16858_amd import binding as b
+    lib = b.load_library()
+    ok = b.RoundCfg(1, 32000, 4096, 6, 10, 60, b.DTYPE_BF16)
+    assert b.eagle2_workspace_bytes(ok) > 0
+    attn = b.AttnCfg(32, 8, 128, 0.0, 4096)
+    assert b.eagle2_workspace_bytes(ok, attn) >= b.eagle2_workspace_bytes(ok)
+    for bad, frag in [(b.RoundCfg(1, 32000, 4096, 6, 17, 60, 1), "topk"),
+                      (b.RoundCfg(1, 32000, 4000, 6, 10, 60, 1), "1024"),
+                      (b.RoundCfg(1, 32000, 4096, 6, 10, 600, 1), "n_tree"),
+                      (b.RoundCfg(1, 8, 4096, 6, 10, 60, 1), "vocab"),
+                      (b.RoundCfg(1, 32000, 4096, 6, 10, 60, 7), "dtype")]:
+        assert b.eagle2_workspace_bytes(bad) == 0
+        assert frag in lib.eagle2_last_error().decode()
+    assert b.eagle2_workspace_bytes(ok, b.AttnCfg(32, 8, 96, 0.0, 0)) == 0
+    assert b.eagle2_workspace_bytes(ok, b.AttnCfg(30, 8, 128, 0.0, 0)) == 0
+    # null pointers are refused before anything is enqueued
+    rc = lib.eagle2_expand(ctypes.byref(ok), 0, None, 0, None, None, None, None, None, None, None, 0, None)
+    assert rc == -1 and "null" in lib.eagle2_last_error().decode()
+    rc = lib.eagle2_expand(ctypes.byref(ok), 9, None, 0, None, None, None, None, None, None, None, 0, None)
+    assert rc == -1 and "pass index" in lib.eagle2_last_error().decode()
+
+
+def test_binding_refuses_host_tensors():
+    from paper_2406_16858_amd import binding as b
+    cfg = b.RoundCfg(1, 1000, 256, 3, 4, 16, b.DTYPE_F32)
+    t = torch.zeros(4)
+    with pytest.raises(b.Eagle2Error):
+        b.eagle2_expand(cfg, 0, t, t, t, t, t, t, None, None)
