@@ -143,7 +143,7 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(
-                            __builtin_bit_cast(float, wf[e]), __builtin_bit_cast(float, hf[t][e]), acc[nb], 0, 0, 0);
+                            __uint_as_float(wf[e]), __uint_as_float(hf[t][e]), acc[nb], 0, 0, 0);
                 }
             }
         }

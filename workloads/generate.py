@@ -36,6 +36,8 @@ class SeededStream:
         so that the fp32 staging buffer stays small for multi-GB tensors."""
         shape = tuple(int(s) for s in shape)
         out = torch.empty(shape, dtype=dtype, device=self.device)
+        if out.numel() == 0:
+            return out
         flat = out.view(shape[0], -1) if len(shape) > 1 else out.view(-1, 1)
         for r0 in range(0, flat.shape[0], chunk_rows):
             r1 = min(flat.shape[0], r0 + chunk_rows)
