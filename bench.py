@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark: draft-tree rounds per second at the LLaMA3-8B shape on one MI355X.
+
+A step is one whole draft-plus-verify round of the hot path on seeded synthetic
+inputs that are already resident in HBM: D x eagle2_expand, eagle2_rerank,
+eagle2_tree_attn (one layer), eagle2_accept.  Prints ONE JSON line with the
+throughput, the HBM roofline of the dominant kernel (the LM-head stream, timed
+with HIP events on the launch stream) and the CPU oracle's speed on the same
+round as a reported baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM traffic per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None until a counter run for this workload has been recorded.
+MEASURED_TRAFFIC_BYTES = {3: None}
+
+
+def algorithmic_bytes(cfg, plens):
+    """LM head: one pass streams W once (H and the partials are negligible).  Attention, per
+    layer: K and V of prefix + tree once, Q read and O written once."""
+    el = 4 if cfg.dtype == "fp32" else 2
+    lm = cfg.vocab * cfg.hidden * el
+    attn = sum(2 * (P + cfg.n_tree) * cfg.n_kv_heads * cfg.head_dim * el
+               + 2 * cfg.n_tree * cfg.n_q_heads * cfg.head_dim * el for P in plens)
+    return lm, attn
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures the one-GPU hot path only; --gpus must be 1 "
+              "(no collectives or sharding exist in this repository).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    from paper_2406_16858_amd import DraftRound, eagle2_kernel_timing_enable, eagle2_kernel_timing_read
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    cfg = wl.get_config(args.config)
+    B, D, k, N, V = cfg.batch, cfg.depth, cfg.topk, cfg.n_tree, cfg.vocab
+
+    # ---- inputs, resident in HBM -------------------------------------------------
+    W = wl.make_lm_head(cfg, dev)
+    H_all = wl.make_hidden_states(cfg, dev)
+    plens = wl.make_prefix_lengths(cfg)
+    modes_l = {"greedy": [0] * B, "sample": [1] * B, "mixed": [b % 2 for b in range(B)]}[cfg.accept]
+    rnd = DraftRound(B, V, cfg.hidden, D, k, N, cfg.dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                     total_prefix=sum(plens), keep_draft_logits=any(modes_l), device=dev)
+    layers = [wl.make_attention_inputs(cfg, dev, layer=l, prefix_lens=plens) for l in range(cfg.n_layers)]
+    O = torch.empty_like(layers[0][0])
+    tl, _ = wl.make_target_logits(cfg, dev)
+    ua, ub = wl.make_uniforms(cfg, dev)
+    temp = torch.full((B,), cfg.temperature, dtype=torch.float32, device=dev)
+    mode_t = torch.tensor(modes_l, dtype=torch.int32, device=dev)
+    root = (torch.arange(B, dtype=torch.int32) * 3 + 7).to(dev)
+    plen_t = torch.tensor(plens, dtype=torch.int32, device=dev)
+
+    def one_round():
+        rnd.expand_all(H_all, W)
+        rnd.rerank(root, plen_t)
+        for (Q, Kp, Vp, Kt, Vt, off) in layers:
+            rnd.tree_attn(Q, Kp, Vp, off, Kt, Vt, O, None)
+        rnd.accept(mode_t, tl, temp, ua, ub)
+
+    for _ in range(args.warmup):
+        one_round()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_round()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    rounds_per_s = B * 1e3 / ms_per_step
+
+    # ---- dominant kernel: LM-head stream, HIP events on the launch stream --------
+    eagle2_kernel_timing_enable(True)
+    reps = max(3, min(10, args.steps))
+    for _ in range(reps):
+        one_round()
+    torch.cuda.synchronize()
+    lm_ms, lm_n = eagle2_kernel_timing_read(0)
+    at_ms, at_n = eagle2_kernel_timing_read(1)
+    eagle2_kernel_timing_enable(False)
+    lm_bytes, attn_bytes = algorithmic_bytes(cfg, plens)
+    lm_avg_ms = lm_ms / max(lm_n, 1)
+    achieved = lm_bytes / (lm_avg_ms * 1e-3) / 1e9
+    round_bytes = D * lm_bytes + cfg.n_layers * attn_bytes
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index),
+                "kernel": "lmhead_kernel", "bytes_per_launch": lm_bytes, "avg_launch_ms": round(lm_avg_ms, 5),
+                "launches_timed": lm_n}
+    extra = {"round_algorithmic_bytes": round_bytes,
+             "round_hbm_roofline_frac": round(round_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
+             "attn_kernel_avg_ms": round(at_ms / max(at_n, 1), 5)}
+
+    # ---- the oracle on the host cores, same round, bounded sample ------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import eagle2_oracle as orc
+        from tests.parity_utils import f64
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        W_h, H_h = W.float().cpu().numpy(), f64(H_all)
+        Q, Kp, Vp, Kt, Vt, off = [t.float().cpu().numpy() if t.dtype != torch.int64 else t.cpu().numpy() for t in layers[0]]
+        tl_h = tl[0].cpu().numpy()
+        ua_h, ub_h = ua[0].cpu().numpy(), ub[0].cpu().numpy()
+        c0 = time.perf_counter()
+        st = orc.DraftState(D, k)
+        dl = np.zeros((orc.n_draft_rows(D, k), V))
+        for d in range(D):
+            orc.expand(st, d, H_h[0, d, : (1 if d == 0 else k)], W_h, draft_logits=dl)
+        tree = orc.rerank(st, N, 7, plens[0])
+        orc.tree_attn(Q[0], Kp[: plens[0]], Vp[: plens[0]], Kt[0], Vt[0], tree.mask)
+        if modes_l[0] == 0:
+            orc.accept_greedy(tl_h, tree.token, tree.parent)
+        else:
+            orc.accept_sample(tl_h, dl, cfg.temperature, ua_h, ub_h, tree.token, tree.parent, tree.cand, k)
+        c1 = time.perf_counter()
+        cpu = {"value": round(1.0 / (c1 - c0), 5), "unit": "rounds/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"one full round of sequence 0 of {cfg.name} (all {D} passes, 1 attention layer, accept), "
+                         f"{c1 - c0:.1f} s of host time"}
+
+    out = {"metric": "draft_tree_rounds_per_sec_llama3_8b_shape" if cfg.index == 3 else f"draft_tree_rounds_per_sec_{cfg.name}",
+           "value": round(rounds_per_s, 2), "unit": "rounds/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+           "config": {"workload": f"cfg{cfg.index} {cfg.name}: V={V} Hd={cfg.hidden} D={D} k={k} N={N} B={B} "
+                                  f"Hq/Hkv={cfg.n_q_heads}/{cfg.n_kv_heads} dh={cfg.head_dim} P={cfg.prefix_lo}"
+                                  f"{'' if cfg.prefix_lo == cfg.prefix_hi else '..' + str(cfg.prefix_hi)} "
+                                  f"layers={cfg.n_layers} accept={cfg.accept}",
+                      "global_batch": B, "round": "6x expand + rerank + tree_attn + accept"},
+           "roofline": roofline, "cpu_baseline": cpu, **extra}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

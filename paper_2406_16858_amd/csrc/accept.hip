@@ -17,7 +17,8 @@
 namespace eagle2 {
 
 constexpr int AM_THREADS = 256;
-constexpr int SAMPLE_WGS = 32;           // most workgroups that cooperate on one sampling sequence
+constexpr int SAMPLE_WGS = 128;          // most workgroups that cooperate on one sampling sequence
+constexpr int SAMPLE_MAXE = 8;           // vocabulary entries a thread can keep in registers
 constexpr int SAMPLE_THREADS = 256;
 constexpr int SAMPLE_NPART = 4;          // doubles exchanged per workgroup per pass
 constexpr unsigned SPIN_LIMIT = 1u << 22;
@@ -192,7 +193,10 @@ __device__ __forceinline__ void element_state(const NodeScalars& ns, int v, floa
     }
 }
 
-// grid (SAMPLE_WGS, B)
+// grid (nwg, B).  CACHED: every thread owns at most SAMPLE_MAXE consecutive vocabulary
+// entries and keeps their current (p_j, q_j) in registers from pass to pass; otherwise the
+// state is rebuilt from the logits and the recorded scalars in every pass.
+template <bool CACHED>
 __global__ __launch_bounds__(SAMPLE_THREADS)
 void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int* __restrict__ mode,
                           const float* __restrict__ target_logits, const float* __restrict__ draft_logits,
@@ -208,6 +212,7 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
     __shared__ double s_red[SAMPLE_THREADS / 64];
     __shared__ double s_scan[SAMPLE_THREADS];
     __shared__ int s_kids[EAGLE2_MAX_TREE];
+    __shared__ int s_last[SAMPLE_THREADS / 64];
     __shared__ int s_nkids, s_ok, s_decision, s_cand;
 
     SampleCtx cx;
@@ -226,16 +231,19 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
     int* path = accept_path + (size_t)b * (D + 1);
     float T = temperature[b];
     if (!(T > 0.f)) T = 1.f;
+    const double inv_t = 1.0 / (double)T;
 
-    // this workgroup's slice of the vocabulary (contiguous, so prefix sums compose)
+    // this workgroup's slice of the vocabulary and this thread's chunk of it (both contiguous,
+    // so prefix sums compose)
     const int per_wg = (V + nwg - 1) / nwg;
     const int v_lo = min(V, wg * per_wg), v_hi = min(V, v_lo + per_wg);
     const int per_th = (v_hi - v_lo + SAMPLE_THREADS - 1) / SAMPLE_THREADS;
     const int t_lo = min(v_hi, v_lo + tid * per_th), t_hi = min(v_hi, t_lo + per_th);
 
+    double pe[CACHED ? SAMPLE_MAXE : 1], qe[CACHED ? SAMPLE_MAXE : 1];
+
     int cur = 0, len = 0;
-    bool failed = false;
-    for (int guard = 0; guard <= N && !failed; ++guard) {
+    for (int guard = 0; guard <= N; ++guard) {
         // children of cur in flat order and the draft row they were taken from
         if (tid == 0) {
             int nk = 0;
@@ -251,9 +259,8 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
             if (drow < 0 || drow >= R) drow = 0;
         }
         const float* zt_row = target_logits + ((size_t)b * N + cur) * (size_t)V;
-        const float* zd_row = draft_logits != nullptr ? draft_logits + ((size_t)b * R + drow) * (size_t)V : nullptr;
-        const bool has_q = nkids > 0 && zd_row != nullptr;
-        const double inv_t = 1.0 / (double)T;
+        const float* zd_row = draft_logits + ((size_t)b * R + drow) * (size_t)V;
+        const bool has_q = nkids > 0;
 
         // pass A: (max, sum-exp) of both rows, merged across workgroups
         double mt = -INFINITY, md = -INFINITY;
@@ -272,7 +279,7 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
         sd = block_sum(sd, s_red);
         {
             const double mine[SAMPLE_NPART] = {mt, st, md, sd};
-            if (!exchange(cx, mine, s_all, &s_ok)) { failed = true; break; }
+            if (!exchange(cx, mine, s_all, &s_ok)) break;
         }
         if (tid == 0) {
             double gmt = -INFINITY, gmd = -INFINITY;
@@ -287,74 +294,109 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
             ns.nrej = 0;
         }
         __syncthreads();
+        if constexpr (CACHED) {
+#pragma unroll
+            for (int e = 0; e < SAMPLE_MAXE; ++e) {
+                const int v = t_lo + e;
+                if (v < t_hi) element_state(ns, v, zt_row[v], has_q ? zd_row[v] : 0.f, pe[e], qe[e]);
+                else { pe[e] = 0.0; qe[e] = 0.0; }
+            }
+        }
 
-        bool moved = false;
-        if (has_q) {
-            for (int ci = 0; ci < nkids && ci < EAGLE2_MAX_TOPK + 1; ++ci) {
-                const int c = s_kids[ci];
-                const int x = tok[c];
-                if (tid == 0) {
-                    int dec = 0;
-                    if (x >= 0 && x < V) {
-                        double p, q;
-                        element_state(ns, x, zt_row[x], zd_row[x], p, q);
-                        dec = ((double)ua[c] < p / q) ? 1 : 0;
-                    }
-                    s_decision = dec;
+        bool moved = false, failed = false;
+        for (int ci = 0; has_q && ci < nkids && ci < EAGLE2_MAX_TOPK + 1; ++ci) {
+            const int c = s_kids[ci];
+            const int x = tok[c];
+            if (tid == 0) {
+                int dec = 0;
+                if (x >= 0 && x < V) {
+                    double p, q;
+                    element_state(ns, x, zt_row[x], zd_row[x], p, q);
+                    dec = ((double)ua[c] < p / q) ? 1 : 0;
                 }
-                __syncthreads();
-                if (s_decision) { cur = c; ++len; moved = true; if (wg == 0 && tid == 0 && len <= D) path[len] = c; break; }
-                // rejected: residual mass and remaining draft mass
-                double tot = 0.0, qs = 0.0;
+                s_decision = dec;
+            }
+            __syncthreads();
+            if (s_decision) { cur = c; ++len; moved = true; if (wg == 0 && tid == 0 && len <= D) path[len] = c; break; }
+            // rejected: residual mass and remaining draft mass
+            double tot = 0.0, qs = 0.0;
+            if constexpr (CACHED) {
+#pragma unroll
+                for (int e = 0; e < SAMPLE_MAXE; ++e) {
+                    tot += fmax(pe[e] - qe[e], 0.0);
+                    if (t_lo + e != x) qs += qe[e];
+                }
+            } else {
                 for (int v = t_lo; v < t_hi; ++v) {
                     double p, q;
                     element_state(ns, v, zt_row[v], zd_row[v], p, q);
                     tot += fmax(p - q, 0.0);
                     if (v != x) qs += q;
                 }
-                tot = block_sum(tot, s_red);
-                qs = block_sum(qs, s_red);
-                {
-                    const double mine[SAMPLE_NPART] = {tot, qs, 0.0, 0.0};
-                    if (!exchange(cx, mine, s_all, &s_ok)) { failed = true; break; }
-                }
-                if (tid == 0) {
-                    double gt = 0.0, gq = 0.0;
-                    for (int g = 0; g < nwg; ++g) { gt += s_all[g * SAMPLE_NPART]; gq += s_all[g * SAMPLE_NPART + 1]; }
-                    const int j = ns.nrej;
-                    ns.rej_tok[j] = x; ns.rej_tot[j] = gt; ns.rej_qs[j] = gq;
-                    ns.nrej = j + 1;
-                }
-                __syncthreads();
             }
-            if (failed) break;
+            tot = block_sum(tot, s_red);
+            qs = block_sum(qs, s_red);
+            {
+                const double mine[SAMPLE_NPART] = {tot, qs, 0.0, 0.0};
+                if (!exchange(cx, mine, s_all, &s_ok)) { failed = true; break; }
+            }
+            double gt = 0.0, gq = 0.0;
+            for (int g = 0; g < nwg; ++g) { gt += s_all[g * SAMPLE_NPART]; gq += s_all[g * SAMPLE_NPART + 1]; }
+            if (tid == 0) {
+                const int j = ns.nrej;
+                ns.rej_tok[j] = x; ns.rej_tot[j] = gt; ns.rej_qs[j] = gq;
+                ns.nrej = j + 1;
+            }
+            if constexpr (CACHED) {
+#pragma unroll
+                for (int e = 0; e < SAMPLE_MAXE; ++e) {
+                    const double r = fmax(pe[e] - qe[e], 0.0);
+                    if (gt > 0.0) pe[e] = r / gt;
+                    if (t_lo + e == x) qe[e] = 0.0;
+                    if (gq > 0.0) qe[e] = qe[e] / gq;
+                }
+            }
+            __syncthreads();
         }
+        if (failed) break;
         if (moved) continue;
 
         // no child accepted: draw the emitted token from the current p by inverse CDF
         double loc = 0.0;
         int last_pos = -1;
-        for (int v = t_lo; v < t_hi; ++v) {
-            double p, q;
-            element_state(ns, v, zt_row[v], has_q ? zd_row[v] : 0.f, p, q);
-            loc += p;
-            if (p > 0.0) last_pos = v;
+        if constexpr (CACHED) {
+#pragma unroll
+            for (int e = 0; e < SAMPLE_MAXE; ++e) { loc += pe[e]; if (pe[e] > 0.0) last_pos = t_lo + e; }
+        } else {
+            for (int v = t_lo; v < t_hi; ++v) {
+                double p, q;
+                element_state(ns, v, zt_row[v], has_q ? zd_row[v] : 0.f, p, q);
+                loc += p;
+                if (p > 0.0) last_pos = v;
+            }
         }
         s_scan[tid] = loc;
         const double wg_sum = block_sum(loc, s_red);
         {
             const double mine[SAMPLE_NPART] = {wg_sum, 0.0, 0.0, 0.0};
-            if (!exchange(cx, mine, s_all, &s_ok)) { failed = true; break; }
+            if (!exchange(cx, mine, s_all, &s_ok)) break;
         }
         double total = 0.0, before = 0.0;
         for (int g = 0; g < nwg; ++g) { if (g == wg) before = total; total += s_all[g * SAMPLE_NPART]; }
         const double goal = (double)ub[cur] * total;
         if (tid == 0) s_cand = INT_MAX;
         __syncthreads();
-        double th_before = before;
-        for (int t = 0; t < tid; ++t) th_before += s_scan[t];
-        {   // every thread scans its chunk; the smallest crossing index wins
-            double c = th_before;
+        double c = before;
+        for (int t = 0; t < tid; ++t) c += s_scan[t];
+        // every thread scans its chunk; the smallest index whose running sum passes the goal wins
+        if constexpr (CACHED) {
+            bool hit = false;
+#pragma unroll
+            for (int e = 0; e < SAMPLE_MAXE; ++e) {
+                c += pe[e];
+                if (!hit && t_lo + e < t_hi && c > goal) { atomicMin(&s_cand, t_lo + e); hit = true; }
+            }
+        } else {
             for (int v = t_lo; v < t_hi; ++v) {
                 double p, q;
                 element_state(ns, v, zt_row[v], has_q ? zd_row[v] : 0.f, p, q);
@@ -365,17 +407,13 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
         // last token with positive mass, for the (measure-zero) case of no crossing
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) last_pos = max(last_pos, __shfl_xor(last_pos, o, 64));
+        if ((tid & 63) == 0) s_last[tid >> 6] = last_pos;
         __syncthreads();
         {
-            const double mine[SAMPLE_NPART] = {(double)s_cand, (double)last_pos, 0.0, 0.0};
-            // last_pos is per wave here; fold the other waves in through LDS first
-            __shared__ int s_last[SAMPLE_THREADS / 64];
-            if ((tid & 63) == 0) s_last[tid >> 6] = last_pos;
-            __syncthreads();
             int lp = -1;
             for (int w2 = 0; w2 < SAMPLE_THREADS / 64; ++w2) lp = max(lp, s_last[w2]);
-            const double mine2[SAMPLE_NPART] = {mine[0], (double)lp, 0.0, 0.0};
-            if (!exchange(cx, mine2, s_all, &s_ok)) { failed = true; break; }
+            const double mine[SAMPLE_NPART] = {(double)s_cand, (double)lp, 0.0, 0.0};
+            if (!exchange(cx, mine, s_all, &s_ok)) break;
         }
         if (wg == 0 && tid == 0) {
             double best = (double)INT_MAX, lastp = -1.0;
@@ -430,10 +468,18 @@ extern "C" int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
         // all workgroups of a sequence wait for each other, so they must be resident together
         int nwg = 2 * device_cu_count() / B;
         nwg = nwg > SAMPLE_WGS ? SAMPLE_WGS : (nwg < 1 ? 1 : nwg);
-        hipLaunchKernelGGL(sample_accept_kernel, dim3(nwg, B), dim3(SAMPLE_THREADS), 0, st,
-                           nwg, V, N, D, cfg->topk, n_draft_rows(cfg), mode, target_logits, draft_logits, temperature,
-                           u_accept, u_bonus, tree_token, tree_parent, tree_cand, bars, parts,
-                           accept_len, accept_path, bonus_token);
+        const int per_wg = (V + nwg - 1) / nwg;
+        const bool cached = (per_wg + SAMPLE_THREADS - 1) / SAMPLE_THREADS <= SAMPLE_MAXE;
+        if (cached)
+            hipLaunchKernelGGL(sample_accept_kernel<true>, dim3(nwg, B), dim3(SAMPLE_THREADS), 0, st,
+                               nwg, V, N, D, cfg->topk, n_draft_rows(cfg), mode, target_logits, draft_logits, temperature,
+                               u_accept, u_bonus, tree_token, tree_parent, tree_cand, bars, parts,
+                               accept_len, accept_path, bonus_token);
+        else
+            hipLaunchKernelGGL(sample_accept_kernel<false>, dim3(nwg, B), dim3(SAMPLE_THREADS), 0, st,
+                               nwg, V, N, D, cfg->topk, n_draft_rows(cfg), mode, target_logits, draft_logits, temperature,
+                               u_accept, u_bonus, tree_token, tree_parent, tree_cand, bars, parts,
+                               accept_len, accept_path, bonus_token);
         E2_HIP(hipGetLastError());
     }
     return EAGLE2_OK;

@@ -31,9 +31,11 @@ constexpr int LM_LOADS = LM_ROWS * LM_CHUNK / 1024;   // 16-byte loads per lane 
 constexpr int LM_GMAX = 1024;                // upper bound on workgroups (partials per row)
 
 __global__ void pack_h_kernel(const uint8_t* __restrict__ H, int64_t seq_stride_bytes, int row_bytes,
-                              int M, int F, u32x4* __restrict__ Hp) {
+                              int M, int F, u32x4* __restrict__ Hp, unsigned* __restrict__ done_count, int B) {
     const int nfrag = row_bytes / 64;
     const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (blockIdx.y == 0)                                // counters of the merge kernel's last-arrival test
+        for (int i = gid; i < B; i += gridDim.x * blockDim.x) done_count[i] = 0u;
     const int fi = gid >> 6, lane = gid & 63;
     if (fi >= nfrag) return;
     const int mblk = blockIdx.y;
@@ -256,95 +258,155 @@ __device__ __forceinline__ void wave_best(double& v, int& i) {
     }
 }
 
-// One workgroup per sequence, one wave per frontier row.
+// One workgroup per (frontier row, sequence).  Threads stride over the row's G*KC partial
+// candidates keeping a sorted top-KC each; waves, then the workgroup, reduce those lists by
+// repeated arg-best.  The workgroup that finishes last for a sequence (a counter in the
+// workspace, zeroed by pack_h_kernel) also selects the next frontier.
+constexpr int MG_THREADS = 256;
+
 template <int KC>
-__global__ __launch_bounds__(1024)
+__device__ __forceinline__ void full_insert(float x, int v, float (&val)[KC], int (&idx)[KC]) {
+    if (ranks_before(x, v, val[KC - 1], idx[KC - 1])) {
+        val[KC - 1] = x; idx[KC - 1] = v;
+#pragma unroll
+        for (int q = KC - 1; q > 0; --q) {
+            if (ranks_before(val[q], idx[q], val[q - 1], idx[q - 1])) {
+                float tv = val[q]; val[q] = val[q - 1]; val[q - 1] = tv;
+                int ti = idx[q]; idx[q] = idx[q - 1]; idx[q - 1] = ti;
+            }
+        }
+    }
+}
+
+// k rounds of wave-wide arg-best over the lanes' sorted lists; lane r ends up holding the
+// r-th best (value, index) of the wave in (out_v, out_i)
+template <int KC>
+__device__ __forceinline__ void wave_topk(float (&val)[KC], int (&idx)[KC], int k, int lane, float& out_v, int& out_i) {
+    out_v = -INFINITY; out_i = INT_MAX;
+    for (int r = 0; r < k; ++r) {
+        float bv = val[0]; int bi = idx[0];
+        wave_best(bv, bi);
+        if (val[0] == bv && idx[0] == bi) {            // the winner pops its head
+#pragma unroll
+            for (int q = 0; q < KC - 1; ++q) { val[q] = val[q + 1]; idx[q] = idx[q + 1]; }
+            val[KC - 1] = -INFINITY; idx[KC - 1] = INT_MAX;
+        }
+        if (lane == r) { out_v = bv; out_i = bi; }
+    }
+}
+
+template <int KC>
+__global__ __launch_bounds__(MG_THREADS)
 void expand_merge_kernel(int d, int F, int k, int D, int C, int G,
                          const float* __restrict__ part_ms, const float* __restrict__ part_val,
                          const int* __restrict__ part_idx,
                          int* __restrict__ cand_token, double* __restrict__ cand_score,
-                         int* __restrict__ cand_parent, int* __restrict__ frontier) {
-    __shared__ double s_score[EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK];
-    const int b = blockIdx.x;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+                         int* __restrict__ cand_parent, int* __restrict__ frontier,
+                         unsigned* __restrict__ done_count) {
+    constexpr int NW = MG_THREADS / 64;
+    __shared__ float s_f[NW];
+    __shared__ double s_d[NW];
+    __shared__ float s_cv[NW * EAGLE2_MAX_TOPK];
+    __shared__ int s_ci[NW * EAGLE2_MAX_TOPK];
+    __shared__ int s_last;
+    const int slot = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int base = d == 0 ? 0 : k + (d - 1) * k * k;
-    if (wave < F) {
-        const size_t prow = (size_t)b * F + wave;
-        const float* ms = part_ms + prow * G * 2;
-        float mloc = -INFINITY;
-        for (int p = lane; p < G; p += 64) mloc = fmaxf(mloc, ms[p * 2]);
-        const float mx = wave_max(mloc);
-        double sloc = 0.0;
-        for (int p = lane; p < G; p += 64) {
-            const float mp = ms[p * 2];
-            if (mp > -INFINITY) sloc += (double)ms[p * 2 + 1] * exp((double)mp - (double)mx);
-        }
-        const double log_sum = log(wave_sum(sloc));
+    const size_t prow = (size_t)b * F + slot;
 
-        float tval[KC]; int tidx[KC];
+    // log-sum-exp over the G partial (max, sum) pairs
+    const float* ms = part_ms + prow * G * 2;
+    float mloc = -INFINITY;
+    for (int p = tid; p < G; p += MG_THREADS) mloc = fmaxf(mloc, ms[p * 2]);
+    mloc = wave_max(mloc);
+    if (lane == 0) s_f[wave] = mloc;
+    __syncthreads();
+    float mx = s_f[0];
 #pragma unroll
-        for (int j = 0; j < KC; ++j) { tval[j] = -INFINITY; tidx[j] = INT_MAX; }
-        const float* pv = part_val + prow * G * KC;
-        const int* pi = part_idx + prow * G * KC;
-        for (int j = lane; j < G * KC; j += 64) {
-            const float x = pv[j];
-            const int v = pi[j];
-            if (ranks_before(x, v, tval[KC - 1], tidx[KC - 1])) {
-                tval[KC - 1] = x; tidx[KC - 1] = v;
+    for (int w = 1; w < NW; ++w) mx = fmaxf(mx, s_f[w]);
+    double sloc = 0.0;
+    for (int p = tid; p < G; p += MG_THREADS) {
+        const float mp = ms[p * 2];
+        if (mp > -INFINITY) sloc += (double)ms[p * 2 + 1] * exp((double)mp - (double)mx);
+    }
+    sloc = wave_sum(sloc);
+    if (lane == 0) s_d[wave] = sloc;
+
+    // per-thread top-KC over its share of the candidates (loads batched four at a time)
+    float tval[KC]; int tidx[KC];
 #pragma unroll
-                for (int q = KC - 1; q > 0; --q) {
-                    if (ranks_before(tval[q], tidx[q], tval[q - 1], tidx[q - 1])) {
-                        float tv = tval[q]; tval[q] = tval[q - 1]; tval[q - 1] = tv;
-                        int ti = tidx[q]; tidx[q] = tidx[q - 1]; tidx[q - 1] = ti;
-                    }
-                }
-            }
+    for (int j = 0; j < KC; ++j) { tval[j] = -INFINITY; tidx[j] = INT_MAX; }
+    const float* pv = part_val + prow * G * KC;
+    const int* pi = part_idx + prow * G * KC;
+    const int n = G * KC;
+    for (int j0 = tid; j0 < n; j0 += 4 * MG_THREADS) {
+        float xv[4]; int xi[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int j = j0 + u * MG_THREADS;
+            xv[u] = j < n ? pv[j] : -INFINITY;
+            xi[u] = j < n ? pi[j] : INT_MAX;
         }
-        float my_x = 0.f; int my_tok = 0;
-        for (int r = 0; r < k; ++r) {
-            float bv = tval[0]; int bi = tidx[0];
-            wave_best(bv, bi);
-            if (tval[0] == bv && tidx[0] == bi) {      // the winner pops its head
 #pragma unroll
-                for (int q = 0; q < KC - 1; ++q) { tval[q] = tval[q + 1]; tidx[q] = tidx[q + 1]; }
-                tval[KC - 1] = -INFINITY; tidx[KC - 1] = INT_MAX;
-            }
-            if (lane == r) { my_x = bv; my_tok = bi; }
-        }
+        for (int u = 0; u < 4; ++u) full_insert<KC>(xv[u], xi[u], tval, tidx);
+    }
+    float wv; int wi;
+    wave_topk<KC>(tval, tidx, k, lane, wv, wi);
+    if (lane < k) { s_cv[wave * k + lane] = wv; s_ci[wave * k + lane] = wi; }
+    __syncthreads();
+    double log_sum = 0.0;
+    if (wave == 0) {
+        double tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) tot += s_d[w];
+        log_sum = log(tot);
+        // NW*k <= 64 candidates, one per lane
+        float cv[1] = {lane < NW * k ? s_cv[lane] : -INFINITY};
+        int ci[1] = {lane < NW * k ? s_ci[lane] : INT_MAX};
+        float my_x; int my_tok;
+        wave_topk<1>(cv, ci, k, lane, my_x, my_tok);
         if (lane < k) {
-            const int cid = base + wave * k + lane;
-            int par = d == 0 ? -1 : frontier[((size_t)b * D + d) * k + wave];
+            const int cid = base + slot * k + lane;
+            int par = d == 0 ? -1 : frontier[((size_t)b * D + d) * k + slot];
             if (d > 0 && (par < 0 || par >= C)) par = 0;   // garbage in the caller's frontier stays in bounds
             const double ps = d == 0 ? 0.0 : cand_score[(size_t)b * C + par];
-            const double sc = ps + (((double)my_x - (double)mx) - log_sum);
             cand_token[(size_t)b * C + cid] = my_tok;
-            cand_score[(size_t)b * C + cid] = sc;
+            cand_score[(size_t)b * C + cid] = ps + (((double)my_x - (double)mx) - log_sum);
             cand_parent[(size_t)b * C + cid] = par;
-            s_score[wave * k + lane] = sc;
         }
+    }
+    if (d + 1 >= D) return;
+
+    // the last workgroup of this sequence picks the next frontier
+    __syncthreads();
+    if (tid == 0) {
+        __threadfence();
+        const unsigned prev = atomicAdd(done_count + b, 1u);
+        s_last = prev == (unsigned)(F - 1) ? 1 : 0;
+        __threadfence();
     }
     __syncthreads();
-    if (d + 1 < D && wave == 0) {
-        const int n = F * k;                            // <= 256 new candidates, <= 4 per lane
-        double v[4]; int id[4];
+    if (!s_last || wave != 0) return;
+    const int nn = F * k;                               // <= 256 new candidates, <= 4 per lane
+    double v[4]; int id[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int j = lane + q * 64;
-            v[q] = j < n ? s_score[j] : -INFINITY;
-            id[q] = j < n ? base + j : INT_MAX;
-        }
-        int mine = -1;
-        for (int r = 0; r < k; ++r) {
-            double bv = v[0]; int bi = id[0];
-#pragma unroll
-            for (int q = 1; q < 4; ++q) if (ranks_before(v[q], id[q], bv, bi)) { bv = v[q]; bi = id[q]; }
-            wave_best(bv, bi);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) if (id[q] == bi) { v[q] = -INFINITY; id[q] = INT_MAX; }
-            if (lane == r) mine = bi;
-        }
-        if (lane < k) frontier[((size_t)b * D + d + 1) * k + lane] = mine;
+    for (int q = 0; q < 4; ++q) {
+        const int j = lane + q * 64;
+        v[q] = j < nn ? __hip_atomic_load(cand_score + (size_t)b * C + base + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                      : -INFINITY;
+        id[q] = j < nn ? base + j : INT_MAX;
     }
+    int mine = -1;
+    for (int r = 0; r < k; ++r) {
+        double bv = v[0]; int bi = id[0];
+#pragma unroll
+        for (int q = 1; q < 4; ++q) if (ranks_before(v[q], id[q], bv, bi)) { bv = v[q]; bi = id[q]; }
+        wave_best(bv, bi);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) if (id[q] == bi) { v[q] = -INFINITY; id[q] = INT_MAX; }
+        if (lane == r) mine = bi;
+    }
+    if (lane < k) frontier[((size_t)b * D + d + 1) * k + lane] = mine;
 }
 
 static int lm_grid(const eagle2_cfg* cfg) {
@@ -355,7 +417,7 @@ static int lm_grid(const eagle2_cfg* cfg) {
     return g < 1 ? 1 : g;
 }
 
-struct ExpandWs { size_t hp, ms, val, idx, total; };
+struct ExpandWs { size_t hp, ms, val, idx, cnt, total; };
 static ExpandWs expand_layout(const eagle2_cfg* cfg) {
     const size_t row_bytes = (size_t)cfg->hidden * elem_size(cfg);
     const size_t mmax = (size_t)cfg->batch * cfg->topk;
@@ -365,7 +427,8 @@ static ExpandWs expand_layout(const eagle2_cfg* cfg) {
     w.ms = round_up(mblks * row_bytes * 16, 256);
     w.val = w.ms + round_up(mblks * 16 * LM_GMAX * 2 * sizeof(float), 256);
     w.idx = w.val + round_up(mblks * 16 * LM_GMAX * EAGLE2_MAX_TOPK * sizeof(float), 256);
-    w.total = w.idx + round_up(mblks * 16 * LM_GMAX * EAGLE2_MAX_TOPK * sizeof(int), 256);
+    w.cnt = w.idx + round_up(mblks * 16 * LM_GMAX * EAGLE2_MAX_TOPK * sizeof(int), 256);
+    w.total = w.cnt + round_up((size_t)cfg->batch * sizeof(unsigned), 256);
     return w;
 }
 size_t expand_workspace(const eagle2_cfg* cfg) { return expand_layout(cfg).total; }
@@ -383,12 +446,13 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
     float* part_ms = reinterpret_cast<float*>(ws + L.ms);
     float* part_val = reinterpret_cast<float*>(ws + L.val);
     int* part_idx = reinterpret_cast<int*>(ws + L.idx);
+    unsigned* done_count = reinterpret_cast<unsigned*>(ws + L.cnt);
     const int64_t stride_el = h_seq_stride == 0 ? (int64_t)F * cfg->hidden : h_seq_stride;
 
     const int nfrag = row_bytes / 64;
     dim3 pg((nfrag * 64 + 255) / 256, mblks);
     hipLaunchKernelGGL(pack_h_kernel, pg, dim3(256), 0, st, reinterpret_cast<const uint8_t*>(H),
-                       stride_el * elem_size(cfg), row_bytes, M, F, Hp);
+                       stride_el * elem_size(cfg), row_bytes, M, F, Hp, done_count, cfg->batch);
     E2_HIP(hipGetLastError());
 
     const size_t smem = 4 * LM_STAGE;
@@ -402,9 +466,9 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
     timing_end(0, st);
     E2_HIP(hipGetLastError());
 
-    hipLaunchKernelGGL((expand_merge_kernel<KC>), dim3(cfg->batch), dim3(1024), 0, st,
+    hipLaunchKernelGGL((expand_merge_kernel<KC>), dim3(F, cfg->batch), dim3(MG_THREADS), 0, st,
                        d, F, k, cfg->depth, n_cand(cfg), G, part_ms, part_val, part_idx,
-                       cand_token, cand_score, cand_parent, frontier);
+                       cand_token, cand_score, cand_parent, frontier, done_count);
     E2_HIP(hipGetLastError());
     return EAGLE2_OK;
 }
