@@ -13,14 +13,16 @@
 // scalars with the same arithmetic.
 
 #include "common.h"
+#include <stdlib.h>
 
 namespace eagle2 {
 
 constexpr int AM_THREADS = 256;
-constexpr int SAMPLE_WGS = 128;          // most workgroups that cooperate on one sampling sequence
-constexpr int SAMPLE_MAXE = 8;           // vocabulary entries a thread can keep in registers
-constexpr int SAMPLE_THREADS = 256;
+constexpr int SAMPLE_WGS = 32;           // most workgroups that cooperate on one sampling sequence
+constexpr int SAMPLE_MAXE = 4;           // vocabulary entries a thread can keep in registers
+constexpr int SAMPLE_THREADS = 1024;
 constexpr int SAMPLE_NPART = 4;          // doubles exchanged per workgroup per pass
+constexpr int SAMPLE_SLOT = 8;           // 64-bit words per exchange slot: the doubles, then a sequence flag
 constexpr unsigned SPIN_LIMIT = 1u << 22;
 
 struct AcceptWs { size_t choice, bar, part, total; };
@@ -28,15 +30,16 @@ static AcceptWs accept_layout(const eagle2_cfg* cfg) {
     AcceptWs w;
     w.choice = 0;
     w.bar = round_up((size_t)cfg->batch * cfg->n_tree * sizeof(int), 256);
-    w.part = w.bar + round_up((size_t)cfg->batch * 2 * sizeof(unsigned), 256);
-    w.total = w.part + round_up((size_t)cfg->batch * 2 * SAMPLE_WGS * SAMPLE_NPART * sizeof(double), 256);
+    w.part = w.bar + round_up((size_t)cfg->batch * sizeof(unsigned), 256);
+    w.total = w.part + round_up((size_t)cfg->batch * 2 * SAMPLE_WGS * SAMPLE_SLOT * sizeof(unsigned long long), 256);
     return w;
 }
 size_t accept_workspace(const eagle2_cfg* cfg) { return accept_layout(cfg).total; }
 
-__global__ void accept_init_kernel(unsigned* bar, int n) {
+__global__ void accept_init_kernel(unsigned* fail, int nfail, unsigned long long* slots, int nwords) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) bar[i] = 0u;
+    if (i < nfail) fail[i] = 0u;
+    if (i < nwords) slots[i] = 0ull;
 }
 
 // grid (N, B): arg-max of one row of target logits, lowest id on ties
@@ -110,48 +113,60 @@ void greedy_walk_kernel(int N, int D, const int* __restrict__ mode, const int* _
 // ---- sampling ------------------------------------------------------------------------
 
 struct SampleCtx {
-    unsigned* bar;       // this sequence's barrier counter (monotonic)
-    unsigned* fail;      // this sequence's failure flag
-    double* part;        // [2][SAMPLE_WGS][SAMPLE_NPART]
-    unsigned target;     // arrivals expected at the next barrier
+    unsigned* fail;              // this sequence's failure flag
+    unsigned long long* slots;   // [2][SAMPLE_WGS][SAMPLE_SLOT]
     int pass;
-    int nwg;             // workgroups cooperating on this sequence (<= SAMPLE_WGS)
+    int nwg;                     // workgroups cooperating on this sequence (<= SAMPLE_WGS)
 };
 
-// Publishes up to SAMPLE_NPART doubles of this workgroup, waits for all workgroups of the
-// sequence, and returns with `out[g*NPART + i]` (LDS) holding every workgroup's values.
-// Returns false if the bounded wait expired (then the kernel gives up cleanly).
+// All-gather of SAMPLE_NPART doubles among the workgroups of one sequence.  Every workgroup
+// publishes its values followed by a sequence flag in its own slot (no shared counter, so
+// no serialised read-modify-writes); thread t of every workgroup waits for slot t's flag
+// and copies that slot into `out[t*NPART + i]` (LDS).  Slots alternate between two sets by
+// pass parity: a workgroup can only be one exchange ahead of the slowest one.  The wait is
+// bounded; false means it expired and the kernel gives up cleanly.
 __device__ bool exchange(SampleCtx& cx, const double (&mine)[SAMPLE_NPART], double* out /*LDS*/, int* s_ok) {
-    const int wg = blockIdx.x;
-    double* buf = cx.part + (size_t)(cx.pass & 1) * SAMPLE_WGS * SAMPLE_NPART;
+    const int wg = blockIdx.x, tid = threadIdx.x;
+    unsigned long long* buf = cx.slots + (size_t)(cx.pass & 1) * SAMPLE_WGS * SAMPLE_SLOT;
+    const unsigned long long seq = (unsigned long long)cx.pass + 1ull;
+    __syncthreads();                                   // the previous exchange's `out` is no longer read
+    if (tid == 0) {
+        *s_ok = 1;
+        for (int i = 0; i < SAMPLE_NPART; ++i)
+            __hip_atomic_store(buf + wg * SAMPLE_SLOT + i, (unsigned long long)__double_as_longlong(mine[i]),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // The values above are device-scope atomic stores (written through to the coherence
+        // point).  Waiting for their acknowledgement is all the ordering the flag needs; a
+        // device-scope release would also write back the whole L2, once per workgroup per pass.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __hip_atomic_store(buf + wg * SAMPLE_SLOT + SAMPLE_NPART, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int i = 0; i < SAMPLE_NPART; ++i) buf[wg * SAMPLE_NPART + i] = mine[i];
-        __threadfence();
-        atomicAdd(cx.bar, 1u);
-        cx.target += (unsigned)cx.nwg;
+    if (tid < cx.nwg) {
         unsigned spins = 0;
         bool ok = true;
-        while (__hip_atomic_load(cx.bar, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < cx.target) {
-            __builtin_amdgcn_s_sleep(4);
-            if (++spins > SPIN_LIMIT || __hip_atomic_load(cx.fail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+        // relaxed device-scope loads: they are served at the coherence point, and the values
+        // read afterwards are fetched the same way, so no cache invalidation is needed per poll
+        while (__hip_atomic_load(buf + tid * SAMPLE_SLOT + SAMPLE_NPART, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != seq) {
+            __builtin_amdgcn_s_sleep(2);
+            if ((++spins & 1023u) == 0u &&
+                (spins > SPIN_LIMIT || __hip_atomic_load(cx.fail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
                 ok = false;
                 atomicExch(cx.fail, 1u);
                 break;
             }
         }
-        __threadfence();
-        *s_ok = ok ? 1 : 0;
-    }
-    __syncthreads();
-    const bool ok = *s_ok != 0;
-    if (ok) {
-        for (int i = threadIdx.x; i < cx.nwg * SAMPLE_NPART; i += SAMPLE_THREADS)
-            out[i] = __hip_atomic_load(buf + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (ok) {
+            for (int i = 0; i < SAMPLE_NPART; ++i)
+                out[tid * SAMPLE_NPART + i] = __longlong_as_double((long long)__hip_atomic_load(
+                    buf + tid * SAMPLE_SLOT + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        } else {
+            *s_ok = 0;
+        }
     }
     __syncthreads();
     cx.pass += 1;
-    return ok;
+    return *s_ok != 0;
 }
 
 __device__ __forceinline__ double block_sum(double v, double* s_red) {
@@ -160,6 +175,7 @@ __device__ __forceinline__ double block_sum(double v, double* s_red) {
     if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
     __syncthreads();
     double t = 0.0;
+#pragma unroll
     for (int w = 0; w < SAMPLE_THREADS / 64; ++w) t += s_red[w];
     return t;
 }
@@ -169,33 +185,82 @@ __device__ __forceinline__ double block_max(double v, double* s_red) {
     if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
     __syncthreads();
     double t = s_red[0];
+#pragma unroll
     for (int w = 1; w < SAMPLE_THREADS / 64; ++w) t = fmax(t, s_red[w]);
     return t;
 }
+__device__ __forceinline__ void block_max2(double& a, double& b, double* s_red2) {
+    a = wave_maxd(a);
+    b = wave_maxd(b);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { s_red2[(threadIdx.x >> 6) * 2] = a; s_red2[(threadIdx.x >> 6) * 2 + 1] = b; }
+    __syncthreads();
+    double ta = s_red2[0], tb = s_red2[1];
+#pragma unroll
+    for (int w = 1; w < SAMPLE_THREADS / 64; ++w) { ta = fmax(ta, s_red2[w * 2]); tb = fmax(tb, s_red2[w * 2 + 1]); }
+    a = ta;
+    b = tb;
+}
+// sums two values per thread over the workgroup with one pair of barriers
+__device__ __forceinline__ void block_sum2(double& a, double& b, double* s_red2 /* 2 * waves */) {
+    a = wave_sum(a);
+    b = wave_sum(b);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { s_red2[(threadIdx.x >> 6) * 2] = a; s_red2[(threadIdx.x >> 6) * 2 + 1] = b; }
+    __syncthreads();
+    double ta = 0.0, tb = 0.0;
+#pragma unroll
+    for (int w = 0; w < SAMPLE_THREADS / 64; ++w) { ta += s_red2[w * 2]; tb += s_red2[w * 2 + 1]; }
+    a = ta;
+    b = tb;
+}
+// exclusive prefix sum of one value per thread, in thread order
+__device__ __forceinline__ double block_exclusive_scan(double v, double* s_red) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    double inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const double up = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += up;
+    }
+    __syncthreads();
+    if (lane == 63) s_red[w] = inc;
+    __syncthreads();
+    double before = 0.0;
+    for (int i = 0; i < w; ++i) before += s_red[i];
+    return before + (inc - v);
+}
 
 struct NodeScalars {      // everything needed to rebuild (p_j(v), q_j(v)) for any v
-    double inv_t, mt, st, md, sd;
+    double inv_t, mt, ist, md, isd;          // 1/T, max and 1/sum-exp of the target row; same for the draft row
     int has_q;
     int nrej;
     int rej_tok[EAGLE2_MAX_TOPK + 1];
-    double rej_tot[EAGLE2_MAX_TOPK + 1];
-    double rej_qs[EAGLE2_MAX_TOPK + 1];
+    double rej_itot[EAGLE2_MAX_TOPK + 1];    // 1 / residual mass of rejection i (0: keep p)
+    double rej_iqs[EAGLE2_MAX_TOPK + 1];     // 1 / remaining draft mass of rejection i (0: keep q)
 };
 
+__device__ __forceinline__ void initial_state(const NodeScalars& ns, float zt, float zd, double& p, double& q) {
+    p = exp((double)zt * ns.inv_t - ns.mt) * ns.ist;
+    q = ns.has_q ? exp((double)zd - ns.md) * ns.isd : 0.0;
+}
+// one rejection: p <- norm(max(0, p - q)); the rejected token leaves q; q renormalised
+__device__ __forceinline__ void reject_step(int v, int x, double itot, double iqs, double& p, double& q) {
+    const double r = fmax(p - q, 0.0);
+    if (itot > 0.0) p = r * itot;
+    if (v == x) q = 0.0;
+    if (iqs > 0.0) q = q * iqs;
+}
 __device__ __forceinline__ void element_state(const NodeScalars& ns, int v, float zt, float zd, double& p, double& q) {
-    p = exp((double)zt * ns.inv_t - ns.mt) / ns.st;
-    q = ns.has_q ? exp((double)zd - ns.md) / ns.sd : 0.0;
-    for (int i = 0; i < ns.nrej; ++i) {
-        const double r = fmax(p - q, 0.0);
-        if (ns.rej_tot[i] > 0.0) p = r / ns.rej_tot[i];
-        if (v == ns.rej_tok[i]) q = 0.0;
-        if (ns.rej_qs[i] > 0.0) q = q / ns.rej_qs[i];
-    }
+    initial_state(ns, zt, zd, p, q);
+    for (int i = 0; i < ns.nrej; ++i) reject_step(v, ns.rej_tok[i], ns.rej_itot[i], ns.rej_iqs[i], p, q);
 }
 
 // grid (nwg, B).  CACHED: every thread owns at most SAMPLE_MAXE consecutive vocabulary
 // entries and keeps their current (p_j, q_j) in registers from pass to pass; otherwise the
-// state is rebuilt from the logits and the recorded scalars in every pass.
+// state is rebuilt from the logits and the recorded scalars in every pass.  The (p_j, q_j)
+// of the current row's children are tracked in LDS by every workgroup, so a decision
+// costs one division.
 template <bool CACHED>
 __global__ __launch_bounds__(SAMPLE_THREADS)
 void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int* __restrict__ mode,
@@ -203,35 +268,39 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
                           const float* __restrict__ temperature, const float* __restrict__ u_accept,
                           const float* __restrict__ u_bonus, const int* __restrict__ tree_token,
                           const int* __restrict__ tree_parent, const int* __restrict__ tree_cand,
-                          unsigned* __restrict__ bars, double* __restrict__ parts,
+                          unsigned* __restrict__ fails, unsigned long long* __restrict__ slots,
                           int* __restrict__ accept_len, int* __restrict__ accept_path, int* __restrict__ bonus) {
     const int b = blockIdx.y, wg = blockIdx.x, tid = threadIdx.x;
     if (mode[b] != EAGLE2_MODE_SAMPLE) return;
+    constexpr int KIDS = EAGLE2_MAX_TOPK + 1;
     __shared__ NodeScalars ns;
     __shared__ double s_all[SAMPLE_WGS * SAMPLE_NPART];
-    __shared__ double s_red[SAMPLE_THREADS / 64];
-    __shared__ double s_scan[SAMPLE_THREADS];
+    __shared__ double s_red[2 * (SAMPLE_THREADS / 64)];
+    __shared__ double s_g[2];                                   // totals shared by the whole workgroup
+    __shared__ double s_pk[KIDS], s_qk[KIDS];                   // current (p, q) at the children's tokens
     __shared__ int s_kids[EAGLE2_MAX_TREE];
+    __shared__ int s_par[EAGLE2_MAX_TREE], s_tok[EAGLE2_MAX_TREE];
+    __shared__ float s_ua[EAGLE2_MAX_TREE];
+    __shared__ float s_ztx[KIDS], s_zdx[KIDS];                  // logits at the children's tokens
     __shared__ int s_last[SAMPLE_THREADS / 64];
     __shared__ int s_nkids, s_ok, s_decision, s_cand;
 
     SampleCtx cx;
-    cx.bar = bars + (size_t)b * 2;
-    cx.fail = bars + (size_t)b * 2 + 1;
-    cx.part = parts + (size_t)b * 2 * SAMPLE_WGS * SAMPLE_NPART;
-    cx.target = 0;
+    cx.fail = fails + b;
+    cx.slots = slots + (size_t)b * 2 * SAMPLE_WGS * SAMPLE_SLOT;
     cx.pass = 0;
     cx.nwg = nwg;
 
-    const int* tok = tree_token + (size_t)b * N;
-    const int* par = tree_parent + (size_t)b * N;
-    const int* cnd = tree_cand + (size_t)b * N;
-    const float* ua = u_accept + (size_t)b * N;
     const float* ub = u_bonus + (size_t)b * N;
     int* path = accept_path + (size_t)b * (D + 1);
     float T = temperature[b];
     if (!(T > 0.f)) T = 1.f;
     const double inv_t = 1.0 / (double)T;
+    for (int c = tid; c < N; c += SAMPLE_THREADS) {
+        s_par[c] = tree_parent[(size_t)b * N + c];
+        s_tok[c] = tree_token[(size_t)b * N + c];
+        s_ua[c] = u_accept[(size_t)b * N + c];
+    }
 
     // this workgroup's slice of the vocabulary and this thread's chunk of it (both contiguous,
     // so prefix sums compose)
@@ -244,78 +313,109 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
 
     int cur = 0, len = 0;
     for (int guard = 0; guard <= N; ++guard) {
-        // children of cur in flat order and the draft row they were taken from
-        if (tid == 0) {
+        // children of cur in flat order (a parallel compaction over the N <= 128 rows)
+        if (tid == 0) s_nkids = 0;
+        __syncthreads();
+        if (tid < 64) {
             int nk = 0;
-            for (int c = cur + 1; c < N; ++c) if (par[c] == cur) s_kids[nk++] = c;
-            s_nkids = nk;
+            for (int c0 = 0; c0 < N; c0 += 64) {
+                const int c = c0 + tid;
+                const bool is_kid = c < N && c > cur && s_par[c] == cur;
+                const unsigned long long m = __ballot(is_kid);
+                if (is_kid) s_kids[nk + __popcll(m & ((1ull << tid) - 1ull))] = c;
+                nk += __popcll(m);
+            }
+            if (tid == 0) s_nkids = nk;
         }
         __syncthreads();
-        const int nkids = s_nkids;
+        const int nkids = min(s_nkids, KIDS);
         int drow = 0;
-        if (nkids > 0) {
-            const int cid = cnd[s_kids[0]];
+        if (nkids > 0) {                                       // the draft row the children were taken from
+            const int cid = tree_cand[(size_t)b * N + s_kids[0]];
             if (cid >= k) { const int layer = 2 + (cid - k) / (k * k); drow = 1 + (layer - 2) * k + ((cid - k) % (k * k)) / k; }
             if (drow < 0 || drow >= R) drow = 0;
         }
         const float* zt_row = target_logits + ((size_t)b * N + cur) * (size_t)V;
         const float* zd_row = draft_logits + ((size_t)b * R + drow) * (size_t)V;
         const bool has_q = nkids > 0;
+        if (tid < nkids) {                                     // one latency for all children
+            const int x = s_tok[s_kids[tid]];
+            const bool okx = x >= 0 && x < V;
+            s_ztx[tid] = okx ? zt_row[x] : 0.f;
+            s_zdx[tid] = okx ? zd_row[x] : 0.f;
+        }
 
         // pass A: (max, sum-exp) of both rows, merged across workgroups
+        float zte[CACHED ? SAMPLE_MAXE : 1], zde[CACHED ? SAMPLE_MAXE : 1];
         double mt = -INFINITY, md = -INFINITY;
-        for (int v = t_lo; v < t_hi; ++v) {
-            mt = fmax(mt, (double)zt_row[v] * inv_t);
-            if (has_q) md = fmax(md, (double)zd_row[v]);
+        if constexpr (CACHED) {
+#pragma unroll
+            for (int e = 0; e < SAMPLE_MAXE; ++e) {            // all loads in flight together
+                const int v = t_lo + e;
+                zte[e] = v < t_hi ? zt_row[v] : -INFINITY;
+                zde[e] = (v < t_hi && has_q) ? zd_row[v] : -INFINITY;
+            }
+#pragma unroll
+            for (int e = 0; e < SAMPLE_MAXE; ++e) {
+                mt = fmax(mt, (double)zte[e] * inv_t);
+                md = fmax(md, (double)zde[e]);
+            }
+        } else {
+            for (int v = t_lo; v < t_hi; ++v) {
+                mt = fmax(mt, (double)zt_row[v] * inv_t);
+                if (has_q) md = fmax(md, (double)zd_row[v]);
+            }
         }
-        mt = block_max(mt, s_red);
-        md = block_max(md, s_red);
+        block_max2(mt, md, s_red);
         double st = 0.0, sd = 0.0;
-        for (int v = t_lo; v < t_hi; ++v) {
-            st += exp((double)zt_row[v] * inv_t - mt);
-            if (has_q) sd += exp((double)zd_row[v] - md);
+        if constexpr (CACHED) {
+#pragma unroll
+            for (int e = 0; e < SAMPLE_MAXE; ++e) {
+                if (t_lo + e < t_hi) {
+                    st += exp((double)zte[e] * inv_t - mt);
+                    if (has_q) sd += exp((double)zde[e] - md);
+                }
+            }
+        } else {
+            for (int v = t_lo; v < t_hi; ++v) {
+                st += exp((double)zt_row[v] * inv_t - mt);
+                if (has_q) sd += exp((double)zd_row[v] - md);
+            }
         }
-        st = block_sum(st, s_red);
-        sd = block_sum(sd, s_red);
+        block_sum2(st, sd, s_red);
         {
             const double mine[SAMPLE_NPART] = {mt, st, md, sd};
             if (!exchange(cx, mine, s_all, &s_ok)) break;
         }
-        if (tid == 0) {
-            double gmt = -INFINITY, gmd = -INFINITY;
-            for (int g = 0; g < nwg; ++g) { gmt = fmax(gmt, s_all[g * SAMPLE_NPART]); gmd = fmax(gmd, s_all[g * SAMPLE_NPART + 2]); }
-            double gst = 0.0, gsd = 0.0;
-            for (int g = 0; g < nwg; ++g) {
-                if (s_all[g * SAMPLE_NPART] > -INFINITY) gst += s_all[g * SAMPLE_NPART + 1] * exp(s_all[g * SAMPLE_NPART] - gmt);
-                if (s_all[g * SAMPLE_NPART + 2] > -INFINITY) gsd += s_all[g * SAMPLE_NPART + 3] * exp(s_all[g * SAMPLE_NPART + 2] - gmd);
+        if (tid < 64) {                                        // every workgroup combines the same values the same way
+            const bool in = tid < nwg;
+            const double m_t = in ? s_all[tid * SAMPLE_NPART] : -INFINITY, s_t = in ? s_all[tid * SAMPLE_NPART + 1] : 0.0;
+            const double m_d = in ? s_all[tid * SAMPLE_NPART + 2] : -INFINITY, s_d = in ? s_all[tid * SAMPLE_NPART + 3] : 0.0;
+            const double gmt = wave_maxd(m_t), gmd = wave_maxd(m_d);
+            const double gst = wave_sum(m_t > -INFINITY ? s_t * exp(m_t - gmt) : 0.0);
+            const double gsd = wave_sum(m_d > -INFINITY ? s_d * exp(m_d - gmd) : 0.0);
+            if (tid == 0) {
+                ns.inv_t = inv_t; ns.mt = gmt; ns.ist = 1.0 / gst; ns.md = gmd; ns.isd = has_q ? 1.0 / gsd : 0.0;
+                ns.has_q = has_q ? 1 : 0;
+                ns.nrej = 0;
             }
-            ns.inv_t = inv_t; ns.mt = gmt; ns.st = gst; ns.md = gmd; ns.sd = gsd;
-            ns.has_q = has_q ? 1 : 0;
-            ns.nrej = 0;
         }
         __syncthreads();
+        if (tid < nkids) initial_state(ns, s_ztx[tid], s_zdx[tid], s_pk[tid], s_qk[tid]);
         if constexpr (CACHED) {
 #pragma unroll
             for (int e = 0; e < SAMPLE_MAXE; ++e) {
-                const int v = t_lo + e;
-                if (v < t_hi) element_state(ns, v, zt_row[v], has_q ? zd_row[v] : 0.f, pe[e], qe[e]);
+                if (t_lo + e < t_hi) initial_state(ns, zte[e], has_q ? zde[e] : 0.f, pe[e], qe[e]);
                 else { pe[e] = 0.0; qe[e] = 0.0; }
             }
         }
+        __syncthreads();
 
         bool moved = false, failed = false;
-        for (int ci = 0; has_q && ci < nkids && ci < EAGLE2_MAX_TOPK + 1; ++ci) {
+        for (int ci = 0; ci < nkids; ++ci) {
             const int c = s_kids[ci];
-            const int x = tok[c];
-            if (tid == 0) {
-                int dec = 0;
-                if (x >= 0 && x < V) {
-                    double p, q;
-                    element_state(ns, x, zt_row[x], zd_row[x], p, q);
-                    dec = ((double)ua[c] < p / q) ? 1 : 0;
-                }
-                s_decision = dec;
-            }
+            const int x = s_tok[c];
+            if (tid == 0) s_decision = (x >= 0 && x < V && (double)s_ua[c] < s_pk[ci] / s_qk[ci]) ? 1 : 0;
             __syncthreads();
             if (s_decision) { cur = c; ++len; moved = true; if (wg == 0 && tid == 0 && len <= D) path[len] = c; break; }
             // rejected: residual mass and remaining draft mass
@@ -334,27 +434,28 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
                     if (v != x) qs += q;
                 }
             }
-            tot = block_sum(tot, s_red);
-            qs = block_sum(qs, s_red);
+            block_sum2(tot, qs, s_red);
             {
                 const double mine[SAMPLE_NPART] = {tot, qs, 0.0, 0.0};
                 if (!exchange(cx, mine, s_all, &s_ok)) { failed = true; break; }
             }
-            double gt = 0.0, gq = 0.0;
-            for (int g = 0; g < nwg; ++g) { gt += s_all[g * SAMPLE_NPART]; gq += s_all[g * SAMPLE_NPART + 1]; }
+            if (tid < 64) {
+                const double gt0 = wave_sum(tid < nwg ? s_all[tid * SAMPLE_NPART] : 0.0);
+                const double gq0 = wave_sum(tid < nwg ? s_all[tid * SAMPLE_NPART + 1] : 0.0);
+                if (tid == 0) { s_g[0] = gt0; s_g[1] = gq0; }
+            }
+            __syncthreads();
+            const double gt = s_g[0], gq = s_g[1];
+            const double itot = gt > 0.0 ? 1.0 / gt : 0.0, iqs = gq > 0.0 ? 1.0 / gq : 0.0;
             if (tid == 0) {
                 const int j = ns.nrej;
-                ns.rej_tok[j] = x; ns.rej_tot[j] = gt; ns.rej_qs[j] = gq;
+                ns.rej_tok[j] = x; ns.rej_itot[j] = itot; ns.rej_iqs[j] = iqs;
                 ns.nrej = j + 1;
             }
+            if (tid < nkids) reject_step(s_tok[s_kids[tid]], x, itot, iqs, s_pk[tid], s_qk[tid]);
             if constexpr (CACHED) {
 #pragma unroll
-                for (int e = 0; e < SAMPLE_MAXE; ++e) {
-                    const double r = fmax(pe[e] - qe[e], 0.0);
-                    if (gt > 0.0) pe[e] = r / gt;
-                    if (t_lo + e == x) qe[e] = 0.0;
-                    if (gq > 0.0) qe[e] = qe[e] / gq;
-                }
+                for (int e = 0; e < SAMPLE_MAXE; ++e) reject_step(t_lo + e, x, itot, iqs, pe[e], qe[e]);
             }
             __syncthreads();
         }
@@ -375,50 +476,57 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
                 if (p > 0.0) last_pos = v;
             }
         }
-        s_scan[tid] = loc;
+        const double th_before = block_exclusive_scan(loc, s_red);
         const double wg_sum = block_sum(loc, s_red);
         {
             const double mine[SAMPLE_NPART] = {wg_sum, 0.0, 0.0, 0.0};
             if (!exchange(cx, mine, s_all, &s_ok)) break;
         }
-        double total = 0.0, before = 0.0;
-        for (int g = 0; g < nwg; ++g) { if (g == wg) before = total; total += s_all[g * SAMPLE_NPART]; }
+        // every workgroup finds, from the same sums in the same order, which workgroup's slice
+        // holds the crossing; only that one scans its slice and writes the result
+        double total = 0.0;
+        for (int g = 0; g < nwg; ++g) total += s_all[g * SAMPLE_NPART];
         const double goal = (double)ub[cur] * total;
+        int owner = -1, last_nonempty = 0;
+        double before = 0.0, run = 0.0;
+        for (int g = 0; g < nwg; ++g) {
+            const double sg = s_all[g * SAMPLE_NPART];
+            if (owner < 0 && run + sg > goal) { owner = g; before = run; }
+            if (sg > 0.0) last_nonempty = g;
+            run += sg;
+        }
+        const bool crossing = owner >= 0;
+        if (!crossing) owner = last_nonempty;          // goal >= total: take the last token with mass
+        if (wg != owner) return;
         if (tid == 0) s_cand = INT_MAX;
         __syncthreads();
-        double c = before;
-        for (int t = 0; t < tid; ++t) c += s_scan[t];
-        // every thread scans its chunk; the smallest index whose running sum passes the goal wins
-        if constexpr (CACHED) {
-            bool hit = false;
+        if (crossing) {
+            double c = before + th_before;
+            // every thread scans its chunk; the smallest index whose running sum passes the goal wins
+            if constexpr (CACHED) {
+                bool hit = false;
 #pragma unroll
-            for (int e = 0; e < SAMPLE_MAXE; ++e) {
-                c += pe[e];
-                if (!hit && t_lo + e < t_hi && c > goal) { atomicMin(&s_cand, t_lo + e); hit = true; }
-            }
-        } else {
-            for (int v = t_lo; v < t_hi; ++v) {
-                double p, q;
-                element_state(ns, v, zt_row[v], has_q ? zd_row[v] : 0.f, p, q);
-                c += p;
-                if (c > goal) { atomicMin(&s_cand, v); break; }
+                for (int e = 0; e < SAMPLE_MAXE; ++e) {
+                    c += pe[e];
+                    if (!hit && t_lo + e < t_hi && c > goal) { atomicMin(&s_cand, t_lo + e); hit = true; }
+                }
+            } else {
+                for (int v = t_lo; v < t_hi; ++v) {
+                    double p, q;
+                    element_state(ns, v, zt_row[v], has_q ? zd_row[v] : 0.f, p, q);
+                    c += p;
+                    if (c > goal) { atomicMin(&s_cand, v); break; }
+                }
             }
         }
-        // last token with positive mass, for the (measure-zero) case of no crossing
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) last_pos = max(last_pos, __shfl_xor(last_pos, o, 64));
         if ((tid & 63) == 0) s_last[tid >> 6] = last_pos;
         __syncthreads();
-        {
+        if (tid == 0) {
             int lp = -1;
             for (int w2 = 0; w2 < SAMPLE_THREADS / 64; ++w2) lp = max(lp, s_last[w2]);
-            const double mine[SAMPLE_NPART] = {(double)s_cand, (double)lp, 0.0, 0.0};
-            if (!exchange(cx, mine, s_all, &s_ok)) break;
-        }
-        if (wg == 0 && tid == 0) {
-            double best = (double)INT_MAX, lastp = -1.0;
-            for (int g = 0; g < nwg; ++g) { best = fmin(best, s_all[g * SAMPLE_NPART]); lastp = fmax(lastp, s_all[g * SAMPLE_NPART + 1]); }
-            int out = best < (double)INT_MAX ? (int)best : (int)lastp;
+            int out = s_cand != INT_MAX ? s_cand : lp;   // rounding at a slice edge: last token with mass
             if (out < 0) out = 0;
             bonus[b] = out;
             accept_len[b] = len;
@@ -452,8 +560,8 @@ extern "C" int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
     const AcceptWs L = accept_layout(cfg);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     int* choice = reinterpret_cast<int*>(ws + L.choice);
-    unsigned* bars = reinterpret_cast<unsigned*>(ws + L.bar);
-    double* parts = reinterpret_cast<double*>(ws + L.part);
+    unsigned* fails = reinterpret_cast<unsigned*>(ws + L.bar);
+    unsigned long long* slots = reinterpret_cast<unsigned long long*>(ws + L.part);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int B = cfg->batch, N = cfg->n_tree, V = cfg->vocab, D = cfg->depth;
 
@@ -463,22 +571,24 @@ extern "C" int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
                        accept_len, accept_path, bonus_token);
     E2_HIP(hipGetLastError());
     if (can_sample) {
-        hipLaunchKernelGGL(accept_init_kernel, dim3((2 * B + 255) / 256), dim3(256), 0, st, bars, 2 * B);
+        const int nwords = B * 2 * SAMPLE_WGS * SAMPLE_SLOT;
+        hipLaunchKernelGGL(accept_init_kernel, dim3((nwords + 255) / 256), dim3(256), 0, st, fails, B, slots, nwords);
         E2_HIP(hipGetLastError());
         // all workgroups of a sequence wait for each other, so they must be resident together
         int nwg = 2 * device_cu_count() / B;
         nwg = nwg > SAMPLE_WGS ? SAMPLE_WGS : (nwg < 1 ? 1 : nwg);
+        
         const int per_wg = (V + nwg - 1) / nwg;
         const bool cached = (per_wg + SAMPLE_THREADS - 1) / SAMPLE_THREADS <= SAMPLE_MAXE;
         if (cached)
             hipLaunchKernelGGL(sample_accept_kernel<true>, dim3(nwg, B), dim3(SAMPLE_THREADS), 0, st,
                                nwg, V, N, D, cfg->topk, n_draft_rows(cfg), mode, target_logits, draft_logits, temperature,
-                               u_accept, u_bonus, tree_token, tree_parent, tree_cand, bars, parts,
+                               u_accept, u_bonus, tree_token, tree_parent, tree_cand, fails, slots,
                                accept_len, accept_path, bonus_token);
         else
             hipLaunchKernelGGL(sample_accept_kernel<false>, dim3(nwg, B), dim3(SAMPLE_THREADS), 0, st,
                                nwg, V, N, D, cfg->topk, n_draft_rows(cfg), mode, target_logits, draft_logits, temperature,
-                               u_accept, u_bonus, tree_token, tree_parent, tree_cand, bars, parts,
+                               u_accept, u_bonus, tree_token, tree_parent, tree_cand, fails, slots,
                                accept_len, accept_path, bonus_token);
         E2_HIP(hipGetLastError());
     }

@@ -2,8 +2,7 @@
 // frontier rows, log-softmax, per-row top-k, joint-score accumulation along the path
 // (value equation of Section 4.1, as a sum of logs) and selection of the next frontier.
 //
-// Three kernels per pass:
-//   pack_h_kernel       frontier hidden states -> MFMA operand order (tiny)
+// Two kernels per pass:
 //   lmhead_kernel       streams W once from HBM; per workgroup and frontier row it
 //                       emits a partial (max, sum-exp, top-k) over the vocab rows it saw
 //   expand_merge_kernel merges the partials, appends the k children per row with their
@@ -30,26 +29,6 @@ constexpr int LM_STAGE = LM_ROWS * LM_RS;    // bytes of LDS per wave (4 waves: 
 constexpr int LM_LOADS = LM_ROWS * LM_CHUNK / 1024;   // 16-byte loads per lane per stage
 constexpr int LM_GMAX = 1024;                // upper bound on workgroups (partials per row)
 
-__global__ void pack_h_kernel(const uint8_t* __restrict__ H, int64_t seq_stride_bytes, int row_bytes,
-                              int M, int F, u32x4* __restrict__ Hp, unsigned* __restrict__ done_count, int B) {
-    const int nfrag = row_bytes / 64;
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-    if (blockIdx.y == 0)                                // counters of the merge kernel's last-arrival test
-        for (int i = gid; i < B; i += gridDim.x * blockDim.x) done_count[i] = 0u;
-    const int fi = gid >> 6, lane = gid & 63;
-    if (fi >= nfrag) return;
-    const int mblk = blockIdx.y;
-    const int f = lane & 15, g = lane >> 4;
-    const int m = mblk * 16 + f;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (m < M) {
-        const int b = m / F, s = m - b * F;
-        const uint8_t* src = H + (int64_t)b * seq_stride_bytes + (int64_t)s * row_bytes + fi * 64 + g * 16;
-        v = *reinterpret_cast<const u32x4*>(src);
-    }
-    Hp[((size_t)mblk * nfrag + fi) * 64 + lane] = v;
-}
-
 template <int KC>
 __device__ __forceinline__ void list_insert(float x, int v, float (&val)[KC], int (&idx)[KC]) {
     // ids arrive in increasing order within a lane, so a strict comparison keeps the lower id first
@@ -69,15 +48,14 @@ __device__ __forceinline__ void list_insert(float x, int v, float (&val)[KC], in
 template <bool BF16, int KC>
 __global__ __launch_bounds__(LM_THREADS, 2)
 void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
-                   const u32x4* __restrict__ Hp, int M, int F,
-                   float* __restrict__ part_ms, float* __restrict__ part_val, int* __restrict__ part_idx,
+                   const uint8_t* __restrict__ Hraw, int64_t h_seq_bytes, int M, int F, int B,
+                   unsigned* __restrict__ done_count, float* __restrict__ part_ms, float* __restrict__ part_val, int* __restrict__ part_idx,
                    float* __restrict__ logits_out, int logit_rows_per_seq, int logit_row_base) {
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m16 = lane & 15, g = lane >> 4;          // MFMA lane coordinates
     const int r_in = lane >> 4, c16 = lane & 15;       // load coordinates: 4 rows x 256 B per instruction
     const int G = gridDim.x, mblk = blockIdx.y;
-    const int nfrag = row_bytes >> 6;
     const int wave_bytes = row_bytes >> 2;             // K bytes owned by this wave
     const int nst = wave_bytes / LM_CHUNK;
     const int ntask = (V + LM_ROWS - 1) / LM_ROWS;
@@ -87,17 +65,26 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     const int mrow = mblk * 16 + m16;                  // frontier row owned by this lane
     const bool row_valid = mrow < M;
 
+    if (blockIdx.x == 0 && mblk == 0)                   // counters of the merge kernel's last-arrival test
+        for (int i = tid; i < B; i += LM_THREADS) done_count[i] = 0u;
+
     float run_m = -INFINITY, run_s = 0.f;
     float tval[KC];
     int tidx[KC];
 #pragma unroll
     for (int j = 0; j < KC; ++j) { tval[j] = -INFINITY; tidx[j] = INT_MAX; }
 
+    // raw logits (optional) leave through an LDS transpose: wave w stores frontier rows 4w..4w+3,
+    // one row per quarter-wave, 256 contiguous bytes each
     float* lrow = nullptr;
-    if (logits_out != nullptr && row_valid) {
-        const int b = mrow / F, s = mrow - b * F;
-        lrow = logits_out + ((size_t)b * logit_rows_per_seq + logit_row_base + s) * (size_t)V;
+    {
+        const int wr = mblk * 16 + w * 4 + r_in;
+        if (logits_out != nullptr && wr < M) {
+            const int b = wr / F, s = wr - b * F;
+            lrow = logits_out + ((size_t)b * logit_rows_per_seq + logit_row_base + s) * (size_t)V;
+        }
     }
+    constexpr int LT_RS = 68;                          // floats per row of the transpose tile (64 + pad)
 
     u32x4 R[LM_LOADS];
     auto issue = [&](int it) {
@@ -116,7 +103,29 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) acc[nb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    if (total > 0) issue(0);
+    // H fragments are fetched one stage ahead and *before* the next stage's W loads are issued:
+    // loads retire in order, so a younger H load would otherwise make the MFMAs wait for the
+    // whole W prefetch.
+    auto frag0 = [&](int it) {
+        const int st = it - (it / nst) * nst;
+        return (w * wave_bytes + st * LM_CHUNK) >> 6;
+    };
+    // H fragments come straight from the caller's H: lane (m16, g) reads 16 bytes at
+    // 64*frag + 16*g of frontier row m16 (rows beyond M are zero)
+    const uint8_t* hrow = nullptr;
+    if (row_valid) {
+        const int b = mrow / F, s = mrow - b * F;
+        hrow = Hraw + (int64_t)b * h_seq_bytes + (int64_t)s * row_bytes + g * 16;
+    }
+    auto load_h = [&](int fi) -> u32x4 {
+        return hrow ? *reinterpret_cast<const u32x4*>(hrow + (size_t)fi * 64) : u32x4{0u, 0u, 0u, 0u};
+    };
+    u32x4 hf[LM_CHUNK / 64], hn[LM_CHUNK / 64];
+    if (total > 0) {
+#pragma unroll
+        for (int t = 0; t < LM_CHUNK / 64; ++t) hn[t] = load_h(frag0(0) + t);
+        issue(0);
+    }
     for (int it = 0; it < total; ++it) {
         const int ti = it / nst;
         const int st = it - ti * nst;
@@ -124,14 +133,16 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
 #pragma unroll
         for (int j = 0; j < LM_LOADS; ++j)
             *reinterpret_cast<u32x4*>(stage + (j * 4 + r_in) * LM_RS + ((c16 ^ ((j * 4 + r_in) & 15)) << 4)) = R[j];
-        __syncthreads();
-        if (it + 1 < total) issue(it + 1);
-
-        const int fi0 = (w * wave_bytes + st * LM_CHUNK) >> 6;
-        u32x4 hf[LM_CHUNK / 64];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");    // stages are wave-private: no workgroup barrier
 #pragma unroll
-        for (int t = 0; t < LM_CHUNK / 64; ++t)
-            hf[t] = Hp[((size_t)mblk * nfrag + fi0 + t) * 64 + lane];
+        for (int t = 0; t < LM_CHUNK / 64; ++t) hf[t] = hn[t];
+        if (it + 1 < total) {
+            const int f1 = frag0(it + 1);
+#pragma unroll
+            for (int t = 0; t < LM_CHUNK / 64; ++t) hn[t] = load_h(f1 + t);
+            issue(it + 1);
+        }
+
 #pragma unroll
         for (int t = 0; t < LM_CHUNK / 64; ++t) {
 #pragma unroll
@@ -149,7 +160,8 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
                 }
             }
         }
-        __syncthreads();                               // all waves are done reading their stage
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (st == nst - 1) __syncthreads();            // the reduction below reuses every wave's stage
 
         if (st == nst - 1) {
             // split-K reduction: wave w collects vocab-row block w from all four waves
@@ -166,15 +178,23 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
             __syncthreads();                           // red aliases the staging buffers
 
             const int vbase = task * LM_ROWS + w * 16 + g * 4;
-            if (row_valid && vbase < V) {
-                if (lrow != nullptr) {
-                    if (vbase + 3 < V && (V & 3) == 0) {
-                        *reinterpret_cast<floatx4*>(lrow + vbase) = x;
+            if (logits_out != nullptr) {               // uniform over the workgroup
+                float* lt = reinterpret_cast<float*>(smem);
+                *reinterpret_cast<floatx4*>(lt + m16 * LT_RS + w * 16 + g * 4) = x;
+                __syncthreads();
+                const floatx4 y = *reinterpret_cast<const floatx4*>(lt + (w * 4 + r_in) * LT_RS + c16 * 4);
+                const int v0 = task * LM_ROWS + c16 * 4;
+                if (lrow != nullptr && v0 < V) {
+                    if (v0 + 3 < V && (V & 3) == 0) {
+                        __builtin_nontemporal_store(y, reinterpret_cast<floatx4*>(lrow + v0));
                     } else {
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) if (vbase + i < V) lrow[vbase + i] = x[i];
+                        for (int i = 0; i < 4; ++i) if (v0 + i < V) lrow[v0 + i] = y[i];
                     }
                 }
+                __syncthreads();                       // lt aliases the staging buffers
+            }
+            if (row_valid && vbase < V) {
                 float xm = x[0];
 #pragma unroll
                 for (int i = 1; i < 4; ++i) if (vbase + i < V) xm = fmaxf(xm, x[i]);
@@ -190,51 +210,69 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
         }
     }
 
-    // ---- merge the 16 per-lane states of each frontier row (4 lane groups x 4 waves) ----
+    // ---- merge the 16 per-lane states of each frontier row: the 4 lane groups of a wave by
+    // shuffles, then the 4 waves through LDS; all 16 rows in parallel ----
+    auto merge_groups = [&]() {
+        // (max, sum-exp) over lanes m16, m16+16, m16+32, m16+48
+#pragma unroll
+        for (int o = 16; o <= 32; o <<= 1) {
+            const float om = __shfl_xor(run_m, o, 64), os = __shfl_xor(run_s, o, 64);
+            const float nm = fmaxf(run_m, om);
+            const float a = run_m > -INFINITY ? run_s * __expf(run_m - nm) : 0.f;
+            const float c = om > -INFINITY ? os * __expf(om - nm) : 0.f;
+            run_m = nm;
+            run_s = a + c;
+        }
+        // KC rounds of arg-best over the four list heads; every lane keeps the merged list
+        float mv[KC]; int mi[KC];
+#pragma unroll
+        for (int r = 0; r < KC; ++r) {
+            float bv = tval[0]; int bi = tidx[0];
+#pragma unroll
+            for (int o = 16; o <= 32; o <<= 1) {
+                const float ov = __shfl_xor(bv, o, 64);
+                const int oi = __shfl_xor(bi, o, 64);
+                if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            }
+            if (tval[0] == bv && tidx[0] == bi) {
+#pragma unroll
+                for (int q = 0; q < KC - 1; ++q) { tval[q] = tval[q + 1]; tidx[q] = tidx[q + 1]; }
+                tval[KC - 1] = -INFINITY; tidx[KC - 1] = INT_MAX;
+            }
+            mv[r] = bv; mi[r] = bi;
+        }
+#pragma unroll
+        for (int r = 0; r < KC; ++r) { tval[r] = mv[r]; tidx[r] = mi[r]; }
+    };
     __syncthreads();
-    float* l_val = reinterpret_cast<float*>(smem);                 // [16 rows][16 src][KC]
-    int* l_idx = reinterpret_cast<int*>(smem + 16 * 16 * KC * 4);
-    float* l_ms = reinterpret_cast<float*>(smem + 2 * 16 * 16 * KC * 4);   // [16][16][2]
-    {
-        const int src = w * 4 + g;
-        const int base = (m16 * 16 + src) * KC;
+    merge_groups();
+    float* l_val = reinterpret_cast<float*>(smem);                     // [4 waves][16 rows][KC]
+    int* l_idx = reinterpret_cast<int*>(smem + 4 * 16 * KC * 4);
+    float* l_ms = reinterpret_cast<float*>(smem + 2 * 4 * 16 * KC * 4);   // [4][16][2]
+    if (g == 0) {
+        const int base = (w * 16 + m16) * KC;
 #pragma unroll
         for (int j = 0; j < KC; ++j) { l_val[base + j] = tval[j]; l_idx[base + j] = tidx[j]; }
-        l_ms[(m16 * 16 + src) * 2 + 0] = run_m;
-        l_ms[(m16 * 16 + src) * 2 + 1] = run_s;
+        l_ms[(w * 16 + m16) * 2 + 0] = run_m;
+        l_ms[(w * 16 + m16) * 2 + 1] = run_s;
     }
     __syncthreads();
-    if (tid < 16) {
-        const int f = tid;
-        const int prow = mblk * 16 + f;                // partial row index (padded rows included)
-        float mx = -INFINITY;
-        for (int s = 0; s < 16; ++s) mx = fmaxf(mx, l_ms[(f * 16 + s) * 2]);
-        float sm = 0.f;
-        for (int s = 0; s < 16; ++s) {
-            const float ms = l_ms[(f * 16 + s) * 2];
-            if (ms > -INFINITY) sm += l_ms[(f * 16 + s) * 2 + 1] * __expf(ms - mx);
-        }
-        part_ms[((size_t)prow * G + blockIdx.x) * 2 + 0] = mx;
-        part_ms[((size_t)prow * G + blockIdx.x) * 2 + 1] = sm;
-        // 16-way merge of sorted lists: heads in registers, one LDS read per output
-        float hv[16]; int hi[16]; int hp[16];
+    if (w == 0) {
+        // lane (g, m16) takes wave g's list for row m16; the same four-way merge finishes the job
+        const int base = (g * 16 + m16) * KC;
 #pragma unroll
-        for (int s = 0; s < 16; ++s) { hv[s] = l_val[(f * 16 + s) * KC]; hi[s] = l_idx[(f * 16 + s) * KC]; hp[s] = 0; }
-        for (int j = 0; j < KC; ++j) {
-            int bs = 0; float bv = hv[0]; int bi = hi[0];
+        for (int j = 0; j < KC; ++j) { tval[j] = l_val[base + j]; tidx[j] = l_idx[base + j]; }
+        run_m = l_ms[(g * 16 + m16) * 2 + 0];
+        run_s = l_ms[(g * 16 + m16) * 2 + 1];
+        merge_groups();
+        if (g == 0) {
+            const size_t prow = (size_t)mblk * 16 + m16;               // padded rows included
+            part_ms[(prow * G + blockIdx.x) * 2 + 0] = run_m;
+            part_ms[(prow * G + blockIdx.x) * 2 + 1] = run_s;
 #pragma unroll
-            for (int s = 1; s < 16; ++s)
-                if (ranks_before(hv[s], hi[s], bv, bi)) { bv = hv[s]; bi = hi[s]; bs = s; }
-            part_val[((size_t)prow * G + blockIdx.x) * KC + j] = bv;
-            part_idx[((size_t)prow * G + blockIdx.x) * KC + j] = bi;
-#pragma unroll
-            for (int s = 0; s < 16; ++s) {
-                if (s == bs) {
-                    const int np = hp[s] + 1;
-                    hp[s] = np;
-                    if (np < KC) { hv[s] = l_val[(f * 16 + s) * KC + np]; hi[s] = l_idx[(f * 16 + s) * KC + np]; }
-                    else { hv[s] = -INFINITY; hi[s] = INT_MAX; }
-                }
+            for (int j = 0; j < KC; ++j) {
+                part_val[(prow * G + blockIdx.x) * KC + j] = tval[j];
+                part_idx[(prow * G + blockIdx.x) * KC + j] = tidx[j];
             }
         }
     }
@@ -258,42 +296,12 @@ __device__ __forceinline__ void wave_best(double& v, int& i) {
     }
 }
 
-// One workgroup per (frontier row, sequence).  Threads stride over the row's G*KC partial
-// candidates keeping a sorted top-KC each; waves, then the workgroup, reduce those lists by
-// repeated arg-best.  The workgroup that finishes last for a sequence (a counter in the
-// workspace, zeroed by pack_h_kernel) also selects the next frontier.
-constexpr int MG_THREADS = 256;
-
-template <int KC>
-__device__ __forceinline__ void full_insert(float x, int v, float (&val)[KC], int (&idx)[KC]) {
-    if (ranks_before(x, v, val[KC - 1], idx[KC - 1])) {
-        val[KC - 1] = x; idx[KC - 1] = v;
-#pragma unroll
-        for (int q = KC - 1; q > 0; --q) {
-            if (ranks_before(val[q], idx[q], val[q - 1], idx[q - 1])) {
-                float tv = val[q]; val[q] = val[q - 1]; val[q - 1] = tv;
-                int ti = idx[q]; idx[q] = idx[q - 1]; idx[q - 1] = ti;
-            }
-        }
-    }
-}
-
-// k rounds of wave-wide arg-best over the lanes' sorted lists; lane r ends up holding the
-// r-th best (value, index) of the wave in (out_v, out_i)
-template <int KC>
-__device__ __forceinline__ void wave_topk(float (&val)[KC], int (&idx)[KC], int k, int lane, float& out_v, int& out_i) {
-    out_v = -INFINITY; out_i = INT_MAX;
-    for (int r = 0; r < k; ++r) {
-        float bv = val[0]; int bi = idx[0];
-        wave_best(bv, bi);
-        if (val[0] == bv && idx[0] == bi) {            // the winner pops its head
-#pragma unroll
-            for (int q = 0; q < KC - 1; ++q) { val[q] = val[q + 1]; idx[q] = idx[q + 1]; }
-            val[KC - 1] = -INFINITY; idx[KC - 1] = INT_MAX;
-        }
-        if (lane == r) { out_v = bv; out_i = bi; }
-    }
-}
+// One workgroup per (frontier row, sequence).  Each of the G partial lists is sorted, so an
+// entry can only be in the row's top k if its list's head is among the k best heads: those
+// heads are found by arg-best rounds (per wave, then over the waves' winners), and the at
+// most k*KC entries of the surviving lists are ranked by counting.  The workgroup that finishes last for a sequence (a counter in the workspace, zeroed
+// by lmhead_kernel) also selects the next frontier.
+constexpr int MG_THREADS = 1024;
 
 template <int KC>
 __global__ __launch_bounds__(MG_THREADS)
@@ -306,84 +314,139 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G,
     constexpr int NW = MG_THREADS / 64;
     __shared__ float s_f[NW];
     __shared__ double s_d[NW];
-    __shared__ float s_cv[NW * EAGLE2_MAX_TOPK];
-    __shared__ int s_ci[NW * EAGLE2_MAX_TOPK];
+    __shared__ float s_hv[LM_GMAX];                     // list heads
+    __shared__ int s_hi[LM_GMAX];
+    __shared__ float s_wv[(MG_THREADS / 64) * EAGLE2_MAX_TOPK];   // per-wave winners: value, token, list
+    __shared__ int s_wi[(MG_THREADS / 64) * EAGLE2_MAX_TOPK], s_wl[(MG_THREADS / 64) * EAGLE2_MAX_TOPK];
+    __shared__ int s_live[EAGLE2_MAX_TOPK];
+    __shared__ float s_cv[EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK];
+    __shared__ int s_ci[EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK];
+    __shared__ float s_ov[EAGLE2_MAX_TOPK];
+    __shared__ int s_oi[EAGLE2_MAX_TOPK];
     __shared__ int s_last;
     const int slot = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int base = d == 0 ? 0 : k + (d - 1) * k * k;
     const size_t prow = (size_t)b * F + slot;
-
-    // log-sum-exp over the G partial (max, sum) pairs
     const float* ms = part_ms + prow * G * 2;
-    float mloc = -INFINITY;
-    for (int p = tid; p < G; p += MG_THREADS) mloc = fmaxf(mloc, ms[p * 2]);
-    mloc = wave_max(mloc);
+    const float* pv = part_val + prow * G * KC;
+    const int* pi = part_idx + prow * G * KC;
+
+    // loads first: heads of the G lists and the (max, sum-exp) pairs
+    float my_m = -INFINITY, my_s = 0.f;
+    if (tid < EAGLE2_MAX_TOPK) { s_ov[tid] = -INFINITY; s_oi[tid] = 0; }
+    if (tid < G) {
+        s_hv[tid] = pv[(size_t)tid * KC];
+        s_hi[tid] = pi[(size_t)tid * KC];
+        my_m = ms[tid * 2];
+        my_s = ms[tid * 2 + 1];
+    }
+    // log-sum-exp over the G partial pairs
+    float mloc = wave_max(my_m);
     if (lane == 0) s_f[wave] = mloc;
     __syncthreads();
     float mx = s_f[0];
 #pragma unroll
     for (int w = 1; w < NW; ++w) mx = fmaxf(mx, s_f[w]);
-    double sloc = 0.0;
-    for (int p = tid; p < G; p += MG_THREADS) {
-        const float mp = ms[p * 2];
-        if (mp > -INFINITY) sloc += (double)ms[p * 2 + 1] * exp((double)mp - (double)mx);
-    }
+    double sloc = my_m > -INFINITY ? (double)my_s * exp((double)my_m - (double)mx) : 0.0;
     sloc = wave_sum(sloc);
     if (lane == 0) s_d[wave] = sloc;
 
-    // per-thread top-KC over its share of the candidates (loads batched four at a time)
-    float tval[KC]; int tidx[KC];
+    // the k best heads: arg-best rounds inside every wave (one head per lane), then wave 0
+    // repeats them over the waves' winners.  The list number travels with each head.
+    const int nlive = G < k ? G : k;
+    {
+        float hv = tid < G ? s_hv[tid] : -INFINITY;
+        int hi = tid < G ? s_hi[tid] : INT_MAX;
+        const int nwv = (G + 63) >> 6;                      // waves that hold heads
+        if (wave < nwv) {
+            for (int r = 0; r < nlive; ++r) {
+                float bv = hv; int bi = hi; int bl = tid;
 #pragma unroll
-    for (int j = 0; j < KC; ++j) { tval[j] = -INFINITY; tidx[j] = INT_MAX; }
-    const float* pv = part_val + prow * G * KC;
-    const int* pi = part_idx + prow * G * KC;
-    const int n = G * KC;
-    for (int j0 = tid; j0 < n; j0 += 4 * MG_THREADS) {
-        float xv[4]; int xi[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int j = j0 + u * MG_THREADS;
-            xv[u] = j < n ? pv[j] : -INFINITY;
-            xi[u] = j < n ? pi[j] : INT_MAX;
+                for (int o = 32; o > 0; o >>= 1) {
+                    const float ov = __shfl_xor(bv, o, 64);
+                    const int oi = __shfl_xor(bi, o, 64);
+                    const int ol = __shfl_xor(bl, o, 64);
+                    if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; bl = ol; }
+                }
+                if (bl == tid) { hv = -INFINITY; hi = INT_MAX; }       // the winner retires
+                if (lane == 0) { s_wv[wave * EAGLE2_MAX_TOPK + r] = bv; s_wi[wave * EAGLE2_MAX_TOPK + r] = bi; s_wl[wave * EAGLE2_MAX_TOPK + r] = bl; }
+            }
         }
+        __syncthreads();
+        if (wave == 0) {
+            // nwv * nlive <= 16 * 16 winners: up to four per lane
+            float cv[4]; int ci[4], cl[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) full_insert<KC>(xv[u], xi[u], tval, tidx);
+            for (int u = 0; u < 4; ++u) {
+                const int e = lane + u * 64;
+                const int w2 = e / nlive, r2 = e - w2 * nlive;
+                const bool ok = w2 < nwv;
+                cv[u] = ok ? s_wv[w2 * EAGLE2_MAX_TOPK + r2] : -INFINITY;
+                ci[u] = ok ? s_wi[w2 * EAGLE2_MAX_TOPK + r2] : INT_MAX;
+                cl[u] = ok ? s_wl[w2 * EAGLE2_MAX_TOPK + r2] : -1;
+            }
+            for (int r = 0; r < nlive; ++r) {
+                float bv = cv[0]; int bi = ci[0]; int bl = cl[0];
+#pragma unroll
+                for (int u = 1; u < 4; ++u) if (ranks_before(cv[u], ci[u], bv, bi)) { bv = cv[u]; bi = ci[u]; bl = cl[u]; }
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) {
+                    const float ov = __shfl_xor(bv, o, 64);
+                    const int oi = __shfl_xor(bi, o, 64);
+                    const int ol = __shfl_xor(bl, o, 64);
+                    if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; bl = ol; }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) if (cl[u] == bl) { cv[u] = -INFINITY; ci[u] = INT_MAX; cl[u] = -1; }
+                if (lane == 0) s_live[r] = bl < 0 ? 0 : bl;
+            }
+        }
     }
-    float wv; int wi;
-    wave_topk<KC>(tval, tidx, k, lane, wv, wi);
-    if (lane < k) { s_cv[wave * k + lane] = wv; s_ci[wave * k + lane] = wi; }
     __syncthreads();
-    double log_sum = 0.0;
-    if (wave == 0) {
+    // gather the surviving lists: nlive * KC candidates
+    const int ncand = nlive * KC;
+    if (tid < ncand) {
+        int l = s_live[tid / KC];
+        if (l < 0 || l >= G) l = 0;
+        const int j = tid - (tid / KC) * KC;
+        s_cv[tid] = pv[(size_t)l * KC + j];
+        s_ci[tid] = pi[(size_t)l * KC + j];
+    }
+    __syncthreads();
+    if (tid < ncand) {
+        const float cv = s_cv[tid];
+        const int ci = s_ci[tid];
+        int r = 0;
+        for (int j = 0; j < ncand; ++j) r += ranks_before(s_cv[j], s_ci[j], cv, ci) ? 1 : 0;
+        if (r < k && ci != INT_MAX) { s_ov[r] = cv; s_oi[r] = ci; }
+    }
+    __syncthreads();
+    if (tid < k) {
         double tot = 0.0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) tot += s_d[w];
-        log_sum = log(tot);
-        // NW*k <= 64 candidates, one per lane
-        float cv[1] = {lane < NW * k ? s_cv[lane] : -INFINITY};
-        int ci[1] = {lane < NW * k ? s_ci[lane] : INT_MAX};
-        float my_x; int my_tok;
-        wave_topk<1>(cv, ci, k, lane, my_x, my_tok);
-        if (lane < k) {
-            const int cid = base + slot * k + lane;
-            int par = d == 0 ? -1 : frontier[((size_t)b * D + d) * k + slot];
-            if (d > 0 && (par < 0 || par >= C)) par = 0;   // garbage in the caller's frontier stays in bounds
-            const double ps = d == 0 ? 0.0 : cand_score[(size_t)b * C + par];
-            cand_token[(size_t)b * C + cid] = my_tok;
-            cand_score[(size_t)b * C + cid] = ps + (((double)my_x - (double)mx) - log_sum);
-            cand_parent[(size_t)b * C + cid] = par;
-        }
+        const double log_sum = log(tot);
+        const int cid = base + slot * k + tid;
+        int par = d == 0 ? -1 : frontier[((size_t)b * D + d) * k + slot];
+        if (d > 0 && (par < 0 || par >= C)) par = 0;       // garbage in the caller's frontier stays in bounds
+        const double ps = d == 0 ? 0.0 : cand_score[(size_t)b * C + par];
+        const double sc = ps + (((double)s_ov[tid] - (double)mx) - log_sum);
+        cand_token[(size_t)b * C + cid] = s_oi[tid];
+        cand_parent[(size_t)b * C + cid] = par;
+        // The score is also read by the workgroup that picks the next frontier, possibly on
+        // another XCD: store it at device scope and wait for the acknowledgement, instead of a
+        // device-scope fence (which writes back and invalidates the whole L2).
+        __hip_atomic_store(cand_score + (size_t)b * C + cid, sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     }
     if (d + 1 >= D) return;
 
     // the last workgroup of this sequence picks the next frontier
     __syncthreads();
     if (tid == 0) {
-        __threadfence();
-        const unsigned prev = atomicAdd(done_count + b, 1u);
+        const unsigned prev = __hip_atomic_fetch_add(done_count + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = prev == (unsigned)(F - 1) ? 1 : 0;
-        __threadfence();
     }
     __syncthreads();
     if (!s_last || wave != 0) return;
@@ -411,20 +474,18 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G,
 
 static int lm_grid(const eagle2_cfg* cfg) {
     const int ntask = (cfg->vocab + LM_ROWS - 1) / LM_ROWS;
-    int g = 2 * device_cu_count();
+    int g = 2 * device_cu_count();                     // two resident workgroups per compute unit
     if (g > LM_GMAX) g = LM_GMAX;
     if (g > ntask) g = ntask;
     return g < 1 ? 1 : g;
 }
 
-struct ExpandWs { size_t hp, ms, val, idx, cnt, total; };
+struct ExpandWs { size_t ms, val, idx, cnt, total; };
 static ExpandWs expand_layout(const eagle2_cfg* cfg) {
-    const size_t row_bytes = (size_t)cfg->hidden * elem_size(cfg);
     const size_t mmax = (size_t)cfg->batch * cfg->topk;
     const size_t mblks = (mmax + 15) / 16;
     ExpandWs w;
-    w.hp = 0;
-    w.ms = round_up(mblks * row_bytes * 16, 256);
+    w.ms = 0;
     w.val = w.ms + round_up(mblks * 16 * LM_GMAX * 2 * sizeof(float), 256);
     w.idx = w.val + round_up(mblks * 16 * LM_GMAX * EAGLE2_MAX_TOPK * sizeof(float), 256);
     w.cnt = w.idx + round_up(mblks * 16 * LM_GMAX * EAGLE2_MAX_TOPK * sizeof(int), 256);
@@ -442,18 +503,11 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
     const int mblks = (M + 15) / 16;
     const int G = lm_grid(cfg);
     const ExpandWs L = expand_layout(cfg);
-    u32x4* Hp = reinterpret_cast<u32x4*>(ws + L.hp);
     float* part_ms = reinterpret_cast<float*>(ws + L.ms);
     float* part_val = reinterpret_cast<float*>(ws + L.val);
     int* part_idx = reinterpret_cast<int*>(ws + L.idx);
     unsigned* done_count = reinterpret_cast<unsigned*>(ws + L.cnt);
     const int64_t stride_el = h_seq_stride == 0 ? (int64_t)F * cfg->hidden : h_seq_stride;
-
-    const int nfrag = row_bytes / 64;
-    dim3 pg((nfrag * 64 + 255) / 256, mblks);
-    hipLaunchKernelGGL(pack_h_kernel, pg, dim3(256), 0, st, reinterpret_cast<const uint8_t*>(H),
-                       stride_el * elem_size(cfg), row_bytes, M, F, Hp, done_count, cfg->batch);
-    E2_HIP(hipGetLastError());
 
     const size_t smem = 4 * LM_STAGE;
     static_assert(4 * LM_STAGE >= 2 * 16 * 16 * EAGLE2_MAX_TOPK * 4 + 16 * 16 * 2 * 4, "merge area must fit");
@@ -461,7 +515,8 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
     const int row_base = d == 0 ? 0 : 1 + (d - 1) * k;
     timing_begin(0, st);
     hipLaunchKernelGGL((lmhead_kernel<BF16, KC>), dim3(G, mblks), dim3(LM_THREADS), smem, st,
-                       reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab, Hp, M, F,
+                       reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab,
+                       reinterpret_cast<const uint8_t*>(H), stride_el * elem_size(cfg), M, F, cfg->batch, done_count,
                        part_ms, part_val, part_idx, draft_logits, R, row_base);
     timing_end(0, st);
     E2_HIP(hipGetLastError());
