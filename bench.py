@@ -23,9 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM traffic per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (see profiles/); None until a counter run for this workload has been recorded.
-MEASURED_TRAFFIC_BYTES = {3: None}
+# HBM bytes per LM-head launch (fetch + write) from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE),
+# each scaled by what the counter reads for a plain 1 GiB copy; the summary is profiles/round_cfg3_llama3_8b.md.
+# None for workloads without a recorded counter run.
+MEASURED_TRAFFIC_BYTES = {3: 1057173366}
 
 
 def algorithmic_bytes(cfg, plens):
@@ -45,6 +46,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures the one-GPU hot path only; --gpus must be 1 "
@@ -58,6 +61,15 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.full((n,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": n, "copies": 5}))
+        return
     cfg = wl.get_config(args.config)
     B, D, k, N, V = cfg.batch, cfg.depth, cfg.topk, cfg.n_tree, cfg.vocab
 
