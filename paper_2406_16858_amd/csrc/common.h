@@ -49,20 +49,52 @@ typedef unsigned u32x4   __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2   __attribute__((ext_vector_type(2)));
 typedef __bf16   bf16x8  __attribute__((ext_vector_type(8)));
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+// ---- wave-wide reductions on the DPP data path -------------------------------------------
+// Four symmetric exchanges inside each row of 16 lanes (lane^1, lane^2, mirror within 8,
+// mirror within 16) leave every lane of a row with the row's result; the four row results
+// are then read with v_readlane and combined in a fixed order.  No LDS traffic, unlike
+// __shfl_xor.  All callers run with full waves in wave-uniform control flow.
+constexpr int DPP_XOR1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;
+constexpr int DPP_MIRROR = 0x140;
+
+template <int CTRL> __device__ __forceinline__ int dpp_mov(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
 }
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+template <int CTRL> __device__ __forceinline__ double dpp_mov(double v) {
+    const int lo = dpp_mov<CTRL>(__double2loint(v)), hi = dpp_mov<CTRL>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ int read_lane(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
+__device__ __forceinline__ float read_lane(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
+__device__ __forceinline__ double read_lane(double v, int l) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l), __builtin_amdgcn_readlane(__double2loint(v), l));
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp_mov<DPP_XOR1>(v));
+    v = fmaxf(v, dpp_mov<DPP_XOR2>(v));
+    v = fmaxf(v, dpp_mov<DPP_HALF_MIRROR>(v));
+    v = fmaxf(v, dpp_mov<DPP_MIRROR>(v));
+    return fmaxf(fmaxf(read_lane(v, 0), read_lane(v, 16)), fmaxf(read_lane(v, 32), read_lane(v, 48)));
 }
 __device__ __forceinline__ double wave_maxd(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
-    return v;
+    v = fmax(v, dpp_mov<DPP_XOR1>(v));
+    v = fmax(v, dpp_mov<DPP_XOR2>(v));
+    v = fmax(v, dpp_mov<DPP_HALF_MIRROR>(v));
+    v = fmax(v, dpp_mov<DPP_MIRROR>(v));
+    return fmax(fmax(read_lane(v, 0), read_lane(v, 16)), fmax(read_lane(v, 32), read_lane(v, 48)));
+}
+__device__ __forceinline__ double wave_sum(double v) {
+    v += dpp_mov<DPP_XOR1>(v);
+    v += dpp_mov<DPP_XOR2>(v);
+    v += dpp_mov<DPP_HALF_MIRROR>(v);
+    v += dpp_mov<DPP_MIRROR>(v);
+    return ((read_lane(v, 0) + read_lane(v, 16)) + read_lane(v, 32)) + read_lane(v, 48);
 }
 // candidate order: higher value first, then lower index
 __device__ __forceinline__ bool ranks_before(float va, int ia, float vb, int ib) {
@@ -71,6 +103,29 @@ __device__ __forceinline__ bool ranks_before(float va, int ia, float vb, int ib)
 __device__ __forceinline__ bool ranks_before(double va, int ia, double vb, int ib) {
     return va > vb || (va == vb && ia < ib);
 }
+// every lane ends with the wave's best (value, index) and the payload that travels with it
+template <typename T>
+__device__ __forceinline__ void wave_best(T& v, int& i, int& pay) {
+#define E2_BEST_STEP(CTRL)                                                                     \
+    {                                                                                          \
+        const T ov = dpp_mov<CTRL>(v);                                                         \
+        const int oi = dpp_mov<CTRL>(i), op = dpp_mov<CTRL>(pay);                              \
+        if (ranks_before(ov, oi, v, i)) { v = ov; i = oi; pay = op; }                          \
+    }
+    E2_BEST_STEP(DPP_XOR1) E2_BEST_STEP(DPP_XOR2) E2_BEST_STEP(DPP_HALF_MIRROR) E2_BEST_STEP(DPP_MIRROR)
+#undef E2_BEST_STEP
+    T bv = read_lane(v, 0);
+    int bi = read_lane(i, 0), bp = read_lane(pay, 0);
+#pragma unroll
+    for (int r = 1; r < 4; ++r) {
+        const T rv = read_lane(v, 16 * r);
+        const int ri = read_lane(i, 16 * r), rp = read_lane(pay, 16 * r);
+        if (ranks_before(rv, ri, bv, bi)) { bv = rv; bi = ri; bp = rp; }
+    }
+    v = bv; i = bi; pay = bp;
+}
+template <typename T>
+__device__ __forceinline__ void wave_best(T& v, int& i) { int pay = 0; wave_best(v, i, pay); }
 #endif
 
 }  // namespace eagle2

@@ -278,30 +278,27 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     }
 }
 
-// butterfly arg-best over a wave: every lane ends with the best (value, index)
-__device__ __forceinline__ void wave_best(float& v, int& i) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const float ov = __shfl_xor(v, o, 64);
-        const int oi = __shfl_xor(i, o, 64);
-        if (ranks_before(ov, oi, v, i)) { v = ov; i = oi; }
-    }
-}
-__device__ __forceinline__ void wave_best(double& v, int& i) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const double ov = __shfl_xor(v, o, 64);
-        const int oi = __shfl_xor(i, o, 64);
-        if (ranks_before(ov, oi, v, i)) { v = ov; i = oi; }
-    }
-}
-
 // One workgroup per (frontier row, sequence).  Each of the G partial lists is sorted, so an
-// entry can only be in the row's top k if its list's head is among the k best heads: those
-// heads are found by arg-best rounds (per wave, then over the waves' winners), and the at
-// most k*KC entries of the surviving lists are ranked by counting.  The workgroup that finishes last for a sequence (a counter in the workspace, zeroed
+// entry can only be in the row's top k if its list's head is among the k best heads.  Heads,
+// surviving entries (<= k*KC) and new candidates (frontier) are all ranked by counting.  The workgroup that finishes last for a sequence (a counter in the workspace, zeroed
 // by lmhead_kernel) also selects the next frontier.
 constexpr int MG_THREADS = 1024;
+
+// number of the n LDS entries that precede (v, i) in the order "higher value, then lower
+// index"; the reads are issued eight at a time so the loop is not a chain of LDS latencies
+template <typename T>
+__device__ __forceinline__ int count_before(const T* sv, const int* si, int n, T v, int i) {
+    int r = 0, j = 0;
+    for (; j + 8 <= n; j += 8) {
+        T a[8]; int c[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { a[u] = sv[j + u]; c[u] = si[j + u]; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) r += ranks_before(a[u], c[u], v, i) ? 1 : 0;
+    }
+    for (; j < n; ++j) r += ranks_before(sv[j], si[j], v, i) ? 1 : 0;
+    return r;
+}
 
 template <int KC>
 __global__ __launch_bounds__(MG_THREADS)
@@ -323,6 +320,8 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G,
     __shared__ int s_ci[EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK];
     __shared__ float s_ov[EAGLE2_MAX_TOPK];
     __shared__ int s_oi[EAGLE2_MAX_TOPK];
+    __shared__ double s_fs[EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK];   // new candidates' scores (frontier selection)
+    __shared__ int s_fi[EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK];
     __shared__ int s_last;
     const int slot = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -352,55 +351,27 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G,
     sloc = wave_sum(sloc);
     if (lane == 0) s_d[wave] = sloc;
 
-    // the k best heads: arg-best rounds inside every wave (one head per lane), then wave 0
-    // repeats them over the waves' winners.  The list number travels with each head.
+    // the k best heads, by counting instead of sorting: inside every wave each head counts the
+    // heads of the other 63 lanes that precede it (broadcast with v_readlane, no LDS); the at
+    // most k survivors per wave are then ranked against each other through LDS
     const int nlive = G < k ? G : k;
+    const int nwv = (G + 63) >> 6;                          // waves that hold heads
+    if (tid < NW * EAGLE2_MAX_TOPK) { s_wv[tid] = -INFINITY; s_wi[tid] = INT_MAX; s_wl[tid] = 0; }
+    __syncthreads();
+    if (wave < nwv) {
+        const float hv = tid < G ? s_hv[tid] : -INFINITY;
+        const int hi = tid < G ? s_hi[tid] : INT_MAX;
+        int r = 0;
+#pragma unroll
+        for (int j = 0; j < 64; ++j) r += ranks_before(read_lane(hv, j), read_lane(hi, j), hv, hi) ? 1 : 0;
+        if (r < nlive && tid < G) { s_wv[wave * nlive + r] = hv; s_wi[wave * nlive + r] = hi; s_wl[wave * nlive + r] = tid; }
+    }
+    __syncthreads();
     {
-        float hv = tid < G ? s_hv[tid] : -INFINITY;
-        int hi = tid < G ? s_hi[tid] : INT_MAX;
-        const int nwv = (G + 63) >> 6;                      // waves that hold heads
-        if (wave < nwv) {
-            for (int r = 0; r < nlive; ++r) {
-                float bv = hv; int bi = hi; int bl = tid;
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) {
-                    const float ov = __shfl_xor(bv, o, 64);
-                    const int oi = __shfl_xor(bi, o, 64);
-                    const int ol = __shfl_xor(bl, o, 64);
-                    if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; bl = ol; }
-                }
-                if (bl == tid) { hv = -INFINITY; hi = INT_MAX; }       // the winner retires
-                if (lane == 0) { s_wv[wave * EAGLE2_MAX_TOPK + r] = bv; s_wi[wave * EAGLE2_MAX_TOPK + r] = bi; s_wl[wave * EAGLE2_MAX_TOPK + r] = bl; }
-            }
-        }
-        __syncthreads();
-        if (wave == 0) {
-            // nwv * nlive <= 16 * 16 winners: up to four per lane
-            float cv[4]; int ci[4], cl[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int e = lane + u * 64;
-                const int w2 = e / nlive, r2 = e - w2 * nlive;
-                const bool ok = w2 < nwv;
-                cv[u] = ok ? s_wv[w2 * EAGLE2_MAX_TOPK + r2] : -INFINITY;
-                ci[u] = ok ? s_wi[w2 * EAGLE2_MAX_TOPK + r2] : INT_MAX;
-                cl[u] = ok ? s_wl[w2 * EAGLE2_MAX_TOPK + r2] : -1;
-            }
-            for (int r = 0; r < nlive; ++r) {
-                float bv = cv[0]; int bi = ci[0]; int bl = cl[0];
-#pragma unroll
-                for (int u = 1; u < 4; ++u) if (ranks_before(cv[u], ci[u], bv, bi)) { bv = cv[u]; bi = ci[u]; bl = cl[u]; }
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) {
-                    const float ov = __shfl_xor(bv, o, 64);
-                    const int oi = __shfl_xor(bi, o, 64);
-                    const int ol = __shfl_xor(bl, o, 64);
-                    if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; bl = ol; }
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) if (cl[u] == bl) { cv[u] = -INFINITY; ci[u] = INT_MAX; cl[u] = -1; }
-                if (lane == 0) s_live[r] = bl < 0 ? 0 : bl;
-            }
+        const int n2 = nwv * nlive;                         // <= 256 survivors, compact in s_w*
+        if (tid < n2) {
+            const int r = count_before(s_wv, s_wi, n2, s_wv[tid], s_wi[tid]);
+            if (r < nlive && s_wi[tid] != INT_MAX) s_live[r] = s_wl[tid];
         }
     }
     __syncthreads();
@@ -417,8 +388,7 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G,
     if (tid < ncand) {
         const float cv = s_cv[tid];
         const int ci = s_ci[tid];
-        int r = 0;
-        for (int j = 0; j < ncand; ++j) r += ranks_before(s_cv[j], s_ci[j], cv, ci) ? 1 : 0;
+        const int r = count_before(s_cv, s_ci, ncand, cv, ci);
         if (r < k && ci != INT_MAX) { s_ov[r] = cv; s_oi[r] = ci; }
     }
     __syncthreads();
@@ -449,27 +419,17 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G,
         s_last = prev == (unsigned)(F - 1) ? 1 : 0;
     }
     __syncthreads();
-    if (!s_last || wave != 0) return;
-    const int nn = F * k;                               // <= 256 new candidates, <= 4 per lane
-    double v[4]; int id[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int j = lane + q * 64;
-        v[q] = j < nn ? __hip_atomic_load(cand_score + (size_t)b * C + base + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                      : -INFINITY;
-        id[q] = j < nn ? base + j : INT_MAX;
+    if (!s_last) return;
+    const int nn = F * k;                               // <= 256 new candidates, ranked by counting
+    if (tid < nn) {
+        s_fs[tid] = __hip_atomic_load(cand_score + (size_t)b * C + base + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_fi[tid] = base + tid;
     }
-    int mine = -1;
-    for (int r = 0; r < k; ++r) {
-        double bv = v[0]; int bi = id[0];
-#pragma unroll
-        for (int q = 1; q < 4; ++q) if (ranks_before(v[q], id[q], bv, bi)) { bv = v[q]; bi = id[q]; }
-        wave_best(bv, bi);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) if (id[q] == bi) { v[q] = -INFINITY; id[q] = INT_MAX; }
-        if (lane == r) mine = bi;
+    __syncthreads();
+    if (tid < nn) {
+        const int r = count_before(s_fs, s_fi, nn, s_fs[tid], s_fi[tid]);
+        if (r < k) frontier[((size_t)b * D + d + 1) * k + r] = base + tid;
     }
-    if (lane < k) frontier[((size_t)b * D + d + 1) * k + lane] = mine;
 }
 
 static int lm_grid(const eagle2_cfg* cfg) {
