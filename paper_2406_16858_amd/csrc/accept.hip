@@ -22,7 +22,7 @@ constexpr int SAMPLE_WGS = 32;           // most workgroups that cooperate on on
 constexpr int SAMPLE_MAXE = 4;           // vocabulary entries a thread can keep in registers
 constexpr int SAMPLE_THREADS = 1024;
 constexpr int SAMPLE_NPART = 4;          // doubles exchanged per workgroup per pass
-constexpr int SAMPLE_SLOT = 8;           // 64-bit words per exchange slot: the doubles, then a sequence flag
+constexpr int SAMPLE_SLOT = 8;           // 64-bit words per exchange slot: two tagged halves per double
 constexpr unsigned SPIN_LIMIT = 1u << 22;
 
 struct AcceptWs { size_t choice, bar, part, total; };
@@ -36,17 +36,18 @@ static AcceptWs accept_layout(const eagle2_cfg* cfg) {
 }
 size_t accept_workspace(const eagle2_cfg* cfg) { return accept_layout(cfg).total; }
 
-__global__ void accept_init_kernel(unsigned* fail, int nfail, unsigned long long* slots, int nwords) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < nfail) fail[i] = 0u;
-    if (i < nwords) slots[i] = 0ull;
-}
-
 // grid (N, B): arg-max of one row of target logits, lowest id on ties
 __global__ __launch_bounds__(AM_THREADS)
 void row_argmax_kernel(const float* __restrict__ logits, int V, int N, const int* __restrict__ mode,
-                       int* __restrict__ choice) {
+                       int* __restrict__ choice, unsigned* __restrict__ fail, int nfail,
+                       unsigned long long* __restrict__ slots, int nwords) {
     const int b = blockIdx.y, n = blockIdx.x;
+    {   // side job: clear the sampling kernel's failure flags and exchange slots (it runs next)
+        const int gid = (blockIdx.y * gridDim.x + blockIdx.x) * AM_THREADS + threadIdx.x;
+        const int nth = gridDim.x * gridDim.y * AM_THREADS;
+        for (int i = gid; i < nfail; i += nth) fail[i] = 0u;
+        for (int i = gid; i < nwords; i += nth) slots[i] = 0ull;
+    }
     if (mode[b] != EAGLE2_MODE_GREEDY) return;
     const float* row = logits + ((size_t)b * N + n) * (size_t)V;
     float bv = -INFINITY;
@@ -78,27 +79,29 @@ void row_argmax_kernel(const float* __restrict__ logits, int V, int N, const int
     }
 }
 
-// grid (B), one wave: follow the matching child from the root
-__global__ __launch_bounds__(64)
-void greedy_walk_kernel(int N, int D, const int* __restrict__ mode, const int* __restrict__ choice,
-                        const int* __restrict__ tree_token, const int* __restrict__ tree_parent,
-                        int* __restrict__ accept_len, int* __restrict__ accept_path, int* __restrict__ bonus) {
-    const int b = blockIdx.x, lane = threadIdx.x;
-    if (mode[b] != EAGLE2_MODE_GREEDY) return;
+// one wave: follow the matching child from the root
+__device__ __forceinline__ void greedy_walk(int b, int lane, int N, int D, const int* __restrict__ choice,
+                                            const int* __restrict__ tree_token, const int* __restrict__ tree_parent,
+                                            int* __restrict__ accept_len, int* __restrict__ accept_path,
+                                            int* __restrict__ bonus) {
     const int* tok = tree_token + (size_t)b * N;
     const int* par = tree_parent + (size_t)b * N;
     const int* ch = choice + (size_t)b * N;
     int* path = accept_path + (size_t)b * (D + 1);
+    // each lane keeps its (up to two) rows in registers: N <= 128
+    const int c0 = lane, c1 = lane + 64;
+    const int p0 = c0 < N ? par[c0] : -2, t0 = c0 < N ? tok[c0] : -1, w0 = c0 < N ? ch[c0] : -1;
+    const int p1 = c1 < N ? par[c1] : -2, t1 = c1 < N ? tok[c1] : -1, w1 = c1 < N ? ch[c1] : -1;
     int cur = 0, len = 0;
     if (lane == 0) path[0] = 0;
     for (int step = 0; step < D; ++step) {
-        const int want = ch[cur];
-        int found = INT_MAX;
-        for (int c = lane; c < N; c += 64)
-            if (c > cur && par[c] == cur && tok[c] == want) { found = c; break; }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) found = min(found, __shfl_xor(found, o, 64));
-        if (found == INT_MAX) break;
+        const int want = cur < 64 ? read_lane_dyn(w0, cur) : read_lane_dyn(w1, cur - 64);
+        const unsigned long long m0 = __ballot(c0 > cur && p0 == cur && t0 == want);
+        const unsigned long long m1 = __ballot(c1 > cur && p1 == cur && t1 == want);
+        int found = -1;
+        if (m0) found = __ffsll((long long)m0) - 1;
+        else if (m1) found = 64 + __ffsll((long long)m1) - 1;
+        if (found < 0) break;
         cur = found;
         ++len;
         if (lane == 0) path[len] = cur;
@@ -106,8 +109,17 @@ void greedy_walk_kernel(int N, int D, const int* __restrict__ mode, const int* _
     if (lane == 0) {
         for (int i = len + 1; i <= D; ++i) path[i] = -1;
         accept_len[b] = len;
-        bonus[b] = ch[cur];
+        bonus[b] = cur < 64 ? read_lane_dyn(w0, cur) : read_lane_dyn(w1, cur - 64);
     }
+}
+
+// grid (B), one wave per sequence; used when no sequence can sample
+__global__ __launch_bounds__(64)
+void greedy_walk_kernel(int N, int D, const int* __restrict__ mode, const int* __restrict__ choice,
+                        const int* __restrict__ tree_token, const int* __restrict__ tree_parent,
+                        int* __restrict__ accept_len, int* __restrict__ accept_path, int* __restrict__ bonus) {
+    if (mode[blockIdx.x] != EAGLE2_MODE_GREEDY) return;
+    greedy_walk(blockIdx.x, threadIdx.x, N, D, choice, tree_token, tree_parent, accept_len, accept_path, bonus);
 }
 
 // ---- sampling ------------------------------------------------------------------------
@@ -119,35 +131,31 @@ struct SampleCtx {
     int nwg;                     // workgroups cooperating on this sequence (<= SAMPLE_WGS)
 };
 
-// All-gather of SAMPLE_NPART doubles among the workgroups of one sequence.  Every workgroup
-// publishes its values followed by a sequence flag in its own slot (no shared counter, so
-// no serialised read-modify-writes); thread t of every workgroup waits for slot t's flag
-// and copies that slot into `out[t*NPART + i]` (LDS).  Slots alternate between two sets by
-// pass parity: a workgroup can only be one exchange ahead of the slowest one.  The wait is
-// bounded; false means it expired and the kernel gives up cleanly.
+// All-gather of SAMPLE_NPART doubles among the workgroups of one sequence.  Every 64-bit word
+// a workgroup publishes carries half a double plus the pass number (tag << 32 | half), so each
+// word validates itself: no flag, no ordering between stores, one store and one load on the
+// critical path.  Thread 8*g + j of every workgroup waits for word j of workgroup g's slot and
+// drops its half into `out` (LDS, doubles viewed as pairs of 32-bit words).  Slots alternate
+// between two sets by pass parity: a workgroup can only be one exchange ahead of the slowest
+// one.  The wait is bounded; false means it expired and the kernel gives up cleanly.
 __device__ bool exchange(SampleCtx& cx, const double (&mine)[SAMPLE_NPART], double* out /*LDS*/, int* s_ok) {
     const int wg = blockIdx.x, tid = threadIdx.x;
     unsigned long long* buf = cx.slots + (size_t)(cx.pass & 1) * SAMPLE_WGS * SAMPLE_SLOT;
-    const unsigned long long seq = (unsigned long long)cx.pass + 1ull;
+    const unsigned long long tag = ((unsigned long long)cx.pass + 1ull) << 32;
     __syncthreads();                                   // the previous exchange's `out` is no longer read
-    if (tid == 0) {
-        *s_ok = 1;
-        for (int i = 0; i < SAMPLE_NPART; ++i)
-            __hip_atomic_store(buf + wg * SAMPLE_SLOT + i, (unsigned long long)__double_as_longlong(mine[i]),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // The values above are device-scope atomic stores (written through to the coherence
-        // point).  Waiting for their acknowledgement is all the ordering the flag needs; a
-        // device-scope release would also write back the whole L2, once per workgroup per pass.
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __hip_atomic_store(buf + wg * SAMPLE_SLOT + SAMPLE_NPART, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) *s_ok = 1;
+    if (tid < SAMPLE_SLOT) {
+        const double v = mine[tid >> 1];
+        const unsigned half = (tid & 1) ? (unsigned)__double2hiint(v) : (unsigned)__double2loint(v);
+        __hip_atomic_store(buf + wg * SAMPLE_SLOT + tid, tag | half, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
-    if (tid < cx.nwg) {
+    if (tid < cx.nwg * SAMPLE_SLOT) {
         unsigned spins = 0;
         bool ok = true;
-        // relaxed device-scope loads: they are served at the coherence point, and the values
-        // read afterwards are fetched the same way, so no cache invalidation is needed per poll
-        while (__hip_atomic_load(buf + tid * SAMPLE_SLOT + SAMPLE_NPART, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != seq) {
+        unsigned long long wv;
+        // relaxed device-scope loads are served at the coherence point: no cache invalidation per poll
+        while (((wv = __hip_atomic_load(buf + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 32) != (tag >> 32)) {
             __builtin_amdgcn_s_sleep(2);
             if ((++spins & 1023u) == 0u &&
                 (spins > SPIN_LIMIT || __hip_atomic_load(cx.fail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
@@ -156,13 +164,8 @@ __device__ bool exchange(SampleCtx& cx, const double (&mine)[SAMPLE_NPART], doub
                 break;
             }
         }
-        if (ok) {
-            for (int i = 0; i < SAMPLE_NPART; ++i)
-                out[tid * SAMPLE_NPART + i] = __longlong_as_double((long long)__hip_atomic_load(
-                    buf + tid * SAMPLE_SLOT + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        } else {
-            *s_ok = 0;
-        }
+        if (ok) reinterpret_cast<unsigned*>(out)[tid] = (unsigned)wv;    // slot g word j -> double g*4 + j/2, half j&1
+        else *s_ok = 0;
     }
     __syncthreads();
     cx.pass += 1;
@@ -264,13 +267,18 @@ __device__ __forceinline__ void element_state(const NodeScalars& ns, int v, floa
 template <bool CACHED>
 __global__ __launch_bounds__(SAMPLE_THREADS)
 void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int* __restrict__ mode,
-                          const float* __restrict__ target_logits, const float* __restrict__ draft_logits,
+                          const int* __restrict__ choice, const float* __restrict__ target_logits, const float* __restrict__ draft_logits,
                           const float* __restrict__ temperature, const float* __restrict__ u_accept,
                           const float* __restrict__ u_bonus, const int* __restrict__ tree_token,
                           const int* __restrict__ tree_parent, const int* __restrict__ tree_cand,
                           unsigned* __restrict__ fails, unsigned long long* __restrict__ slots,
                           int* __restrict__ accept_len, int* __restrict__ accept_path, int* __restrict__ bonus) {
     const int b = blockIdx.y, wg = blockIdx.x, tid = threadIdx.x;
+    if (mode[b] == EAGLE2_MODE_GREEDY) {
+        if (wg == 0 && tid < 64)
+            greedy_walk(b, tid, N, D, choice, tree_token, tree_parent, accept_len, accept_path, bonus);
+        return;
+    }
     if (mode[b] != EAGLE2_MODE_SAMPLE) return;
     constexpr int KIDS = EAGLE2_MAX_TOPK + 1;
     __shared__ NodeScalars ns;
@@ -565,32 +573,31 @@ extern "C" int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int B = cfg->batch, N = cfg->n_tree, V = cfg->vocab, D = cfg->depth;
 
-    hipLaunchKernelGGL(row_argmax_kernel, dim3(N, B), dim3(AM_THREADS), 0, st, target_logits, V, N, mode, choice);
+    const int nwords = can_sample ? B * 2 * SAMPLE_WGS * SAMPLE_SLOT : 0;
+    hipLaunchKernelGGL(row_argmax_kernel, dim3(N, B), dim3(AM_THREADS), 0, st, target_logits, V, N, mode, choice,
+                       fails, can_sample ? B : 0, slots, nwords);
     E2_HIP(hipGetLastError());
-    hipLaunchKernelGGL(greedy_walk_kernel, dim3(B), dim3(64), 0, st, N, D, mode, choice, tree_token, tree_parent,
-                       accept_len, accept_path, bonus_token);
-    E2_HIP(hipGetLastError());
-    if (can_sample) {
-        const int nwords = B * 2 * SAMPLE_WGS * SAMPLE_SLOT;
-        hipLaunchKernelGGL(accept_init_kernel, dim3((nwords + 255) / 256), dim3(256), 0, st, fails, B, slots, nwords);
+    if (!can_sample) {
+        hipLaunchKernelGGL(greedy_walk_kernel, dim3(B), dim3(64), 0, st, N, D, mode, choice, tree_token, tree_parent,
+                           accept_len, accept_path, bonus_token);
         E2_HIP(hipGetLastError());
-        // all workgroups of a sequence wait for each other, so they must be resident together
-        int nwg = 2 * device_cu_count() / B;
-        nwg = nwg > SAMPLE_WGS ? SAMPLE_WGS : (nwg < 1 ? 1 : nwg);
-        
-        const int per_wg = (V + nwg - 1) / nwg;
-        const bool cached = (per_wg + SAMPLE_THREADS - 1) / SAMPLE_THREADS <= SAMPLE_MAXE;
-        if (cached)
-            hipLaunchKernelGGL(sample_accept_kernel<true>, dim3(nwg, B), dim3(SAMPLE_THREADS), 0, st,
-                               nwg, V, N, D, cfg->topk, n_draft_rows(cfg), mode, target_logits, draft_logits, temperature,
-                               u_accept, u_bonus, tree_token, tree_parent, tree_cand, fails, slots,
-                               accept_len, accept_path, bonus_token);
-        else
-            hipLaunchKernelGGL(sample_accept_kernel<false>, dim3(nwg, B), dim3(SAMPLE_THREADS), 0, st,
-                               nwg, V, N, D, cfg->topk, n_draft_rows(cfg), mode, target_logits, draft_logits, temperature,
-                               u_accept, u_bonus, tree_token, tree_parent, tree_cand, fails, slots,
-                               accept_len, accept_path, bonus_token);
-        E2_HIP(hipGetLastError());
+        return EAGLE2_OK;
     }
+    // all workgroups of a sequence wait for each other, so they must be resident together
+    int nwg = 2 * device_cu_count() / B;
+    nwg = nwg > SAMPLE_WGS ? SAMPLE_WGS : (nwg < 1 ? 1 : nwg);
+    const int per_wg = (V + nwg - 1) / nwg;
+    const bool cached = (per_wg + SAMPLE_THREADS - 1) / SAMPLE_THREADS <= SAMPLE_MAXE;
+    if (cached)
+        hipLaunchKernelGGL(sample_accept_kernel<true>, dim3(nwg, B), dim3(SAMPLE_THREADS), 0, st,
+                           nwg, V, N, D, cfg->topk, n_draft_rows(cfg), mode, choice, target_logits, draft_logits, temperature,
+                           u_accept, u_bonus, tree_token, tree_parent, tree_cand, fails, slots,
+                           accept_len, accept_path, bonus_token);
+    else
+        hipLaunchKernelGGL(sample_accept_kernel<false>, dim3(nwg, B), dim3(SAMPLE_THREADS), 0, st,
+                           nwg, V, N, D, cfg->topk, n_draft_rows(cfg), mode, choice, target_logits, draft_logits, temperature,
+                           u_accept, u_bonus, tree_token, tree_parent, tree_cand, fails, slots,
+                           accept_len, accept_path, bonus_token);
+    E2_HIP(hipGetLastError());
     return EAGLE2_OK;
 }
