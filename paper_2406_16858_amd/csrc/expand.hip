@@ -59,7 +59,10 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     const int wave_bytes = row_bytes >> 2;             // K bytes owned by this wave
     const int nst = wave_bytes / LM_CHUNK;
     const int ntask = (V + LM_ROWS - 1) / LM_ROWS;
-    const int my_tasks = ((int)blockIdx.x < ntask) ? (ntask - (int)blockIdx.x + G - 1) / G : 0;
+    // workgroup bx owns a contiguous block of tasks (2 MB runs of W at the LLaMA shapes)
+    const int tq = ntask / G, tr = ntask - tq * G;
+    const int my_tasks = tq + ((int)blockIdx.x < tr ? 1 : 0);
+    const int task_first = (int)blockIdx.x * tq + min((int)blockIdx.x, tr);
     const int total = my_tasks * nst;
     uint8_t* stage = smem + w * LM_STAGE;
     const int mrow = mblk * 16 + m16;                  // frontier row owned by this lane
@@ -74,21 +77,53 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
 #pragma unroll
     for (int j = 0; j < KC; ++j) { tval[j] = -INFINITY; tidx[j] = INT_MAX; }
 
-    // raw logits (optional) leave through an LDS transpose: wave w stores frontier rows 4w..4w+3,
-    // one row per quarter-wave, 256 contiguous bytes each
-    float* lrow = nullptr;
-    {
-        const int wr = mblk * 16 + w * 4 + r_in;
-        if (logits_out != nullptr && wr < M) {
-            const int b = wr / F, s = wr - b * F;
-            lrow = logits_out + ((size_t)b * logit_rows_per_seq + logit_row_base + s) * (size_t)V;
+    // Raw logits (optional) are kept in registers for up to LOGIT_BUF finished tasks and leave
+    // in one burst through an LDS transpose: wave w stores frontier rows w, w+4, w+8, w+12, each
+    // quarter-wave 256 contiguous bytes.  Stores sprinkled into the read stream cost far more
+    // than their bytes (the HBM channels keep turning around), so they are clustered in time.
+    constexpr int LOGIT_BUF = 4;
+    constexpr int LT_RS = LOGIT_BUF * LM_ROWS + 4;     // floats per row of the transpose tile (+16 B pad)
+    float* lrow[4] = {nullptr, nullptr, nullptr, nullptr};
+    if (logits_out != nullptr) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int wr = mblk * 16 + q * 4 + w;
+            if (wr < M) {
+                const int b = wr / F, s = wr - b * F;
+                lrow[q] = logits_out + ((size_t)b * logit_rows_per_seq + logit_row_base + s) * (size_t)V;
+            }
         }
     }
-    constexpr int LT_RS = 68;                          // floats per row of the transpose tile (64 + pad)
+    floatx4 xs[LOGIT_BUF];
+    int nbuf = 0, buf_task0 = task_first;
+    auto flush_logits = [&]() {                        // called by the whole workgroup; stages must be idle
+        float* lt = reinterpret_cast<float*>(smem);
+#pragma unroll
+        for (int t = 0; t < LOGIT_BUF; ++t)
+            if (t < nbuf) *reinterpret_cast<floatx4*>(lt + m16 * LT_RS + t * LM_ROWS + w * 16 + g * 4) = xs[t];
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            // quarter-wave r_in takes buffered task r_in of row 4q + w: the wave writes one 1 KB run
+            const int v0 = (buf_task0 + r_in) * LM_ROWS + c16 * 4;
+            if (lrow[q] != nullptr && r_in < nbuf && v0 < V) {
+                const floatx4 y = *reinterpret_cast<const floatx4*>(lt + (q * 4 + w) * LT_RS + r_in * LM_ROWS + c16 * 4);
+                if (v0 + 3 < V && (V & 3) == 0) {
+                    __builtin_nontemporal_store(y, reinterpret_cast<floatx4*>(lrow[q] + v0));
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) if (v0 + i < V) lrow[q][v0 + i] = y[i];
+                }
+            }
+        }
+        __syncthreads();                               // lt aliases the staging buffers
+        buf_task0 += nbuf;
+        nbuf = 0;
+    };
 
     u32x4 R[LM_LOADS];
     auto issue = [&](int it) {
-        const int task = blockIdx.x + (it / nst) * G;
+        const int task = task_first + it / nst;
         const int st = it - (it / nst) * nst;
         const size_t kb = (size_t)w * wave_bytes + (size_t)st * LM_CHUNK + c16 * 16;
 #pragma unroll
@@ -129,7 +164,7 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     for (int it = 0; it < total; ++it) {
         const int ti = it / nst;
         const int st = it - ti * nst;
-        const int task = blockIdx.x + ti * G;
+        const int task = task_first + ti;
 #pragma unroll
         for (int j = 0; j < LM_LOADS; ++j)
             *reinterpret_cast<u32x4*>(stage + (j * 4 + r_in) * LM_RS + ((c16 ^ ((j * 4 + r_in) & 15)) << 4)) = R[j];
@@ -179,20 +214,10 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
 
             const int vbase = task * LM_ROWS + w * 16 + g * 4;
             if (logits_out != nullptr) {               // uniform over the workgroup
-                float* lt = reinterpret_cast<float*>(smem);
-                *reinterpret_cast<floatx4*>(lt + m16 * LT_RS + w * 16 + g * 4) = x;
-                __syncthreads();
-                const floatx4 y = *reinterpret_cast<const floatx4*>(lt + (w * 4 + r_in) * LT_RS + c16 * 4);
-                const int v0 = task * LM_ROWS + c16 * 4;
-                if (lrow != nullptr && v0 < V) {
-                    if (v0 + 3 < V && (V & 3) == 0) {
-                        __builtin_nontemporal_store(y, reinterpret_cast<floatx4*>(lrow + v0));
-                    } else {
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) if (v0 + i < V) lrow[v0 + i] = y[i];
-                    }
-                }
-                __syncthreads();                       // lt aliases the staging buffers
+                for (int t = 0; t < LOGIT_BUF; ++t) if (t == nbuf) xs[t] = x;
+                ++nbuf;
+                if (nbuf == LOGIT_BUF || ti == my_tasks - 1) flush_logits();
             }
             if (row_valid && vbase < V) {
                 float xm = x[0];
