@@ -72,6 +72,7 @@ template <int CTRL> __device__ __forceinline__ double dpp_mov(double v) {
 __device__ __forceinline__ int read_lane(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
 // lane index held in a register (must be wave-uniform)
 __device__ __forceinline__ int read_lane_dyn(int v, int l) { return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(l)); }
+__device__ __forceinline__ float read_lane_dyn(float v, int l) { return __int_as_float(read_lane_dyn(__float_as_int(v), l)); }
 __device__ __forceinline__ float read_lane(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
 __device__ __forceinline__ double read_lane(double v, int l) {
     return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l), __builtin_amdgcn_readlane(__double2loint(v), l));
@@ -90,6 +91,13 @@ __device__ __forceinline__ double wave_maxd(double v) {
     v = fmax(v, dpp_mov<DPP_HALF_MIRROR>(v));
     v = fmax(v, dpp_mov<DPP_MIRROR>(v));
     return fmax(fmax(read_lane(v, 0), read_lane(v, 16)), fmax(read_lane(v, 32), read_lane(v, 48)));
+}
+__device__ __forceinline__ float wave_sumf(float v) {
+    v += dpp_mov<DPP_XOR1>(v);
+    v += dpp_mov<DPP_XOR2>(v);
+    v += dpp_mov<DPP_HALF_MIRROR>(v);
+    v += dpp_mov<DPP_MIRROR>(v);
+    return ((read_lane(v, 0) + read_lane(v, 16)) + read_lane(v, 32)) + read_lane(v, 48);
 }
 __device__ __forceinline__ double wave_sum(double v) {
     v += dpp_mov<DPP_XOR1>(v);

@@ -101,40 +101,54 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
         for (int db = 0; db < DH / 16; ++db) acc[rb][db] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
+    // The next tile's K and V are fetched into registers while the current tile is multiplied.
+    constexpr int NKP = TA_KEYS * SLOTS / TA_THREADS;          // 16-byte K pieces per thread per tile
+    constexpr bool V_ALL = 16 * SLOTS >= TA_THREADS;            // every thread owns a V unit (dh 128)
+    const bool v_owner = V_ALL || tid < 16 * SLOTS;
+    const int v_c = tid % SLOTS, v_kg = tid / SLOTS;            // V unit: 8 dh (chunk v_c) x 4 keys (group v_kg)
+    u32x4 kr[NKP], vr[4];
+    auto fetch_tile = [&](int tile) {
+        const int key0 = tile * TA_KEYS;
+#pragma unroll
+        for (int i = 0; i < NKP; ++i) {
+            const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
+            kr[i] = key0 + key < count ? *reinterpret_cast<const u32x4*>(kbase + (size_t)(key0 + key) * kv_stride + c * 8)
+                                       : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int key = key0 + v_kg * 4 + i;
+            vr[i] = (v_owner && key < count) ? *reinterpret_cast<const u32x4*>(vbase + (size_t)key * kv_stride + v_c * 8)
+                                             : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
     const int ntile = (count + TA_KEYS - 1) / TA_KEYS;
+    if (ntile > 0) fetch_tile(0);
     for (int tile = 0; tile < ntile; ++tile) {
         const int key0 = tile * TA_KEYS;
         __syncthreads();                           // previous tile fully consumed
         // K tile -> LDS, row-major, 16-byte slots swizzled by the row
-        for (int p = tid; p < TA_KEYS * SLOTS; p += TA_THREADS) {
-            const int key = p / SLOTS, c = p - key * SLOTS;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (key0 + key < count) v = *reinterpret_cast<const u32x4*>(kbase + (size_t)(key0 + key) * kv_stride + c * 8);
-            *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + ((c ^ k_swz<DH>(key)) << 4)) = v;
-        }
-        // V tile -> LDS transposed: thread takes 4 keys x 8 dh, writes 8 dh rows x 4 keys (8 bytes each)
-        for (int u = tid; u < 16 * SLOTS; u += TA_THREADS) {
-            const int c = u % SLOTS, kg = u / SLOTS;
-            u32x4 r[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int key = key0 + kg * 4 + i;
-                r[i] = key < count ? *reinterpret_cast<const u32x4*>(vbase + (size_t)key * kv_stride + c * 8)
-                                   : u32x4{0u, 0u, 0u, 0u};
-            }
+        for (int i = 0; i < NKP; ++i) {
+            const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
+            *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + ((c ^ k_swz<DH>(key)) << 4)) = kr[i];
+        }
+        // V tile -> LDS transposed: 4 keys x 8 dh become 8 dh rows x 4 keys (8 bytes each)
+        if (v_owner) {
 #pragma unroll
             for (int e2 = 0; e2 < 4; ++e2) {
                 u32x2 lo, hi;                      // dh 2*e2 and 2*e2+1, keys 0..3
-                lo[0] = (r[0][e2] & 0xffffu) | (r[1][e2] << 16);
-                lo[1] = (r[2][e2] & 0xffffu) | (r[3][e2] << 16);
-                hi[0] = (r[0][e2] >> 16) | (r[1][e2] & 0xffff0000u);
-                hi[1] = (r[2][e2] >> 16) | (r[3][e2] & 0xffff0000u);
-                const int row0 = c * 8 + e2 * 2, row1 = row0 + 1;
-                *reinterpret_cast<u32x2*>(s_vt + row0 * (TA_KEYS * 2) + ((kg ^ v_swz(row0)) << 3)) = lo;
-                *reinterpret_cast<u32x2*>(s_vt + row1 * (TA_KEYS * 2) + ((kg ^ v_swz(row1)) << 3)) = hi;
+                lo[0] = (vr[0][e2] & 0xffffu) | (vr[1][e2] << 16);
+                lo[1] = (vr[2][e2] & 0xffffu) | (vr[3][e2] << 16);
+                hi[0] = (vr[0][e2] >> 16) | (vr[1][e2] & 0xffff0000u);
+                hi[1] = (vr[2][e2] >> 16) | (vr[3][e2] & 0xffff0000u);
+                const int row0 = v_c * 8 + e2 * 2, row1 = row0 + 1;
+                *reinterpret_cast<u32x2*>(s_vt + row0 * (TA_KEYS * 2) + ((v_kg ^ v_swz(row0)) << 3)) = lo;
+                *reinterpret_cast<u32x2*>(s_vt + row1 * (TA_KEYS * 2) + ((v_kg ^ v_swz(row1)) << 3)) = hi;
             }
         }
         __syncthreads();
+        if (tile + 1 < ntile) fetch_tile(tile + 1);
 
         // S^T = K Q^T : s[rb][kb][i] = score(query row of this lane, key kb*16 + 4*g4 + i)
         floatx4 s[RBW][4];
@@ -224,7 +238,9 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     }
 }
 
-// grid (B*N, Hq / 4), 4 waves: one wave per (row, head), lanes over dh
+// grid (B*N, Hq / 4), 4 waves: one wave per (row, head).  Lanes first act as chunks (max and
+// weights of up to 64 chunks at a time), then as dh columns for the weighted sum of the
+// partial outputs, whose loads are independent and issued four chunks at a time.
 template <int DH>
 __global__ __launch_bounds__(256)
 void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, int N, int Hq, int Hkv, int chunk, int rows_pad,
@@ -236,17 +252,42 @@ void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, int N, i
     const int grp = Hq / Hkv, kvh = h / grp, rho = n * grp + (h - kvh * grp);
     int first, nc;
     locate_seq(b, chunk, kv_offsets, first, nc);
+    const size_t cstride = (size_t)Hkv * rows_pad;               // rows between consecutive chunks
+    const size_t row0 = ((size_t)first * Hkv + kvh) * rows_pad + rho;
     float mx = NEG_BIG;
-    for (int c = 0; c < nc; ++c) mx = fmaxf(mx, part_ml[(((size_t)(first + c) * Hkv + kvh) * rows_pad + rho) * 2]);
+    for (int c = lane; c < nc; c += 64) mx = fmaxf(mx, part_ml[(row0 + c * cstride) * 2]);
+    mx = wave_max(mx);
     float l = 0.f, o[DH / 64];
 #pragma unroll
     for (int e = 0; e < DH / 64; ++e) o[e] = 0.f;
-    for (int c = 0; c < nc; ++c) {
-        const size_t prow = ((size_t)(first + c) * Hkv + kvh) * rows_pad + rho;
-        const float wgt = exp2f(part_ml[prow * 2] - mx);
-        l += wgt * part_ml[prow * 2 + 1];
+    for (int c0 = 0; c0 < nc; c0 += 64) {
+        const int c = c0 + lane;
+        float wgt = 0.f, lc = 0.f;
+        if (c < nc) {
+            wgt = exp2f(part_ml[(row0 + c * cstride) * 2] - mx);
+            lc = part_ml[(row0 + c * cstride) * 2 + 1];
+        }
+        l += wave_sumf(wgt * lc);
+        const int nb = min(64, nc - c0);
+        int j = 0;
+        for (; j + 4 <= nb; j += 4) {
+            float v[4][DH / 64];
 #pragma unroll
-        for (int e = 0; e < DH / 64; ++e) o[e] += wgt * part_o[prow * DH + e * 64 + lane];
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < DH / 64; ++e) v[u][e] = part_o[(row0 + (size_t)(c0 + j + u) * cstride) * DH + e * 64 + lane];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float wu = read_lane_dyn(wgt, j + u);
+#pragma unroll
+                for (int e = 0; e < DH / 64; ++e) o[e] += wu * v[u][e];
+            }
+        }
+        for (; j < nb; ++j) {
+            const float wu = read_lane_dyn(wgt, j);
+#pragma unroll
+            for (int e = 0; e < DH / 64; ++e) o[e] += wu * part_o[(row0 + (size_t)(c0 + j) * cstride) * DH + e * 64 + lane];
+        }
     }
     const float inv = 1.f / l;
     uint16_t* orow = O + ((size_t)bn * Hq + h) * DH;
@@ -330,11 +371,15 @@ static AttnPlan attn_plan(const eagle2_cfg* cfg, const eagle2_attn_cfg* a) {
     p.bm = 64 * p.rbw;
     p.nmblk = (rows + p.bm - 1) / p.bm;
     p.rows_pad = p.nmblk * p.bm;
-    // aim at about two workgroups per compute unit; never less than 4 tiles per chunk
+    // One resident round of workgroups: the wide variant keeps one workgroup per compute unit,
+    // the narrow one two.  Each sequence also has its tree chunk; at least two tiles per chunk.
     const long long wg_per_chunk = (long long)a->n_kv_heads * p.nmblk;
-    long long want = a->total_prefix * wg_per_chunk / (2ll * device_cu_count());
+    const long long target = (long long)device_cu_count() * (p.rbw == 2 ? 1 : 2);
+    long long budget = target / wg_per_chunk - cfg->batch;
+    if (budget < 1) budget = 1;
+    long long want = (a->total_prefix + budget - 1) / budget;
     want = (want + TA_KEYS - 1) / TA_KEYS * TA_KEYS;
-    if (want < 256) want = 256;
+    if (want < 2 * TA_KEYS) want = 2 * TA_KEYS;
     if (want > 8192) want = 8192;
     p.chunk = (int)want;
     p.max_chunks = (int)(a->total_prefix / p.chunk) + 2 * cfg->batch;
