@@ -19,8 +19,8 @@ namespace eagle2 {
 
 constexpr int AM_THREADS = 256;
 constexpr int SAMPLE_WGS = 32;           // most workgroups that cooperate on one sampling sequence
-constexpr int SAMPLE_MAXE = 4;           // vocabulary entries a thread can keep in registers
-constexpr int SAMPLE_THREADS = 1024;
+constexpr int SAMPLE_MAXE = 16;          // vocabulary entries a thread can keep in registers
+constexpr int SAMPLE_THREADS = 256;
 constexpr int SAMPLE_NPART = 4;          // doubles exchanged per workgroup per pass
 constexpr int SAMPLE_SLOT = 8;           // 64-bit words per exchange slot: two tagged halves per double
 constexpr unsigned SPIN_LIMIT = 1u << 22;
