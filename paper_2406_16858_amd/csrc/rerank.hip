@@ -3,8 +3,9 @@
 // flattening in increasing id order behind the root, parent rows, depths, position ids
 // and the ancestor bitmask ("each token can only see its ancestor nodes").
 //
-// One workgroup per sequence.  The C <= 2048 (score, id) pairs are sorted by a bitonic
-// network in LDS; the rest is a handful of LDS look-ups.
+// One workgroup per sequence.  The C <= 2048 candidates are ranked by counting (runs of 64
+// ranked with lane broadcasts, run against run by binary search); the rest is a handful of
+// LDS look-ups.
 
 #include "common.h"
 
@@ -13,7 +14,7 @@ namespace eagle2 {
 constexpr int RR_THREADS = 1024;
 
 __global__ __launch_bounds__(RR_THREADS)
-void rerank_kernel(int C, int n2, int N, int k, int words,
+void rerank_kernel(int C, int N, int k, int words,
                    const int* __restrict__ cand_token, const double* __restrict__ cand_score,
                    const int* __restrict__ cand_parent, const int* __restrict__ root_token,
                    const int* __restrict__ prefix_len,
@@ -22,6 +23,8 @@ void rerank_kernel(int C, int n2, int N, int k, int words,
                    unsigned long long* __restrict__ mask_bits) {
     __shared__ double s_key[EAGLE2_MAX_CAND];
     __shared__ int s_id[EAGLE2_MAX_CAND];
+    __shared__ int s_in[EAGLE2_MAX_CAND];          // rank inside the candidate's own run
+    __shared__ int s_rank[EAGLE2_MAX_CAND];
     __shared__ int s_row_of[EAGLE2_MAX_CAND];      // flat row of a candidate, -1 if not selected
     __shared__ int s_sel[EAGLE2_MAX_TREE];         // selected candidate ids (sorted order)
     __shared__ int s_par[EAGLE2_MAX_TREE];         // flat parent row per flat row
@@ -30,32 +33,49 @@ void rerank_kernel(int C, int n2, int N, int k, int words,
     const int* ctok = cand_token + (size_t)b * C;
     const int* cpar = cand_parent + (size_t)b * C;
 
-    for (int i = tid; i < n2; i += RR_THREADS) {
-        s_key[i] = i < C ? score[i] : -INFINITY;
-        s_id[i] = i < C ? i : INT_MAX;
-        if (i < C) s_row_of[i] = -1;
-    }
-    // bitonic sort, best candidate first
-    for (int size = 2; size <= n2; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (int t = tid; t < (n2 >> 1); t += RR_THREADS) {
-                const int i = 2 * t - (t & (stride - 1));
-                const int j = i + stride;
-                const bool fwd = (i & size) == 0;
-                const double ka = s_key[i], kb = s_key[j];
-                const int ia = s_id[i], ib = s_id[j];
-                const bool b_first = ranks_before(kb, ib, ka, ia);
-                if (b_first == fwd) {
-                    s_key[i] = kb; s_key[j] = ka;
-                    s_id[i] = ib; s_id[j] = ia;
-                }
-            }
+    // Rank of every candidate = number of candidates that precede it (score desc, id asc).
+    // Candidates are cut into runs of 64.  Inside a run the count is taken with v_readlane
+    // broadcasts (no LDS); the run is then laid out sorted in LDS, and the count against every
+    // other run is a binary search in that run.
+    const int nrun = (C + 63) >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int run = wave; run < nrun; run += RR_THREADS / 64) {
+        const int i = run * 64 + lane;
+        const double v = i < C ? score[i] : -INFINITY;
+        const int id = i < C ? i : INT_MAX;
+        int r = 0;
+#pragma unroll
+        for (int j = 0; j < 64; ++j) {
+            const double vj = read_lane(v, j);
+            r += (vj > v || (vj == v && j < lane)) ? 1 : 0;       // same run: id order = lane order
         }
+        s_key[run * 64 + r] = v;
+        s_id[run * 64 + r] = id;
+        if (i < C) s_in[i] = r;                                   // padding entries sort after the real ones
+    }
+    __syncthreads();
+    for (int i = tid; i < C; i += RR_THREADS) {
+        const double v = score[i];
+        const int myrun = i >> 6;
+        int r = s_in[i];
+        for (int run = 0; run < nrun; ++run) {
+            if (run == myrun) continue;
+            const double* kk = s_key + run * 64;
+            const int* ii = s_id + run * 64;
+            int lo = 0;                                           // entries [0, lo) precede (v, i)
+#pragma unroll
+            for (int step = 32; step > 0; step >>= 1)
+                if (ranks_before(kk[lo + step - 1], ii[lo + step - 1], v, i)) lo += step;
+            if (lo == 63 && ranks_before(kk[63], ii[63], v, i)) lo = 64;
+            r += lo;
+        }
+        s_rank[i] = r;
+        s_row_of[i] = -1;
     }
     __syncthreads();
     const int nsel = N - 1;
-    if (tid < nsel) s_sel[tid] = s_id[tid];
+    for (int i = tid; i < C; i += RR_THREADS)
+        if (s_rank[i] < nsel) s_sel[s_rank[i]] = i;
     __syncthreads();
     int my_row = -1, my_id = -1;
     if (tid < nsel) {
@@ -117,11 +137,9 @@ extern "C" int eagle2_rerank(const eagle2_cfg* cfg,
     E2_REQUIRE(cand_token && cand_score && cand_parent && root_token && prefix_len && tree_token && tree_parent &&
                tree_depth && tree_cand && position_ids && mask_bits, EAGLE2_ERR_ARG, "eagle2_rerank: null pointer argument");
     const int C = n_cand(cfg);
-    int n2 = 2;
-    while (n2 < C) n2 <<= 1;
     const int words = (cfg->n_tree + 63) / 64;
     hipLaunchKernelGGL(rerank_kernel, dim3(cfg->batch), dim3(RR_THREADS), 0, static_cast<hipStream_t>(stream),
-                       C, n2, cfg->n_tree, cfg->topk, words, cand_token, cand_score, cand_parent, root_token, prefix_len,
+                       C, cfg->n_tree, cfg->topk, words, cand_token, cand_score, cand_parent, root_token, prefix_len,
                        tree_token, tree_parent, tree_depth, tree_cand, position_ids,
                        reinterpret_cast<unsigned long long*>(mask_bits));
     E2_HIP(hipGetLastError());
