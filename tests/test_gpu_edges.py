@@ -1,0 +1,93 @@
+"""GPU edge cases through the C ABI: determinism, the largest supported shapes, error
+returns that must not enqueue anything, and sequences that accept with both modes."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from tests.parity_utils import run_and_check_round
+
+pytestmark = pytest.mark.gpu
+
+
+def _cfg(name, **kw):
+    base = dict(name=name, index=0, dtype="bf16", batch=1, vocab=4096, hidden=512, depth=4, topk=5, n_tree=24,
+                n_q_heads=8, n_kv_heads=2, head_dim=64, prefix_lo=130, prefix_hi=130, n_layers=1, w_std=0.05,
+                accept="greedy", temperature=1.0, seed=4321)
+    base.update(kw)
+    return wl.RoundConfig(**base)
+
+
+def test_largest_candidate_count_and_tree():
+    # C = 16 + 7*256 = 1808 candidates, N = 128 rows (two mask words), 33 rejections possible at most
+    cfg = _cfg("max_cand", topk=16, depth=8, n_tree=128, vocab=3000, accept="sample", seed=12)
+    run_and_check_round(cfg, h_scale=6.0)
+
+
+def test_smallest_shapes():
+    cfg = _cfg("min_shapes", vocab=16, topk=1, depth=1, n_tree=2, hidden=512, n_q_heads=1, n_kv_heads=1,
+               prefix_lo=0, prefix_hi=0, seed=2)
+    run_and_check_round(cfg, h_scale=2.0)
+    cfg = _cfg("vocab_eq_topk", vocab=16, topk=16, depth=2, n_tree=20, accept="sample", seed=3)
+    run_and_check_round(cfg, h_scale=2.0)
+
+
+def test_many_sequences_ragged_and_long_prefix():
+    cfg = _cfg("batch9", batch=9, accept="mixed", prefix_lo=0, prefix_hi=9000, n_q_heads=8, n_kv_heads=8,
+               head_dim=128, n_tree=30, seed=21)
+    run_and_check_round(cfg, h_scale=6.0, plant=True)
+
+
+def test_bitwise_determinism():
+    from paper_2406_16858_amd import DraftRound
+    cfg = wl.get_config(2)
+    W = wl.make_lm_head(cfg, "cuda")
+    H = wl.make_hidden_states(cfg, "cuda", scale=6.0)
+    Q, Kp, Vp, Kt, Vt, off = wl.make_attention_inputs(cfg, "cuda")
+    tl, _ = wl.make_target_logits(cfg, "cuda")
+    ua, ub = wl.make_uniforms(cfg, "cuda")
+    outs = []
+    for rep in range(3):
+        rnd = DraftRound(1, cfg.vocab, cfg.hidden, cfg.depth, cfg.topk, cfg.n_tree, cfg.dtype, cfg.n_q_heads,
+                         cfg.n_kv_heads, cfg.head_dim, total_prefix=cfg.prefix_lo, keep_draft_logits=True)
+        rnd.workspace.fill_(rep * 37 + 1)                  # the workspace carries nothing between calls
+        rnd.expand_all(H, W)
+        rnd.rerank(torch.tensor([5], dtype=torch.int32, device="cuda"),
+                   torch.tensor([cfg.prefix_lo], dtype=torch.int32, device="cuda"))
+        O = torch.empty_like(Q)
+        lse = torch.empty((1, cfg.n_tree, cfg.n_q_heads), dtype=torch.float32, device="cuda")
+        rnd.tree_attn(Q, Kp, Vp, off, Kt, Vt, O, lse)
+        mode = torch.ones(1, dtype=torch.int32, device="cuda")
+        rnd.accept(mode, tl, torch.ones(1, device="cuda"), ua, ub)
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (rnd.cand_token, rnd.cand_score, rnd.frontier, rnd.draft_logits, rnd.tree_token,
+                                         rnd.tree_parent, rnd.mask_bits, O, lse, rnd.accept_len, rnd.accept_path,
+                                         rnd.bonus_token)])
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b), "two runs on the same inputs differ bitwise"
+
+
+def test_errors_enqueue_nothing():
+    from paper_2406_16858_amd import DraftRound, Eagle2Error, binding as b
+    cfg = wl.get_config(1)
+    rnd = DraftRound(1, cfg.vocab, cfg.hidden, cfg.depth, cfg.topk, cfg.n_tree, cfg.dtype, cfg.n_q_heads,
+                     cfg.n_kv_heads, cfg.head_dim, total_prefix=128)
+    W = wl.make_lm_head(cfg, "cuda")
+    H = wl.make_hidden_states(cfg, "cuda")
+    before = rnd.cand_token.clone()
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(Eagle2Error, match="workspace"):
+        b.eagle2_expand(rnd.cfg, 0, H[:, 0], W, rnd.cand_token, rnd.cand_score, rnd.cand_parent, rnd.frontier, None, small)
+    with pytest.raises(Eagle2Error, match="pass index"):
+        b.eagle2_expand(rnd.cfg, cfg.depth, H[:, 0], W, rnd.cand_token, rnd.cand_score, rnd.cand_parent, rnd.frontier,
+                        None, rnd.workspace)
+    with pytest.raises(Eagle2Error, match="aligned"):
+        b.eagle2_expand(rnd.cfg, 0, H.view(-1)[1:1 + cfg.hidden], W, rnd.cand_token, rnd.cand_score, rnd.cand_parent,
+                        rnd.frontier, None, rnd.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(before, rnd.cand_token)
+    lib = b.load_library()
+    assert lib.eagle2_kernel_timing_read(7, ctypes.byref(ctypes.c_double()), ctypes.byref(ctypes.c_int32())) == -1
