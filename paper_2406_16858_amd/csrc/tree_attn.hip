@@ -201,8 +201,10 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
                 }
             }
             l_run[rb] = l_run[rb] * alpha + psum;
+            if (__any(alpha != 1.f)) {                 // the running maximum rarely moves after the first tiles
 #pragma unroll
-            for (int db = 0; db < DH / 16; ++db) acc[rb][db] *= alpha;
+                for (int db = 0; db < DH / 16; ++db) acc[rb][db] *= alpha;
+            }
         }
 
         // O^T += V^T P^T : keys of MFMA u for lane group g4 are {32u + 4g4 + i} and {32u + 16 + 4g4 + i}
@@ -380,7 +382,7 @@ static AttnPlan attn_plan(const eagle2_cfg* cfg, const eagle2_attn_cfg* a) {
     long long want = (a->total_prefix + budget - 1) / budget;
     want = (want + TA_KEYS - 1) / TA_KEYS * TA_KEYS;
     if (want < 2 * TA_KEYS) want = 2 * TA_KEYS;
-    if (want > 8192) want = 8192;
+    if (want > 2048) want = 2048;                      // bounded chunks keep ragged batches balanced
     p.chunk = (int)want;
     p.max_chunks = (int)(a->total_prefix / p.chunk) + 2 * cfg->batch;
     p.o_bytes = round_up((size_t)p.max_chunks * a->n_kv_heads * p.rows_pad * a->head_dim * sizeof(float), 256);
