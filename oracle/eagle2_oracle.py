@@ -110,6 +110,7 @@ class DraftState:
     score: np.ndarray = field(init=False)      # [C] sum of log confidences along the root path
     parent: np.ndarray = field(init=False)     # [C] candidate id of the parent, -1 = root
     frontier: np.ndarray = field(init=False)   # [D, k] candidate ids expanded by pass d (row 0 unused)
+    own: np.ndarray = field(init=False)        # [C] each candidate's own log confidence (score minus the parent's)
 
     def __post_init__(self):
         c = n_candidates(self.depth, self.topk)
@@ -117,11 +118,13 @@ class DraftState:
         self.score = np.full(c, -np.inf, dtype=np.float64)
         self.parent = np.full(c, -1, dtype=np.int64)
         self.frontier = np.full((self.depth, self.topk), -1, dtype=np.int64)
+        self.own = np.full(c, -np.inf, dtype=np.float64)
 
     def copy(self) -> "DraftState":
         s = DraftState(self.depth, self.topk)
         s.token, s.score = self.token.copy(), self.score.copy()
         s.parent, s.frontier = self.parent.copy(), self.frontier.copy()
+        s.own = self.own.copy()
         return s
 
 
@@ -154,7 +157,6 @@ def expand(state: DraftState, d: int, H, W, draft_logits: Optional[np.ndarray] =
     logp = np.empty_like(x)
     base = cand_base(d, k)
     tok_ids = np.arange(V)
-    own = np.empty(F * k, dtype=np.float64)                  # each new node's own log confidence
     for s in range(F):
         logp[s] = log_softmax64(x[s])
         if draft_logits is not None:
@@ -167,10 +169,10 @@ def expand(state: DraftState, d: int, H, W, draft_logits: Optional[np.ndarray] =
             state.token[cid] = v
             state.score[cid] = par_score + logp[s, v]
             state.parent[cid] = par
-            own[s * k + r] = logp[s, v]
+            state.own[cid] = logp[s, v]
     if d + 1 < D:
         new = np.arange(base, base + F * k)
-        key = state.score[new] if rank_by_value else own
+        key = state.score[new] if rank_by_value else state.own[new]
         order = np.lexsort((new, -key))[:k]
         state.frontier[d + 1] = new[order]
     return logp
@@ -197,14 +199,17 @@ def select_top(state: DraftState, m: int) -> np.ndarray:
     return np.lexsort((ids, -state.score))[:m]
 
 
-def select_frontiers(state: DraftState) -> np.ndarray:
+def select_frontiers(state: DraftState, rank_by_value: bool = True) -> np.ndarray:
     """The "w/o reranking" ablation of Section 5.2: the draft is what the expansion
     phase itself selected -- every layer's k best nodes (the frontiers, plus the k
-    best of the last layer, which is never expanded)."""
+    best of the last layer, which is never expanded).  The last layer is ranked the
+    way the expansion phase ranks: by value, or by the nodes' own confidence when
+    value is switched off too ("w/o both" in Table 3)."""
     k, D = state.topk, state.depth
     ids = [int(c) for c in state.frontier[1:].reshape(-1) if c >= 0]
     last = np.arange(cand_base(D - 1, k), n_candidates(D, k))
-    ids += [int(c) for c in last[np.lexsort((last, -state.score[last]))[:k]]]
+    key = state.score[last] if rank_by_value else state.own[last]
+    ids += [int(c) for c in last[np.lexsort((last, -key))[:k]]]
     return np.array(sorted(set(ids)), dtype=np.int64)
 
 
@@ -244,9 +249,10 @@ def flatten(state: DraftState, selected: np.ndarray, root_token: int, prefix_len
 
 
 def rerank(state: DraftState, n_tree: int, root_token: int, prefix_len: int,
-           use_rerank: bool = True) -> FlatTree:
-    """Top-(n_tree - 1) of all candidates by value, flattened behind the root."""
-    sel = select_top(state, n_tree - 1) if use_rerank else select_frontiers(state)
+           use_rerank: bool = True, rank_by_value: bool = True) -> FlatTree:
+    """Top-(n_tree - 1) of all candidates by value, flattened behind the root.
+    use_rerank=False: the expansion phase's own selection (n_tree is then D*k + 1)."""
+    sel = select_top(state, n_tree - 1) if use_rerank else select_frontiers(state, rank_by_value)
     return flatten(state, sel, root_token, prefix_len)
 
 

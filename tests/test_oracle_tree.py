@@ -294,3 +294,41 @@ def test_ablation_switches():
     last = list(range(orc.cand_base(D - 1, k), orc.n_candidates(D, k)))
     last_best = sorted(last, key=lambda c: -a.score[c])[:k]
     assert set(t.cand[1:].tolist()) == set(a.frontier[1:].reshape(-1).tolist()) | set(last_best)
+
+
+def test_ablation_closed_forms_context_free():
+    """Section 5.2 on a context-free draft (every row has the same distribution c_1 > c_2 > ...),
+    where both ablated selections have closed forms that differ from the full method's.
+    Ranked by confidence, the k rank-0 children (one per parent) tie at c_1 and win in parent
+    order; ranked by value, slot 0's children compete with their parent's head start.
+    Without reranking the tree has exactly k nodes per layer."""
+    D, k, V = 4, 3, 12
+    x = np.linspace(2.0, -3.0, V)                      # strictly decreasing logits: token v has rank v
+    W = np.eye(V)
+    H = [np.tile(x, (1 if d == 0 else k, 1)) for d in range(D)]
+    lp = x - np.log(np.sum(np.exp(x)))
+    conf, val = orc.DraftState(D, k), orc.DraftState(D, k)
+    for d in range(D):
+        orc.expand(conf, d, H[d], W, rank_by_value=False)
+        orc.expand(val, d, H[d], W)
+    for d in range(2, D):
+        base = orc.cand_base(d - 1, k)
+        assert conf.frontier[d].tolist() == [base + s * k for s in range(k)]       # rank-0 child of every slot
+        assert np.allclose(conf.own[conf.frontier[d]], lp[0])
+    # by value the best path keeps winning: frontier 2 = children 0, 1 of slot 0 and child 0 of slot 1
+    # iff 2*lp[0] > lp[0]+lp[1] > max(lp[1]+lp[0] (tie, higher id), lp[0]+lp[2])
+    assert val.frontier[2].tolist() == [orc.cand_base(1, k), orc.cand_base(1, k) + 1, orc.cand_base(1, k) + k]
+    # w/o reranking: k nodes per layer, D*k + 1 rows; last layer by confidence = rank-0 children again
+    t_both = orc.rerank(conf, D * k + 1, 0, 0, use_rerank=False, rank_by_value=False)
+    assert np.bincount(t_both.depth).tolist() == [1] + [k] * D
+    lastb = orc.cand_base(D - 1, k)
+    assert t_both.cand[-k:].tolist() == [lastb + s * k for s in range(k)]
+    t_val = orc.rerank(val, D * k + 1, 0, 0, use_rerank=False)
+    assert np.bincount(t_val.depth).tolist() == [1] + [k] * D
+    best_last = sorted(range(lastb, orc.n_candidates(D, k)), key=lambda c: (-val.score[c], c))[:k]
+    assert sorted(t_val.cand[-k:].tolist()) == sorted(best_last)
+    # value of every node is the sum of its path's confidences (value equation, Section 4.1)
+    for st in (conf, val):
+        for c in range(orc.n_candidates(D, k)):
+            if st.parent[c] >= 0:
+                assert abs(st.score[c] - (st.score[st.parent[c]] + st.own[c])) < 1e-12
