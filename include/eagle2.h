@@ -57,6 +57,15 @@ extern "C" {
 #define EAGLE2_MODE_GREEDY 0
 #define EAGLE2_MODE_SAMPLE 1
 
+/* Bits of eagle2_cfg.flags: the two switches of the ablation study (Section 5.2, Table 3).
+ * RANK_BY_CONFIDENCE ("w/o value"): the expansion phase picks the next frontier by each new
+ * node's own confidence instead of its value (the product along the path).
+ * NO_RERANK ("w/o reranking"): the draft is what the expansion phase itself selected -- the
+ * k nodes expanded in every layer plus the k best nodes of the last layer -- with no global
+ * re-selection; the tree then has exactly D*k + 1 rows. */
+#define EAGLE2_FLAG_RANK_BY_CONFIDENCE 1
+#define EAGLE2_FLAG_NO_RERANK          2
+
 #define EAGLE2_MAX_TOPK    16
 #define EAGLE2_MAX_TREE    128
 #define EAGLE2_MAX_CAND    2048
@@ -74,6 +83,8 @@ typedef struct eagle2_cfg {
     int32_t topk;    /* k                                                         */
     int32_t n_tree;  /* N: flattened rows including the root                     */
     int32_t dtype;   /* EAGLE2_DTYPE_*: element type of H, W, Q, K, V and O      */
+    int32_t flags;   /* 0 = the method as published; EAGLE2_FLAG_* select ablations;
+                        with EAGLE2_FLAG_NO_RERANK n_tree must equal D*k + 1      */
 } eagle2_cfg;
 
 /* Attention geometry.  Supported: head_dim 64 or 128; n_q_heads a multiple of
@@ -106,7 +117,9 @@ size_t eagle2_workspace_bytes(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn
  * Section 4.1, kept as a sum of logs; the root's score is 0).  Children are
  * appended to the candidate arrays at ids base_d + s*k + rank.  If d+1 < D the k
  * new candidates of highest score (ties: lower id) are written to
- * frontier[b,d+1,:], best first (Section 4.1, last paragraph).
+ * frontier[b,d+1,:], best first (Section 4.1, last paragraph).  With
+ * EAGLE2_FLAG_RANK_BY_CONFIDENCE the k new candidates of highest own
+ * log-probability are taken instead (Section 5.2); the stored scores stay joint.
  *
  *   H            [B, F_d, Hd] dtype; sequence b starts at element b*h_seq_stride
  *                (h_seq_stride = 0 means F_d*Hd, i.e. contiguous).
@@ -140,12 +153,17 @@ int eagle2_expand(const eagle2_cfg* cfg, int32_t d,
  *   tree_cand (candidate id, -1 for the root), position_ids: [B, N] int32 outputs
  *   mask_bits    [B, N, ceil(N/64)] uint64 output: bit (j % 64) of word j / 64 of
  *                row i is set iff j == i or row j is an ancestor of row i.
+ *   frontier     [B, D, k] int32 as left by the D expand passes; read only with
+ *                EAGLE2_FLAG_NO_RERANK (may be NULL otherwise).  With that flag the
+ *                selection is frontier rows 1..D-1 plus the k best candidates of
+ *                layer D (by score, or by own confidence = score - parent's score
+ *                with EAGLE2_FLAG_RANK_BY_CONFIDENCE; ties: lower id) (Section 5.2).
  * The candidate arrays must come from D completed eagle2_expand passes (scores
  * non-increasing from parent to child); otherwise tree_parent is unspecified.
  */
 int eagle2_rerank(const eagle2_cfg* cfg,
                   const int32_t* cand_token, const double* cand_score, const int32_t* cand_parent,
-                  const int32_t* root_token, const int32_t* prefix_len,
+                  const int32_t* frontier, const int32_t* root_token, const int32_t* prefix_len,
                   int32_t* tree_token, int32_t* tree_parent, int32_t* tree_depth,
                   int32_t* tree_cand, int32_t* position_ids, uint64_t* mask_bits,
                   void* workspace, size_t workspace_bytes, void* stream);

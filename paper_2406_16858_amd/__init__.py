@@ -8,6 +8,8 @@ library has not been built the import of `binding` raises.
 from .binding import (  # noqa: F401
     AttnCfg,
     Eagle2Error,
+    FLAG_NO_RERANK,
+    FLAG_RANK_BY_CONFIDENCE,
     RoundCfg,
     eagle2_accept,
     eagle2_expand,

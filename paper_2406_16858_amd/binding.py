@@ -13,6 +13,7 @@ _lib = None
 
 DTYPE_F32, DTYPE_BF16 = 0, 1
 MODE_GREEDY, MODE_SAMPLE = 0, 1
+FLAG_RANK_BY_CONFIDENCE, FLAG_NO_RERANK = 1, 2
 
 
 class Eagle2Error(RuntimeError):
@@ -22,7 +23,7 @@ class Eagle2Error(RuntimeError):
 class RoundCfg(C.Structure):
     """Mirror of eagle2_cfg."""
     _fields_ = [("batch", C.c_int32), ("vocab", C.c_int32), ("hidden", C.c_int32), ("depth", C.c_int32),
-                ("topk", C.c_int32), ("n_tree", C.c_int32), ("dtype", C.c_int32)]
+                ("topk", C.c_int32), ("n_tree", C.c_int32), ("dtype", C.c_int32), ("flags", C.c_int32)]
 
     @property
     def n_cand(self) -> int:
@@ -60,7 +61,7 @@ def load_library():
     lib.eagle2_expand.restype = C.c_int
     lib.eagle2_expand.argtypes = [C.POINTER(RoundCfg), i32, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.eagle2_rerank.restype = C.c_int
-    lib.eagle2_rerank.argtypes = [C.POINTER(RoundCfg)] + [vp] * 11 + [vp, sz, vp]
+    lib.eagle2_rerank.argtypes = [C.POINTER(RoundCfg)] + [vp] * 12 + [vp, sz, vp]
     lib.eagle2_tree_attn.restype = C.c_int
     lib.eagle2_tree_attn.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg)] + [vp] * 9 + [vp, sz, vp]
     lib.eagle2_accept.restype = C.c_int
@@ -128,13 +129,14 @@ def eagle2_expand(cfg: RoundCfg, d: int, H: torch.Tensor, W: torch.Tensor, cand_
                              _ptr(draft_logits, torch.float32, "draft_logits"), wp, wb, _stream(stream)))
 
 
-def eagle2_rerank(cfg: RoundCfg, cand_token, cand_score, cand_parent, root_token, prefix_len,
+def eagle2_rerank(cfg: RoundCfg, cand_token, cand_score, cand_parent, frontier, root_token, prefix_len,
                   tree_token, tree_parent, tree_depth, tree_cand, position_ids, mask_bits, workspace=None, stream=None):
     lib = load_library()
     wp, wb = _ws(workspace)
     i32 = torch.int32
     _check(lib.eagle2_rerank(C.byref(cfg), _ptr(cand_token, i32, "cand_token"), _ptr(cand_score, torch.float64, "cand_score"),
-                             _ptr(cand_parent, i32, "cand_parent"), _ptr(root_token, i32, "root_token"),
+                             _ptr(cand_parent, i32, "cand_parent"), _ptr(frontier, i32, "frontier"),
+                             _ptr(root_token, i32, "root_token"),
                              _ptr(prefix_len, i32, "prefix_len"), _ptr(tree_token, i32, "tree_token"),
                              _ptr(tree_parent, i32, "tree_parent"), _ptr(tree_depth, i32, "tree_depth"),
                              _ptr(tree_cand, i32, "tree_cand"), _ptr(position_ids, i32, "position_ids"),

@@ -31,6 +31,11 @@ int validate_cfg(const eagle2_cfg* c) {
     E2_REQUIRE(C <= EAGLE2_MAX_CAND, EAGLE2_ERR_SHAPE, "%lld candidates per round exceed %d", (long long)C, EAGLE2_MAX_CAND);
     E2_REQUIRE(c->n_tree >= 2 && c->n_tree <= EAGLE2_MAX_TREE && c->n_tree - 1 <= C, EAGLE2_ERR_SHAPE,
                "n_tree %d outside [2, min(%d, C+1 = %lld)]", c->n_tree, EAGLE2_MAX_TREE, (long long)C + 1);
+    E2_REQUIRE((c->flags & ~(EAGLE2_FLAG_RANK_BY_CONFIDENCE | EAGLE2_FLAG_NO_RERANK)) == 0, EAGLE2_ERR_ARG,
+               "flags 0x%x contain unknown bits", c->flags);
+    if (c->flags & EAGLE2_FLAG_NO_RERANK)
+        E2_REQUIRE(c->n_tree == c->depth * c->topk + 1, EAGLE2_ERR_SHAPE,
+                   "without reranking the tree has depth*topk + 1 = %d rows, n_tree is %d", c->depth * c->topk + 1, c->n_tree);
     E2_REQUIRE((int64_t)c->vocab * c->n_tree * (int64_t)c->batch < (1ll << 40), EAGLE2_ERR_SHAPE, "logit tensor too large");
     return EAGLE2_OK;
 }

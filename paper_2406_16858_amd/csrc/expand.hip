@@ -327,7 +327,7 @@ __device__ __forceinline__ int count_before(const T* sv, const int* si, int n, T
 
 template <int KC>
 __global__ __launch_bounds__(MG_THREADS)
-void expand_merge_kernel(int d, int F, int k, int D, int C, int G,
+void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confidence,
                          const float* __restrict__ part_ms, const float* __restrict__ part_val,
                          const int* __restrict__ part_idx,
                          int* __restrict__ cand_token, double* __restrict__ cand_score,
@@ -447,7 +447,13 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G,
     if (!s_last) return;
     const int nn = F * k;                               // <= 256 new candidates, ranked by counting
     if (tid < nn) {
-        s_fs[tid] = __hip_atomic_load(cand_score + (size_t)b * C + base + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        double key = __hip_atomic_load(cand_score + (size_t)b * C + base + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (by_confidence && d > 0) {                   // "w/o value" (Section 5.2): the node's own log confidence
+            int par = frontier[((size_t)b * D + d) * k + tid / k];
+            if (par < 0 || par >= C) par = 0;
+            key -= cand_score[(size_t)b * C + par];     // written by an earlier pass
+        }
+        s_fs[tid] = key;
         s_fi[tid] = base + tid;
     }
     __syncthreads();
@@ -507,7 +513,7 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
     E2_HIP(hipGetLastError());
 
     hipLaunchKernelGGL((expand_merge_kernel<KC>), dim3(F, cfg->batch), dim3(MG_THREADS), 0, st,
-                       d, F, k, cfg->depth, n_cand(cfg), G, part_ms, part_val, part_idx,
+                       d, F, k, cfg->depth, n_cand(cfg), G, (cfg->flags & EAGLE2_FLAG_RANK_BY_CONFIDENCE) ? 1 : 0, part_ms, part_val, part_idx,
                        cand_token, cand_score, cand_parent, frontier, done_count);
     E2_HIP(hipGetLastError());
     return EAGLE2_OK;

@@ -14,9 +14,10 @@ namespace eagle2 {
 constexpr int RR_THREADS = 1024;
 
 __global__ __launch_bounds__(RR_THREADS)
-void rerank_kernel(int C, int N, int k, int words,
+void rerank_kernel(int C, int N, int k, int D, int words, int flags,
                    const int* __restrict__ cand_token, const double* __restrict__ cand_score,
-                   const int* __restrict__ cand_parent, const int* __restrict__ root_token,
+                   const int* __restrict__ cand_parent, const int* __restrict__ frontier,
+                   const int* __restrict__ root_token,
                    const int* __restrict__ prefix_len,
                    int* __restrict__ tree_token, int* __restrict__ tree_parent, int* __restrict__ tree_depth,
                    int* __restrict__ tree_cand, int* __restrict__ position_ids,
@@ -33,6 +34,34 @@ void rerank_kernel(int C, int N, int k, int words,
     const int* ctok = cand_token + (size_t)b * C;
     const int* cpar = cand_parent + (size_t)b * C;
 
+    const int nsel = N - 1;
+    if (flags & EAGLE2_FLAG_NO_RERANK) {
+        // Section 5.2, "w/o reranking": the draft is what the expansion phase selected, i.e. the
+        // frontiers of layers 1..D-1 and the k best nodes of layer D (nsel = D*k, checked by the host).
+        const int last = k + (D - 2) * k * k;            // first id of layer D (D >= 2 here; D = 1 has no frontier rows)
+        for (int i = tid; i < C; i += RR_THREADS) s_row_of[i] = -1;
+        for (int i = tid; i < (D - 1) * k; i += RR_THREADS) {
+            int c = frontier[((size_t)b * D + 1) * k + i];
+            if (c < 0 || c >= C) c = 0;                   // garbage in the caller's frontier stays in bounds
+            s_sel[i] = c;
+        }
+        const int nl = D == 1 ? k : k * k;               // size of layer D
+        const int lbase = D == 1 ? 0 : last;
+        if (tid < nl) {
+            const int c = lbase + tid;
+            double key = score[c];
+            if ((flags & EAGLE2_FLAG_RANK_BY_CONFIDENCE) && cpar[c] >= 0 && cpar[c] < C) key -= score[cpar[c]];
+            s_key[tid] = key;
+        }
+        __syncthreads();
+        if (tid < nl) {
+            const double v = s_key[tid];
+            int r = 0;
+            for (int j = 0; j < nl; ++j) r += ranks_before(s_key[j], j, v, tid) ? 1 : 0;
+            if (r < k) s_sel[(D - 1) * k + r] = lbase + tid;
+        }
+        __syncthreads();
+    } else {
     // Rank of every candidate = number of candidates that precede it (score desc, id asc).
     // Candidates are cut into runs of 64.  Inside a run the count is taken with v_readlane
     // broadcasts (no LDS); the run is then laid out sorted in LDS, and the count against every
@@ -73,10 +102,10 @@ void rerank_kernel(int C, int N, int k, int words,
         s_row_of[i] = -1;
     }
     __syncthreads();
-    const int nsel = N - 1;
     for (int i = tid; i < C; i += RR_THREADS)
         if (s_rank[i] < nsel) s_sel[s_rank[i]] = i;
     __syncthreads();
+    }
     int my_row = -1, my_id = -1;
     if (tid < nsel) {
         my_id = s_sel[tid];
@@ -127,7 +156,7 @@ using namespace eagle2;
 
 extern "C" int eagle2_rerank(const eagle2_cfg* cfg,
                              const int32_t* cand_token, const double* cand_score, const int32_t* cand_parent,
-                             const int32_t* root_token, const int32_t* prefix_len,
+                             const int32_t* frontier, const int32_t* root_token, const int32_t* prefix_len,
                              int32_t* tree_token, int32_t* tree_parent, int32_t* tree_depth,
                              int32_t* tree_cand, int32_t* position_ids, uint64_t* mask_bits,
                              void* workspace, size_t workspace_bytes, void* stream) {
@@ -136,10 +165,13 @@ extern "C" int eagle2_rerank(const eagle2_cfg* cfg,
     if (rc != EAGLE2_OK) return rc;
     E2_REQUIRE(cand_token && cand_score && cand_parent && root_token && prefix_len && tree_token && tree_parent &&
                tree_depth && tree_cand && position_ids && mask_bits, EAGLE2_ERR_ARG, "eagle2_rerank: null pointer argument");
+    E2_REQUIRE(frontier || !(cfg->flags & EAGLE2_FLAG_NO_RERANK), EAGLE2_ERR_ARG,
+               "eagle2_rerank: EAGLE2_FLAG_NO_RERANK needs the frontier array");
     const int C = n_cand(cfg);
     const int words = (cfg->n_tree + 63) / 64;
     hipLaunchKernelGGL(rerank_kernel, dim3(cfg->batch), dim3(RR_THREADS), 0, static_cast<hipStream_t>(stream),
-                       C, cfg->n_tree, cfg->topk, words, cand_token, cand_score, cand_parent, root_token, prefix_len,
+                       C, cfg->n_tree, cfg->topk, cfg->depth, words, cfg->flags, cand_token, cand_score, cand_parent, frontier,
+                       root_token, prefix_len,
                        tree_token, tree_parent, tree_depth, tree_cand, position_ids,
                        reinterpret_cast<unsigned long long*>(mask_bits));
     E2_HIP(hipGetLastError());

@@ -18,10 +18,10 @@ from . import binding as _b
 class DraftRound:
     def __init__(self, batch: int, vocab: int, hidden: int, depth: int, topk: int, n_tree: int, dtype: str,
                  n_q_heads: int = 0, n_kv_heads: int = 0, head_dim: int = 0, total_prefix: int = 0,
-                 keep_draft_logits: bool = False, device="cuda"):
+                 keep_draft_logits: bool = False, device="cuda", flags: int = 0):
         self.device = torch.device(device)
         self.cfg = _b.RoundCfg(batch, vocab, hidden, depth, topk, n_tree,
-                               _b.DTYPE_F32 if dtype == "fp32" else _b.DTYPE_BF16)
+                               _b.DTYPE_F32 if dtype == "fp32" else _b.DTYPE_BF16, flags)
         self.attn: Optional[_b.AttnCfg] = None
         if n_q_heads:
             self.attn = _b.AttnCfg(n_q_heads, n_kv_heads, head_dim, 0.0, total_prefix)
@@ -62,7 +62,7 @@ class DraftRound:
 
     # -- Section 4.2 ---------------------------------------------------------------
     def rerank(self, root_token: torch.Tensor, prefix_len: torch.Tensor):
-        _b.eagle2_rerank(self.cfg, self.cand_token, self.cand_score, self.cand_parent, root_token, prefix_len,
+        _b.eagle2_rerank(self.cfg, self.cand_token, self.cand_score, self.cand_parent, self.frontier, root_token, prefix_len,
                          self.tree_token, self.tree_parent, self.tree_depth, self.tree_cand, self.position_ids,
                          self.mask_bits, self.workspace)
 

@@ -63,8 +63,11 @@ def _admissible(picked_vals: np.ndarray, all_vals: np.ndarray, picked_idx: np.nd
             f"{what}: a candidate left out beats a pick by {rest.max() - picked_vals.min():.3e}"
 
 
+FLAG_RANK_BY_CONFIDENCE, FLAG_NO_RERANK = 1, 2      # the C ABI's ablation switches (Section 5.2)
+
+
 def lockstep_expand(rnd, cfg, H_all: torch.Tensor, W: torch.Tensor, W64: np.ndarray = None,
-                    report: Report = None, check_logits: bool = True):
+                    report: Report = None, check_logits: bool = True, flags: int = 0):
     """Runs the D expand passes on the GPU, checking each against the oracle.
     Returns (oracle states continued from the GPU's choices, report)."""
     report = report or Report()
@@ -75,6 +78,7 @@ def lockstep_expand(rnd, cfg, H_all: torch.Tensor, W: torch.Tensor, W64: np.ndar
     H64 = f64(H_all)
     states = [orc.DraftState(D, k) for _ in range(B)]
     rel_tol = REL_TOL[cfg.dtype]
+    by_value = not (flags & FLAG_RANK_BY_CONFIDENCE)
     for d in range(D):
         rnd.expand(d, H_all[:, d], W, h_seq_stride=D * k * cfg.hidden)
         if H_all.is_cuda:
@@ -89,7 +93,7 @@ def lockstep_expand(rnd, cfg, H_all: torch.Tensor, W: torch.Tensor, W64: np.ndar
             st = states[b]
             ref = st.copy()
             dl_ref = np.zeros((orc.n_draft_rows(D, k), cfg.vocab)) if (check_logits and rnd.draft_logits is not None) else None
-            logp = orc.expand(ref, d, H64[b, d, :F], W64, draft_logits=dl_ref)
+            logp = orc.expand(ref, d, H64[b, d, :F], W64, draft_logits=dl_ref, rank_by_value=by_value)
             if dl_ref is not None:
                 rows = [orc.draft_row(d, s, k) for s in range(F)]
                 got = rnd.draft_logits[b, rows].cpu().numpy().astype(np.float64)
@@ -106,6 +110,7 @@ def lockstep_expand(rnd, cfg, H_all: torch.Tensor, W: torch.Tensor, W64: np.ndar
                 st.token[ids] = picks
                 st.parent[ids] = par
                 st.score[ids] = par_score + logp[s, picks]          # oracle values for the GPU's picks
+                st.own[ids] = logp[s, picks]
                 err = np.abs(g_score[b, ids] - st.score[ids])
                 report.max_score_err = max(report.max_score_err, float(err.max()))
                 assert np.all(err <= rel_tol * np.maximum(np.abs(st.score[ids]), 1.0)), \
@@ -114,14 +119,15 @@ def lockstep_expand(rnd, cfg, H_all: torch.Tensor, W: torch.Tensor, W64: np.ndar
                 new = base + np.arange(F * k)
                 gf = g_front[b, d + 1].astype(np.int64)
                 assert gf.min() >= base and gf.max() < base + F * k, f"seq {b} pass {d}: frontier outside the new layer"
-                _admissible(st.score[gf], st.score[new], gf - base, f"seq {b} pass {d} frontier")
-                want = new[np.lexsort((new, -st.score[new]))[:k]]
+                key = st.score if by_value else st.own
+                _admissible(key[gf], key[new], gf - base, f"seq {b} pass {d} frontier")
+                want = new[np.lexsort((new, -key[new]))[:k]]
                 report.swaps_frontier += int(np.sum(gf != want))
                 st.frontier[d + 1] = gf
     return states, report
 
 
-def check_rerank(rnd, cfg, states, root_token: np.ndarray, prefix_len: np.ndarray, report: Report):
+def check_rerank(rnd, cfg, states, root_token: np.ndarray, prefix_len: np.ndarray, report: Report, flags: int = 0):
     """GPU rerank vs oracle: admissible selection, then bit-exact flattening of that selection."""
     B, N, k = cfg.batch, cfg.n_tree, cfg.topk
     t_tok = rnd.tree_token.cpu().numpy()
@@ -136,9 +142,23 @@ def check_rerank(rnd, cfg, states, root_token: np.ndarray, prefix_len: np.ndarra
         sel = t_cand[b, 1:].astype(np.int64)
         assert t_cand[b, 0] == -1 and sel.min() >= 0 and sel.max() < cfg.n_cand
         assert np.all(np.diff(sel) > 0), "flat order must be increasing candidate id"
-        order = np.lexsort((sel, -st.score[sel]))
-        _admissible(st.score[sel][order], st.score, sel[order], f"seq {b} rerank")
-        want = np.sort(orc.select_top(st, N - 1))
+        if flags & FLAG_NO_RERANK:
+            # the expansion phase's own selection: every frontier, plus an admissible top-k of the last layer
+            D = cfg.depth
+            assert N == D * k + 1
+            lbase = orc.cand_base(D - 1, k)              # first id of the last layer
+            picked = sel[sel >= lbase]
+            assert set(sel[sel < lbase].tolist()) == set(st.frontier[1:].reshape(-1).tolist()), \
+                f"seq {b}: rows of layers 1..D-1 are not the expanded frontiers"
+            assert len(picked) == k, f"seq {b}: {len(picked)} last-layer nodes selected, expected {k}"
+            key = st.score if not (flags & FLAG_RANK_BY_CONFIDENCE) else st.own
+            order = np.lexsort((picked, -key[picked]))
+            _admissible(key[picked][order], key[lbase:], picked[order] - lbase, f"seq {b} last-layer top-k")
+            want = orc.select_frontiers(st, not (flags & FLAG_RANK_BY_CONFIDENCE))
+        else:
+            order = np.lexsort((sel, -st.score[sel]))
+            _admissible(st.score[sel][order], st.score, sel[order], f"seq {b} rerank")
+            want = np.sort(orc.select_top(st, N - 1))
         report.swaps_rerank += int(np.sum(sel != want))
         tree = orc.flatten(st, sel, int(root_token[b]), int(prefix_len[b]))
         assert np.array_equal(t_tok[b], tree.token), f"seq {b}: tree tokens differ"
@@ -218,7 +238,7 @@ def check_accept(rnd, cfg, trees, modes, target_logits, temperature, u_accept, u
 
 def run_and_check_round(cfg, device="cuda", h_scale: float = 1.0, plant: bool = False,
                         layers=(0,), attn_seqs=None, attn_heads=None, W=None, W64=None, verbose=True,
-                        round_factory=None):
+                        round_factory=None, flags: int = 0):
     """Runs one draft-plus-verify round of `cfg` on the GPU and checks every stage.
     plant=True plants the target's preferred tokens along a tree path so that sequence b
     accepts min(b mod (D+1), deepest available) tokens in greedy mode."""
@@ -238,14 +258,14 @@ def run_and_check_round(cfg, device="cuda", h_scale: float = 1.0, plant: bool = 
     plens = wl.make_prefix_lengths(cfg)
     modes_l = {"greedy": [0] * B, "sample": [1] * B, "mixed": [b % 2 for b in range(B)]}[cfg.accept]
     rnd = round_factory(B, V, cfg.hidden, D, k, N, cfg.dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
-                     total_prefix=sum(plens), keep_draft_logits=any(modes_l), device=device)
-    states, rep = lockstep_expand(rnd, cfg, H_all, W, W64=W64, report=rep)
+                     total_prefix=sum(plens), keep_draft_logits=any(modes_l), device=device, **({"flags": flags} if flags else {}))
+    states, rep = lockstep_expand(rnd, cfg, H_all, W, W64=W64, report=rep, flags=flags)
 
     root = torch.arange(B, dtype=torch.int32) * 3 + 7
     plen_t = torch.tensor(plens, dtype=torch.int32)
     rnd.rerank(root.to(device), plen_t.to(device))
     sync()
-    trees = check_rerank(rnd, cfg, states, root.numpy(), plen_t.numpy(), rep)
+    trees = check_rerank(rnd, cfg, states, root.numpy(), plen_t.numpy(), rep, flags=flags)
 
     for layer in layers:
         Q, Kp, Vp, Kt, Vt, off = wl.make_attention_inputs(cfg, device, layer=layer, prefix_lens=plens)

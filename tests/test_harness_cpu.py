@@ -24,7 +24,8 @@ class OracleBackedRound:
     """Same attributes and methods as DraftRound, computed by the oracle (test stand-in)."""
 
     def __init__(self, batch, vocab, hidden, depth, topk, n_tree, dtype, n_q_heads=0, n_kv_heads=0, head_dim=0,
-                 total_prefix=0, keep_draft_logits=False, device="cpu"):
+                 total_prefix=0, keep_draft_logits=False, device="cpu", flags=0):
+        self.flags = flags
         self.B, self.V, self.D, self.k, self.N = batch, vocab, depth, topk, n_tree
         C, R = orc.n_candidates(depth, topk), orc.n_draft_rows(depth, topk)
         self.states = [orc.DraftState(depth, topk) for _ in range(batch)]
@@ -39,7 +40,7 @@ class OracleBackedRound:
         F = 1 if d == 0 else self.k
         for b, st in enumerate(self.states):
             dl = np.zeros((orc.n_draft_rows(self.D, self.k), self.V))
-            orc.expand(st, d, pu.f64(H[b, :F]), pu.f64(W), draft_logits=dl)
+            orc.expand(st, d, pu.f64(H[b, :F]), pu.f64(W), draft_logits=dl, rank_by_value=not (self.flags & 1))
             self.cand_token[b] = torch.from_numpy(st.token.astype(np.int32))
             self.cand_score[b] = torch.from_numpy(st.score)
             self.cand_parent[b] = torch.from_numpy(st.parent.astype(np.int32))
@@ -51,7 +52,8 @@ class OracleBackedRound:
 
     def rerank(self, root_token, prefix_len):
         N = self.N
-        self.trees = [orc.rerank(st, N, int(root_token[b]), int(prefix_len[b])) for b, st in enumerate(self.states)]
+        self.trees = [orc.rerank(st, N, int(root_token[b]), int(prefix_len[b]), use_rerank=not (self.flags & 2),
+                                 rank_by_value=not (self.flags & 1)) for b, st in enumerate(self.states)]
         t = self.trees
         as32 = lambda f: torch.from_numpy(np.stack([getattr(x, f) for x in t]).astype(np.int32))
         self.tree_token, self.tree_parent, self.tree_depth = as32("token"), as32("parent"), as32("depth")
@@ -98,6 +100,26 @@ def test_harness_accepts_an_exact_round(scale, plant):
     assert rep.max_score_err == 0.0
     if plant:
         assert res[0].accept_len == 0 and res[1].accept_len in (0, 1)     # b mod (D+1), greedy only for even b
+
+
+@pytest.mark.parametrize("flags", [1, 2, 3])
+def test_harness_accepts_an_exact_ablated_round(flags):
+    """Section 5.2's switches: the harness follows the ablated oracle, and a round that ignores
+    the switch is rejected."""
+    cfg = _cfg(n_tree=3 * 3 + 1 if flags & 2 else 12)
+    rep, trees, _ = pu.run_and_check_round(cfg, device="cpu", h_scale=3.0, round_factory=OracleBackedRound,
+                                           verbose=False, flags=flags)
+    assert rep.swaps_frontier == rep.swaps_rerank == 0
+    if flags & 2:
+        assert all(np.bincount(t.depth).tolist() == [1, 3, 3, 3] for t in trees)
+
+    class IgnoresFlags(OracleBackedRound):
+        def __init__(self, *a, flags=0, **kw):
+            super().__init__(*a, flags=0, **kw)
+
+    with pytest.raises(AssertionError):
+        pu.run_and_check_round(_cfg(n_tree=cfg.n_tree, batch=4), device="cpu", h_scale=3.0, round_factory=IgnoresFlags,
+                               verbose=False, flags=flags)
 
 
 def test_harness_rejects_a_wrong_parent_and_a_wrong_token():
