@@ -18,6 +18,9 @@ the paper's steps in the paper's order:
   accept_*    Section 2.1 (front-to-back acceptance with min(1, p/p_hat), residual
               norm(max(0, p - p_hat))) and Section 2.2 ("Verification Stage":
               alternative branches are attempted after a rejection)
+  commit_*    Section 2.1 (accepted tokens are kept, the rest of the draft is
+              discarded) on a pre-allocated KV cache (Appendix, "Implementation
+              Details"): what one round leaves behind for the next
 
 Conventions (readings of points the paper leaves open; listed in the design
 notes of this repository):
@@ -35,7 +38,10 @@ the invariants the paper states.  accept_sample is pinned for the chain case
 (Section 2.1's rule) and by the exactness of the emitted-token law; the order in
 which sibling branches are tried and the renormalisation of the draft
 distribution after a rejected sibling are this repository's reading of Section
-2.2 -- "parity unpinned" by the paper for that particular choice.
+2.2 -- "parity unpinned" by the paper for that particular choice.  commit_* is
+pinned by multi-round decoding: the emitted stream equals vanilla greedy
+decoding, and attention over the committed cache equals attention over an
+explicitly concatenated prefix.
 """
 from __future__ import annotations
 
@@ -381,3 +387,44 @@ def accept_sample(target_logits, draft_logits, temperature: float, u_accept, u_b
             hit = np.nonzero(cdf > float(u_bonus[cur]) * total)[0]
             bonus = int(hit[0]) if hit.size else int(np.nonzero(p > 0.0)[0][-1])
             return AcceptResult(len(path) - 1, path, bonus, trace, p)
+
+
+# ----------------------------------------------------------------------------
+# what a round leaves behind (Section 2.1: keep the accepted tokens, discard the rest)
+# ----------------------------------------------------------------------------
+
+def commit_kv(K_cache, V_cache, region_start: int, region_end: int, prefix_len: int,
+              K_tree, V_tree, path) -> int:
+    """Appends the keys/values of the accepted rows to the sequence's region of a
+    pre-allocated cache.  `path` is the accepted path in flat rows, root first: the
+    root is the last committed token, whose key/value this verification pass
+    computed, so len(path) = accept_len + 1 rows are appended behind the prefix_len
+    rows already there.  Rows of rejected branches are not copied anywhere.  Rows
+    that would fall outside the region are dropped.  Returns the new prefix length
+    (of the rows that fitted)."""
+    n = int(prefix_len)
+    for row in path:
+        dst = region_start + n
+        if dst >= region_end:
+            break
+        K_cache[dst] = K_tree[int(row)]
+        V_cache[dst] = V_tree[int(row)]
+        n += 1
+    return n
+
+
+@dataclass
+class RoundOutput:
+    tokens: List[int]        # tokens this round adds to the text: the accepted draft tokens, then the bonus token
+    root_token: int          # root of the next round's tree = the bonus token
+    prefix_len: int          # KV rows after the round
+    next_hidden: Optional[np.ndarray]   # target feature at the last accepted row (input of the next draft)
+
+
+def commit_round(tree_token, path, bonus_token: int, prefix_len: int, target_hidden=None) -> RoundOutput:
+    """The accepted draft tokens are kept, followed by the token the target emitted
+    at the last accepted row (Section 2.1); it becomes the next root.  The KV prefix
+    grows by the root and the accepted tokens (the bonus token has no key yet)."""
+    toks = [int(tree_token[int(r)]) for r in path[1:]] + [int(bonus_token)]
+    nh = None if target_hidden is None else np.array(target_hidden[int(path[-1])], copy=True)
+    return RoundOutput(toks, int(bonus_token), int(prefix_len) + len(path), nh)
