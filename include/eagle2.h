@@ -3,7 +3,8 @@
  * round of the context-aware dynamic draft tree of EAGLE-2 (arXiv 2406.16858).
  *
  * One round = depth x eagle2_expand, eagle2_rerank, eagle2_tree_attn (once per
- * attention layer of the verifying model), eagle2_accept.
+ * attention layer of the verifying model), eagle2_accept; eagle2_commit_kv and
+ * eagle2_commit_round carry the accepted tokens over to the next round.
  *
  * Common rules for every entry point
  *   - Every pointer is caller-owned DEVICE memory on the current HIP device,
@@ -180,6 +181,10 @@ int eagle2_rerank(const eagle2_cfg* cfg,
  *   K_prefix, V_prefix  [total_prefix, Hkv, dh] dtype; sequence b owns rows
  *                kv_offsets[b] .. kv_offsets[b+1]-1
  *   kv_offsets   [B+1] int64 (device), non-decreasing, kv_offsets[0] = 0
+ *   prefix_len   nullable; [B] int32 (device).  With a pre-allocated KV cache
+ *                (Appendix "Implementation Details") sequence b's region
+ *                kv_offsets[b] .. kv_offsets[b+1]-1 is only partly filled: P_b =
+ *                prefix_len[b] (clamped to the region).  NULL: the whole region.
  *   K_tree, V_tree      [B, N, Hkv, dh] dtype
  *   mask_bits    as written by eagle2_rerank
  *   O            [B, N, Hq, dh] dtype output
@@ -187,7 +192,8 @@ int eagle2_rerank(const eagle2_cfg* cfg,
  */
 int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn,
                      const void* Q, const void* K_prefix, const void* V_prefix,
-                     const int64_t* kv_offsets, const void* K_tree, const void* V_tree,
+                     const int64_t* kv_offsets, const int32_t* prefix_len,
+                     const void* K_tree, const void* V_tree,
                      const uint64_t* mask_bits, void* O, float* lse,
                      void* workspace, size_t workspace_bytes, void* stream);
 
@@ -222,6 +228,58 @@ int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
                   const int32_t* tree_token, const int32_t* tree_parent, const int32_t* tree_cand,
                   int32_t* accept_len, int32_t* accept_path, int32_t* bonus_token,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Commit of a round, part 1: the KV cache (Section 2.1: accepted tokens are kept
+ * and the remaining draft is discarded; Appendix "Implementation Details": the KV
+ * cache is pre-allocated).
+ *
+ * For every sequence b and every layer l, the keys and values of the accepted
+ * path accept_path[b, 0 .. accept_len[b]] (root first; the root is the last
+ * committed token, whose key this verification pass computed) are copied from
+ * the tree tensors to rows kv_offsets[b] + prefix_len[b] + i of the cache, behind
+ * the prefix_len[b] rows already there.  Rows of rejected branches are not
+ * copied.  Rows that would fall at or beyond kv_offsets[b+1] are dropped (the
+ * caller sizes each region for prefix + D + 1 more rows).  prefix_len is not
+ * changed here: eagle2_commit_round advances it once all layers are committed.
+ *
+ *   n_layers            layers committed by this call (>= 1)
+ *   accept_len, accept_path   outputs of eagle2_accept
+ *   kv_offsets   [B+1] int64: regions of the cache, as for eagle2_tree_attn
+ *   prefix_len   [B] int32: filled rows of each region before the round
+ *   K_tree, V_tree      [n_layers][B, N, Hkv, dh] dtype, layers tree_layer_stride
+ *                       elements apart
+ *   K_cache, V_cache    [n_layers][total_prefix, Hkv, dh] dtype in/out, layers
+ *                       cache_layer_stride elements apart (attn->total_prefix =
+ *                       kv_offsets[B] rows per layer)
+ * Strides are in elements and multiples of 16 bytes; with n_layers = 1 they are
+ * ignored.
+ */
+int eagle2_commit_kv(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int32_t n_layers,
+                     const int32_t* accept_len, const int32_t* accept_path,
+                     const int64_t* kv_offsets, const int32_t* prefix_len,
+                     const void* K_tree, const void* V_tree, int64_t tree_layer_stride,
+                     void* K_cache, void* V_cache, int64_t cache_layer_stride, void* stream);
+
+/*
+ * Commit of a round, part 2: tokens and bookkeeping (Section 2.1; Section 2.2,
+ * "Drafting Stage": the next draft starts from the target's feature and the token
+ * sequence advanced by one step).
+ *
+ *   out_tokens   [B, D+1] int32 output: the tokens this round adds to the text --
+ *                the accept_len[b] accepted draft tokens, then bonus_token[b];
+ *                -1 padded
+ *   root_token   [B] int32 output: root of the next round's tree (= bonus_token)
+ *   prefix_len   [B] int32 in/out: advanced by accept_len[b] + 1 (the root and the
+ *                accepted tokens now have KV rows; the bonus token has none yet)
+ *   target_hidden  nullable; [B, N, Hd] dtype: the verifying model's feature per
+ *                tree row.  next_hidden [B, Hd] dtype output (given together with
+ *                target_hidden): the feature at the last accepted row.
+ */
+int eagle2_commit_round(const eagle2_cfg* cfg, const int32_t* accept_len, const int32_t* accept_path,
+                        const int32_t* tree_token, const int32_t* bonus_token, const void* target_hidden,
+                        int32_t* out_tokens, int32_t* root_token, int32_t* prefix_len, void* next_hidden,
+                        void* stream);
 
 /*
  * Kernel timing for benchmarks (not part of the method).  While enabled, every

@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     FLAG_RANK_BY_CONFIDENCE,
     RoundCfg,
     eagle2_accept,
+    eagle2_commit_kv,
+    eagle2_commit_round,
     eagle2_expand,
     eagle2_kernel_timing_enable,
     eagle2_kernel_timing_read,

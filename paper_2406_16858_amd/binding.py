@@ -63,9 +63,13 @@ def load_library():
     lib.eagle2_rerank.restype = C.c_int
     lib.eagle2_rerank.argtypes = [C.POINTER(RoundCfg)] + [vp] * 12 + [vp, sz, vp]
     lib.eagle2_tree_attn.restype = C.c_int
-    lib.eagle2_tree_attn.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg)] + [vp] * 9 + [vp, sz, vp]
+    lib.eagle2_tree_attn.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg)] + [vp] * 10 + [vp, sz, vp]
     lib.eagle2_accept.restype = C.c_int
     lib.eagle2_accept.argtypes = [C.POINTER(RoundCfg)] + [vp] * 12 + [vp, sz, vp]
+    lib.eagle2_commit_kv.restype = C.c_int
+    lib.eagle2_commit_kv.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg), i32, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
+    lib.eagle2_commit_round.restype = C.c_int
+    lib.eagle2_commit_round.argtypes = [C.POINTER(RoundCfg)] + [vp] * 9 + [vp]
     lib.eagle2_kernel_timing_enable.restype = C.c_int
     lib.eagle2_kernel_timing_enable.argtypes = [i32]
     lib.eagle2_kernel_timing_read.restype = C.c_int
@@ -144,13 +148,13 @@ def eagle2_rerank(cfg: RoundCfg, cand_token, cand_score, cand_parent, frontier, 
 
 
 def eagle2_tree_attn(cfg: RoundCfg, attn: AttnCfg, Q, K_prefix, V_prefix, kv_offsets, K_tree, V_tree, mask_bits,
-                     O, lse, workspace, stream=None):
+                     O, lse, workspace, stream=None, prefix_len=None):
     lib = load_library()
     el = _elem(cfg)
     wp, wb = _ws(workspace)
     _check(lib.eagle2_tree_attn(C.byref(cfg), C.byref(attn), _ptr(Q, el, "Q"), _ptr(K_prefix, el, "K_prefix"),
                                 _ptr(V_prefix, el, "V_prefix"), _ptr(kv_offsets, torch.int64, "kv_offsets"),
-                                _ptr(K_tree, el, "K_tree"), _ptr(V_tree, el, "V_tree"),
+                                _ptr(prefix_len, torch.int32, "prefix_len"), _ptr(K_tree, el, "K_tree"), _ptr(V_tree, el, "V_tree"),
                                 _ptr(mask_bits, torch.int64, "mask_bits"), _ptr(O, el, "O"),
                                 _ptr(lse, torch.float32, "lse"), wp, wb, _stream(stream)))
 
@@ -167,6 +171,28 @@ def eagle2_accept(cfg: RoundCfg, mode, target_logits, draft_logits, temperature,
                              _ptr(tree_cand, i32, "tree_cand"), _ptr(accept_len, i32, "accept_len"),
                              _ptr(accept_path, i32, "accept_path"), _ptr(bonus_token, i32, "bonus_token"),
                              wp, wb, _stream(stream)))
+
+
+def eagle2_commit_kv(cfg: RoundCfg, attn: AttnCfg, n_layers: int, accept_len, accept_path, kv_offsets, prefix_len,
+                     K_tree, V_tree, tree_layer_stride: int, K_cache, V_cache, cache_layer_stride: int, stream=None):
+    lib = load_library()
+    el, i32 = _elem(cfg), torch.int32
+    _check(lib.eagle2_commit_kv(C.byref(cfg), C.byref(attn), n_layers, _ptr(accept_len, i32, "accept_len"),
+                                _ptr(accept_path, i32, "accept_path"), _ptr(kv_offsets, torch.int64, "kv_offsets"),
+                                _ptr(prefix_len, i32, "prefix_len"), _ptr(K_tree, el, "K_tree"), _ptr(V_tree, el, "V_tree"),
+                                tree_layer_stride, _ptr(K_cache, el, "K_cache"), _ptr(V_cache, el, "V_cache"),
+                                cache_layer_stride, _stream(stream)))
+
+
+def eagle2_commit_round(cfg: RoundCfg, accept_len, accept_path, tree_token, bonus_token, target_hidden,
+                        out_tokens, root_token, prefix_len, next_hidden, stream=None):
+    lib = load_library()
+    el, i32 = _elem(cfg), torch.int32
+    _check(lib.eagle2_commit_round(C.byref(cfg), _ptr(accept_len, i32, "accept_len"), _ptr(accept_path, i32, "accept_path"),
+                                   _ptr(tree_token, i32, "tree_token"), _ptr(bonus_token, i32, "bonus_token"),
+                                   _ptr(target_hidden, el, "target_hidden"), _ptr(out_tokens, i32, "out_tokens"),
+                                   _ptr(root_token, i32, "root_token"), _ptr(prefix_len, i32, "prefix_len"),
+                                   _ptr(next_hidden, el, "next_hidden"), _stream(stream)))
 
 
 def eagle2_kernel_timing_enable(enable: bool):

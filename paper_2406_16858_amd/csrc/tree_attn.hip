@@ -25,13 +25,21 @@ constexpr float NEG_BIG = -1.0e30f;
 
 struct SeqChunk { int b; int c; int nc; long long off; long long P; int first; };
 
+// Keys of sequence b's prefix: its whole region of the KV buffer, or the filled part of it when
+// the caller keeps a pre-allocated cache (kv_len, clamped to the region).
+__device__ __forceinline__ long long prefix_keys(int b, const long long* kv_offsets, const int* kv_len) {
+    const long long region = kv_offsets[b + 1] - kv_offsets[b];
+    if (kv_len == nullptr) return region;
+    const long long n = kv_len[b];
+    return n < 0 ? 0 : (n < region ? n : region);
+}
 // Maps a flat chunk index to (sequence, chunk); chunks of sequence b are
 // ceil(P_b / chunk) prefix chunks followed by the tree chunk.
-__device__ __forceinline__ bool locate_chunk(int flat, int B, int chunk, const long long* kv_offsets, SeqChunk& sc) {
+__device__ __forceinline__ bool locate_chunk(int flat, int B, int chunk, const long long* kv_offsets, const int* kv_len, SeqChunk& sc) {
     int rem = flat, first = 0;
     for (int b = 0; b < B; ++b) {
         const long long off = kv_offsets[b];
-        const long long P = kv_offsets[b + 1] - off;
+        const long long P = prefix_keys(b, kv_offsets, kv_len);
         const int nc = (int)((P + chunk - 1) / chunk) + 1;
         if (rem < nc) { sc.b = b; sc.c = rem; sc.nc = nc; sc.off = off; sc.P = P; sc.first = first; return true; }
         rem -= nc;
@@ -39,10 +47,10 @@ __device__ __forceinline__ bool locate_chunk(int flat, int B, int chunk, const l
     }
     return false;
 }
-__device__ __forceinline__ void locate_seq(int b, int chunk, const long long* kv_offsets, int& first, int& nc) {
+__device__ __forceinline__ void locate_seq(int b, int chunk, const long long* kv_offsets, const int* kv_len, int& first, int& nc) {
     first = 0;
-    for (int i = 0; i < b; ++i) first += (int)((kv_offsets[i + 1] - kv_offsets[i] + chunk - 1) / chunk) + 1;
-    nc = (int)((kv_offsets[b + 1] - kv_offsets[b] + chunk - 1) / chunk) + 1;
+    for (int i = 0; i < b; ++i) first += (int)((prefix_keys(i, kv_offsets, kv_len) + chunk - 1) / chunk) + 1;
+    nc = (int)((prefix_keys(b, kv_offsets, kv_len) + chunk - 1) / chunk) + 1;
 }
 
 template <int DH> __device__ __forceinline__ int k_swz(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
@@ -51,7 +59,8 @@ __device__ __forceinline__ int v_swz(int row) { return (row & 15) ^ (((row >> 4)
 template <int DH, int RBW>
 __global__ __launch_bounds__(TA_THREADS)
 void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kp, const uint16_t* __restrict__ Vp,
-                           const long long* __restrict__ kv_offsets, const uint16_t* __restrict__ Kt,
+                           const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len,
+                           const uint16_t* __restrict__ Kt,
                            const uint16_t* __restrict__ Vt, const unsigned long long* __restrict__ mask_bits,
                            int B, int N, int Hq, int Hkv, int chunk, int words, int nmblk, int rows_pad,
                            float scale_log2e, float* __restrict__ part_o, float* __restrict__ part_ml) {
@@ -61,7 +70,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     __shared__ __align__(16) uint8_t s_vt[DH * TA_KEYS * 2];
 
     SeqChunk sc;
-    if (!locate_chunk(blockIdx.x, B, chunk, kv_offsets, sc)) return;
+    if (!locate_chunk(blockIdx.x, B, chunk, kv_offsets, kv_len, sc)) return;
     const int kvh = blockIdx.y / nmblk, mblk = blockIdx.y - kvh * nmblk;
     const int grp = Hq / Hkv, rows = grp * N;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -245,7 +254,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
 // partial outputs, whose loads are independent and issued four chunks at a time.
 template <int DH>
 __global__ __launch_bounds__(256)
-void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, int N, int Hq, int Hkv, int chunk, int rows_pad,
+void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len, int N, int Hq, int Hkv, int chunk, int rows_pad,
                               const float* __restrict__ part_o, const float* __restrict__ part_ml,
                               uint16_t* __restrict__ O, float* __restrict__ lse) {
     const int bn = blockIdx.x, b = bn / N, n = bn - b * N;
@@ -253,7 +262,7 @@ void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, int N, i
     if (h >= Hq) return;
     const int grp = Hq / Hkv, kvh = h / grp, rho = n * grp + (h - kvh * grp);
     int first, nc;
-    locate_seq(b, chunk, kv_offsets, first, nc);
+    locate_seq(b, chunk, kv_offsets, kv_len, first, nc);
     const size_t cstride = (size_t)Hkv * rows_pad;               // rows between consecutive chunks
     const size_t row0 = ((size_t)first * Hkv + kvh) * rows_pad + rho;
     float mx = NEG_BIG;
@@ -305,7 +314,8 @@ void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, int N, i
 template <int DH>
 __global__ __launch_bounds__(256)
 void tree_attn_f32_kernel(const float* __restrict__ Q, const float* __restrict__ Kp, const float* __restrict__ Vp,
-                          const long long* __restrict__ kv_offsets, const float* __restrict__ Kt,
+                          const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len,
+                          const float* __restrict__ Kt,
                           const float* __restrict__ Vt, const unsigned long long* __restrict__ mask_bits,
                           int N, int Hq, int Hkv, int words, float scale, float* __restrict__ O, float* __restrict__ lse) {
     constexpr int E = DH / 64;
@@ -313,7 +323,7 @@ void tree_attn_f32_kernel(const float* __restrict__ Q, const float* __restrict__
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int kvh = h / (Hq / Hkv);
     const long long off = kv_offsets[b];
-    const int P = (int)(kv_offsets[b + 1] - off);
+    const int P = (int)prefix_keys(b, kv_offsets, kv_len);
     float q[E], o[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) { q[e] = Q[((size_t)bn * Hq + h) * DH + e * 64 + lane]; o[e] = 0.f; }
@@ -399,7 +409,8 @@ using namespace eagle2;
 
 extern "C" int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn,
                                 const void* Q, const void* K_prefix, const void* V_prefix,
-                                const int64_t* kv_offsets, const void* K_tree, const void* V_tree,
+                                const int64_t* kv_offsets, const int32_t* kv_len,
+                                const void* K_tree, const void* V_tree,
                                 const uint64_t* mask_bits, void* O, float* lse,
                                 void* workspace, size_t workspace_bytes, void* stream) {
     int rc = validate_cfg(cfg);
@@ -422,11 +433,11 @@ extern "C" int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* at
         timing_begin(1, st);
         if (dh == 128)
             hipLaunchKernelGGL((tree_attn_f32_kernel<128>), grid, dim3(256), 0, st, (const float*)Q, (const float*)K_prefix,
-                               (const float*)V_prefix, offs, (const float*)K_tree, (const float*)V_tree, mb, N, Hq, Hkv, words,
+                               (const float*)V_prefix, offs, kv_len, (const float*)K_tree, (const float*)V_tree, mb, N, Hq, Hkv, words,
                                scale, (float*)O, lse);
         else
             hipLaunchKernelGGL((tree_attn_f32_kernel<64>), grid, dim3(256), 0, st, (const float*)Q, (const float*)K_prefix,
-                               (const float*)V_prefix, offs, (const float*)K_tree, (const float*)V_tree, mb, N, Hq, Hkv, words,
+                               (const float*)V_prefix, offs, kv_len, (const float*)K_tree, (const float*)V_tree, mb, N, Hq, Hkv, words,
                                scale, (float*)O, lse);
         timing_end(1, st);
         E2_HIP(hipGetLastError());
@@ -443,7 +454,7 @@ extern "C" int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* at
     timing_begin(1, st);
 #define E2_ATTN(DHV, RB)                                                                                              \
     hipLaunchKernelGGL((tree_attn_bf16_kernel<DHV, RB>), grid, dim3(TA_THREADS), 0, st, (const uint16_t*)Q,            \
-                       (const uint16_t*)K_prefix, (const uint16_t*)V_prefix, offs, (const uint16_t*)K_tree,            \
+                       (const uint16_t*)K_prefix, (const uint16_t*)V_prefix, offs, kv_len, (const uint16_t*)K_tree,            \
                        (const uint16_t*)V_tree, mb, B, N, Hq, Hkv, p.chunk, words, p.nmblk, p.rows_pad, sl2, part_o, part_ml)
     if (dh == 128) { if (p.rbw == 2) E2_ATTN(128, 2); else E2_ATTN(128, 1); }
     else           { if (p.rbw == 2) E2_ATTN(64, 2); else E2_ATTN(64, 1); }
@@ -452,10 +463,10 @@ extern "C" int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* at
     E2_HIP(hipGetLastError());
     dim3 cgrid(B * N, (Hq + 3) / 4);
     if (dh == 128)
-        hipLaunchKernelGGL((tree_attn_combine_kernel<128>), cgrid, dim3(256), 0, st, offs, N, Hq, Hkv, p.chunk, p.rows_pad,
+        hipLaunchKernelGGL((tree_attn_combine_kernel<128>), cgrid, dim3(256), 0, st, offs, kv_len, N, Hq, Hkv, p.chunk, p.rows_pad,
                            part_o, part_ml, (uint16_t*)O, lse);
     else
-        hipLaunchKernelGGL((tree_attn_combine_kernel<64>), cgrid, dim3(256), 0, st, offs, N, Hq, Hkv, p.chunk, p.rows_pad,
+        hipLaunchKernelGGL((tree_attn_combine_kernel<64>), cgrid, dim3(256), 0, st, offs, kv_len, N, Hq, Hkv, p.chunk, p.rows_pad,
                            part_o, part_ml, (uint16_t*)O, lse);
     E2_HIP(hipGetLastError());
     return EAGLE2_OK;

@@ -66,12 +66,22 @@ class DraftRound:
                          self.tree_token, self.tree_parent, self.tree_depth, self.tree_cand, self.position_ids,
                          self.mask_bits, self.workspace)
 
-    def tree_attn(self, Q, K_prefix, V_prefix, kv_offsets, K_tree, V_tree, O, lse=None):
+    def tree_attn(self, Q, K_prefix, V_prefix, kv_offsets, K_tree, V_tree, O, lse=None, prefix_len=None):
         _b.eagle2_tree_attn(self.cfg, self.attn, Q, K_prefix, V_prefix, kv_offsets, K_tree, V_tree, self.mask_bits,
-                            O, lse, self.workspace)
+                            O, lse, self.workspace, prefix_len=prefix_len)
 
     # -- Sections 2.1 / 2.2 -----------------------------------------------------------
     def accept(self, mode, target_logits, temperature=None, u_accept=None, u_bonus=None):
         _b.eagle2_accept(self.cfg, mode, target_logits, self.draft_logits, temperature, u_accept, u_bonus,
                          self.tree_token, self.tree_parent, self.tree_cand, self.accept_len, self.accept_path,
                          self.bonus_token, self.workspace)
+
+    # -- Section 2.1: what the round leaves behind ----------------------------------------
+    def commit_kv(self, kv_offsets, prefix_len, K_tree, V_tree, K_cache, V_cache, n_layers: int = 1,
+                  tree_layer_stride: int = 0, cache_layer_stride: int = 0):
+        _b.eagle2_commit_kv(self.cfg, self.attn, n_layers, self.accept_len, self.accept_path, kv_offsets, prefix_len,
+                            K_tree, V_tree, tree_layer_stride, K_cache, V_cache, cache_layer_stride)
+
+    def commit_round(self, out_tokens, root_token, prefix_len, target_hidden=None, next_hidden=None):
+        _b.eagle2_commit_round(self.cfg, self.accept_len, self.accept_path, self.tree_token, self.bonus_token,
+                               target_hidden, out_tokens, root_token, prefix_len, next_hidden)

@@ -171,13 +171,16 @@ def check_rerank(rnd, cfg, states, root_token: np.ndarray, prefix_len: np.ndarra
 
 
 def check_attention(cfg, trees, Q, Kp, Vp, Kt, Vt, kv_offsets, O, lse, report: Report,
-                    seqs=None, heads=None):
-    """GPU attention output vs oracle, for all or a sample of (sequence, head)."""
+                    seqs=None, heads=None, prefix_lens=None):
+    """GPU attention output vs oracle, for all or a sample of (sequence, head).
+    prefix_lens: filled rows per region when the KV buffer is a pre-allocated cache."""
     off = kv_offsets.cpu().numpy()
     tol = REL_TOL[cfg.dtype]
     g = cfg.n_q_heads // cfg.n_kv_heads
     for b in (range(cfg.batch) if seqs is None else seqs):
         lo, hi = int(off[b]), int(off[b + 1])
+        if prefix_lens is not None:
+            hi = lo + int(prefix_lens[b])
         hq = list(range(cfg.n_q_heads)) if heads is None else list(heads)
         kvh = sorted({h // g for h in hq})
         # the oracle maps head h -> kv head h // g; feed it the needed kv heads with g preserved
