@@ -303,6 +303,341 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     }
 }
 
+// ---- many frontier rows (more than one 16-row block: batched serving) -----------------------
+// With M > 16 rows the per-lane statistics of lmhead_kernel no longer fit in registers, and
+// re-streaming W once per 16-row block multiplies the HBM traffic.  Instead W is streamed once
+// for up to 160 rows: lmhead_gemm_kernel writes the raw logits [M, V] (to the caller's
+// draft_logits rows, else to the workspace) and row_stats_kernel turns each row into the same
+// (max, sum-exp, top-k) partials the merge kernel reads, one partial per 4096 vocabulary entries.
+constexpr int GB_MBMAX = 10;                 // 16-row blocks per workgroup pass (160 frontier rows)
+constexpr int GB_CHUNK = 256;                // bytes of K per row per stage
+constexpr int GB_WSTAGE = LM_ROWS * GB_CHUNK;            // 16 KB of W per stage
+constexpr int RS_CHUNK = 4096;               // vocabulary entries per row_stats workgroup
+
+// Destination of frontier row m's logits: the caller's [B, R, V] tensor or the dense workspace.
+__device__ __forceinline__ float* logit_row_ptr(int m, int F, int V, float* logits_ws, float* logits_out,
+                                                int logit_rows_per_seq, int logit_row_base) {
+    if (logits_out == nullptr) return logits_ws + (size_t)m * V;
+    const int b = m / F, s = m - b * F;
+    return logits_out + ((size_t)b * logit_rows_per_seq + logit_row_base + s) * (size_t)V;
+}
+
+// Workgroup = 4 waves, task = 64 vocab rows x the whole K; a stage is 256 bytes of K of the 64 W
+// rows and of all the frontier rows of this pass, staged through LDS (XOR-swizzled 16-byte
+// slots) and shared by the waves.  (Reading the frontier fragments straight from global memory
+// in MFMA order instead was measured slower: 16 rows per load instruction.)  Wave (kh, mh)
+// multiplies K half kh of the stage for half mh of the frontier blocks (at most five) with all
+// four 16-row W blocks: the four waves carry the same number of MFMAs, and a W fragment feeds
+// up to five of them.  At the end of a task the two K halves are added through LDS, each wave
+// finishing two of the four W blocks.  In registers, W runs two stages ahead of the
+// multiplication and the frontier rows one.
+constexpr int GB_RED = 4 * (GB_MBMAX / 2) * 2 * 64 * 16;   // bytes of the end-of-task exchange area
+
+template <bool BF16>
+__global__ __launch_bounds__(LM_THREADS, 2)
+void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
+                        const uint8_t* __restrict__ Hraw, int64_t h_seq_bytes, int M, int F, int B,
+                        unsigned* __restrict__ done_count, float* __restrict__ logits_ws,
+                        float* __restrict__ logits_out, int logit_rows_per_seq, int logit_row_base) {
+    constexpr int MH = GB_MBMAX / 2;                   // frontier blocks per wave
+    constexpr int TH = GB_CHUNK / 128;                 // 64-byte K fragments per wave per stage
+    extern __shared__ __align__(16) uint8_t smem[];
+    uint8_t* sW = smem;
+    uint8_t* sH = smem + GB_WSTAGE;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int m16 = lane & 15, g = lane >> 4;          // MFMA lane coordinates
+    const int r16 = tid >> 4, c16 = tid & 15;          // load coordinates: 16 rows x 256 B per instruction
+    const int kh = w & 1, mh = w >> 1;
+    const int G = gridDim.x;
+    const int mb0 = blockIdx.y * GB_MBMAX;
+    const int nmb = min(GB_MBMAX, (M + 15) / 16 - mb0);
+    const int nlo = (nmb + 1) >> 1;
+    const int mfirst = mh ? nlo : 0, mcnt = mh ? nmb - nlo : nlo;   // this wave's frontier blocks
+    const int nst = row_bytes / GB_CHUNK;
+    const int ntask = (V + LM_ROWS - 1) / LM_ROWS;
+    const int tq = ntask / G, tr = ntask - tq * G;
+    const int my_tasks = tq + ((int)blockIdx.x < tr ? 1 : 0);
+    const int task_first = (int)blockIdx.x * tq + min((int)blockIdx.x, tr);
+    const int total = my_tasks * nst;
+
+    if (blockIdx.x == 0 && blockIdx.y == 0)            // counters of the merge kernel's last-arrival test
+        for (int i = tid; i < B; i += LM_THREADS) done_count[i] = 0u;
+
+    // frontier rows this thread stages (row r16 of block j) and the rows it stores
+    const uint8_t* hsrc[GB_MBMAX];
+#pragma unroll
+    for (int j = 0; j < GB_MBMAX; ++j) {
+        const int m = (mb0 + j) * 16 + r16;
+        hsrc[j] = nullptr;
+        if (j < nmb && m < M) {
+            const int b = m / F, s = m - b * F;
+            hsrc[j] = Hraw + (int64_t)b * h_seq_bytes + (int64_t)s * row_bytes + c16 * 16;
+        }
+    }
+    float* lrow[MH];
+#pragma unroll
+    for (int jj = 0; jj < MH; ++jj) {
+        const int m = (mb0 + mfirst + jj) * 16 + m16;
+        lrow[jj] = (jj < mcnt && m < M) ? logit_row_ptr(m, F, V, logits_ws, logits_out, logit_rows_per_seq, logit_row_base)
+                                        : nullptr;
+    }
+
+    // W is fetched two stages ahead (two register sets, used alternately), the frontier rows (L2
+    // hits) one stage ahead and *before* the younger W loads: loads retire in order, so the wait
+    // for a stage's operands leaves the W loads of the stage after it in flight.
+    u32x4 RWa[4], RWb[4], RH[GB_MBMAX];
+    auto issue_h = [&](int it) {
+        const int st = it - (it / nst) * nst;
+        const size_t kb = (size_t)st * GB_CHUNK;
+#pragma unroll
+        for (int j = 0; j < GB_MBMAX; ++j)
+            if (j < nmb) RH[j] = hsrc[j] ? *reinterpret_cast<const u32x4*>(hsrc[j] + kb) : u32x4{0u, 0u, 0u, 0u};
+    };
+    auto issue_w = [&](int it, u32x4 (&RW)[4]) {
+        const int task = task_first + it / nst;
+        const int st = it - (it / nst) * nst;
+        const size_t kb = (size_t)st * GB_CHUNK;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int row = task * LM_ROWS + j * 16 + r16;
+            row = row < V ? row : V - 1;               // ragged tail: re-read the last row, never stored
+            RW[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(W + (size_t)row * row_bytes + kb + c16 * 16));
+        }
+    };
+
+    floatx4 acc[MH][4];
+#pragma unroll
+    for (int jj = 0; jj < MH; ++jj)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) acc[jj][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    auto step = [&](int it, u32x4 (&RW)[4]) {
+        const int ti = it / nst;
+        const int st = it - ti * nst;
+        __syncthreads();                               // the previous stage has been multiplied
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            *reinterpret_cast<u32x4*>(sW + (j * 16 + r16) * GB_CHUNK + ((c16 ^ r16) << 4)) = RW[j];
+#pragma unroll
+        for (int j = 0; j < GB_MBMAX; ++j)
+            if (j < nmb) *reinterpret_cast<u32x4*>(sH + (j * 16 + r16) * GB_CHUNK + ((c16 ^ r16) << 4)) = RH[j];
+        __syncthreads();
+        if (it + 1 < total) issue_h(it + 1);
+        if (it + 2 < total) issue_w(it + 2, RW);
+
+#pragma unroll
+        for (int tt = 0; tt < TH; ++tt) {
+            const int t = kh * TH + tt;                // 64-byte K fragment of the stage
+            u32x4 wf[4];
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+                wf[nb] = *reinterpret_cast<const u32x4*>(sW + ((((nb + 2 * kh) & 3) * 16) + m16) * GB_CHUNK + (((t * 4 + g) ^ m16) << 4));
+#pragma unroll
+            for (int jj = 0; jj < MH; ++jj) {
+                if (jj < mcnt) {                       // uniform over the wave
+                    const u32x4 hf = *reinterpret_cast<const u32x4*>(
+                        sH + ((mfirst + jj) * 16 + m16) * GB_CHUNK + (((t * 4 + g) ^ m16) << 4));
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) {
+                        if constexpr (BF16) {
+                            acc[jj][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8, wf[nb]), __builtin_bit_cast(bf16x8, hf), acc[jj][nb], 0, 0, 0);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                acc[jj][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                                    __uint_as_float(wf[nb][e]), __uint_as_float(hf[e]), acc[jj][nb], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+
+        if (st == nst - 1) {
+            // Add the two K halves: wave kh finishes W blocks 2 kh and 2 kh + 1 (its accumulators 0, 1:
+            // accumulator nb of wave kh belongs to W block (nb + 2 kh) mod 4, so that register
+            // indices stay compile-time constants) and hands the other two to its partner through
+            // LDS (the stage buffers are idle after the barrier).
+            floatx4* red = reinterpret_cast<floatx4*>(smem);
+            __syncthreads();
+#pragma unroll
+            for (int jj = 0; jj < MH; ++jj)
+#pragma unroll
+                for (int nl = 0; nl < 2; ++nl)
+                    if (jj < mcnt) red[(((mh * 2 + (1 - kh)) * MH + jj) * 2 + nl) * 64 + lane] = acc[jj][2 + nl];
+            __syncthreads();
+            // output register i of W block nb: vocab row 64*task + 16*nb + 4*g + i, frontier row of lrow[jj]
+            const int task = task_first + ti;
+#pragma unroll
+            for (int jj = 0; jj < MH; ++jj) {
+#pragma unroll
+                for (int nl = 0; nl < 2; ++nl) {
+                    if (jj < mcnt) {
+                        const floatx4 other = red[(((mh * 2 + kh) * MH + jj) * 2 + nl) * 64 + lane];
+                        const floatx4 y = acc[jj][nl] + other;
+                        const int v0 = task * LM_ROWS + (2 * kh + nl) * 16 + g * 4;
+                        if (lrow[jj] != nullptr && v0 < V) {
+                            if (v0 + 3 < V && (V & 3) == 0) {
+                                *reinterpret_cast<floatx4*>(lrow[jj] + v0) = y;
+                            } else {
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) if (v0 + i < V) lrow[jj][v0 + i] = y[i];
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) acc[jj][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+    };
+    if (total > 0) { issue_w(0, RWa); issue_h(0); }
+    if (total > 1) issue_w(1, RWb);
+    for (int it = 0; it < total; it += 2) {
+        step(it, RWa);
+        if (it + 1 < total) step(it + 1, RWb);
+    }
+}
+
+// (max, sum-exp, top-KC) of RS_CHUNK logits of one frontier row, in the partial format of
+// lmhead_kernel: grid (M, chunks), partial index = chunk; a thread holds 16 values, a wave
+// finds its KC best by counting among the few values above a bound, the four waves' lists are
+// merged by counting.
+template <int KC>
+__global__ __launch_bounds__(256)
+void row_stats_kernel(int V, int F, const float* __restrict__ logits_ws, const float* __restrict__ logits_out,
+                      int logit_rows_per_seq, int logit_row_base,
+                      float* __restrict__ part_ms, float* __restrict__ part_val, int* __restrict__ part_idx) {
+    __shared__ float s_m[4], s_s[4];
+    __shared__ __align__(16) float s_v[4 * KC];
+    __shared__ __align__(16) int s_i[4 * KC];
+    __shared__ __align__(16) float s_cv[4 * 64];       // per wave: values at or above its bound
+    __shared__ __align__(16) int s_ci[4 * 64];
+    const int m = blockIdx.x, chunk = blockIdx.y, G = gridDim.y;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const float* src = logit_row_ptr(m, F, V, const_cast<float*>(logits_ws), const_cast<float*>(logits_out),
+                                     logit_rows_per_seq, logit_row_base);
+    const int c0 = chunk * RS_CHUNK;
+    float x[16];
+    const bool vec = (V & 3) == 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int v = c0 + (i * 256 + tid) * 4;
+        if (vec && v + 3 < V) {
+            const floatx4 y = *reinterpret_cast<const floatx4*>(src + v);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[i * 4 + e] = y[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[i * 4 + e] = v + e < V ? src[v + e] : -INFINITY;
+        }
+    }
+    float mx = x[0];
+#pragma unroll
+    for (int q = 1; q < 16; ++q) mx = fmaxf(mx, x[q]);
+    const float wm = wave_max(mx);
+    if (lane == 0) s_m[w] = wm;
+    __syncthreads();
+    const float bm = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));   // finite: the chunk holds at least one entry
+    float sum = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) sum += __expf(x[q] - bm);                 // exp(-inf) = 0 for the padding
+    sum = wave_sumf(sum);
+    if (lane == 0) s_s[w] = sum;
+
+    // The wave's KC best of its 1024 values.  The KC-th largest of the 64 lane maxima is a lower
+    // bound of the KC-th largest value, so only values at or above it can matter: usually
+    // between KC and 2 KC of them.  They are compacted into LDS and ranked by counting.
+    // (counting through LDS broadcast reads: 16-byte reads of the same address by all lanes)
+    float* cv = s_cv + w * 64;
+    int* ci = s_ci + w * 64;
+    cv[lane] = mx;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    int cge = 0;                                       // lane maxima at or above this lane's
+#pragma unroll
+    for (int j = 0; j < 64; j += 4) {
+        const floatx4 o = *reinterpret_cast<const floatx4*>(cv + j);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cge += o[e] >= mx ? 1 : 0;
+    }
+    const float thr = wave_max(cge >= KC ? mx : -INFINITY);                // the KC-th largest lane maximum
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                 // cv is reused below
+    int ncand = 0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int v = c0 + ((q >> 2) * 256 + tid) * 4 + (q & 3);
+        const bool take = x[q] >= thr && v < V;                            // padding is -inf: never above a finite bound
+        const unsigned long long bal = __ballot(take);
+        const int pos = ncand + __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
+        if (take && pos < 64) { cv[pos] = x[q]; ci[pos] = v; }
+        ncand += __popcll(bal);
+    }
+    if (ncand <= 64) {                                                     // uniform over the wave
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (lane >= ncand) { cv[lane] = -INFINITY; ci[lane] = INT_MAX; }   // pad to a multiple of four
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const float v = cv[lane];
+        const int id = ci[lane];
+        int r = 0;
+        for (int j = 0; j < ncand; j += 4) {
+            const floatx4 ov = *reinterpret_cast<const floatx4*>(cv + j);
+            const u32x4 oi = *reinterpret_cast<const u32x4*>(ci + j);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r += ranks_before(ov[e], (int)oi[e], v, id) ? 1 : 0;
+        }
+        if (lane < KC) { s_v[w * KC + lane] = -INFINITY; s_i[w * KC + lane] = INT_MAX; }   // fewer than KC entries in a ragged tail
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (lane < ncand && r < KC) { s_v[w * KC + r] = v; s_i[w * KC + r] = id; }
+    } else {
+        // many equal values: per-lane sorted lists merged by KC rounds of arg-best (slow, exact)
+        float tval[KC];
+        int tidx[KC];
+#pragma unroll
+        for (int j = 0; j < KC; ++j) { tval[j] = -INFINITY; tidx[j] = INT_MAX; }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int v = c0 + ((q >> 2) * 256 + tid) * 4 + (q & 3);     // increasing in q
+            if (v < V) list_insert<KC>(x[q], v, tval, tidx);
+        }
+#pragma unroll
+        for (int r = 0; r < KC; ++r) {
+            float bv = tval[0];
+            int bi = tidx[0];
+            wave_best(bv, bi);
+            if (tidx[0] == bi && bi != INT_MAX) {      // token ids are unique: exactly one lane pops
+#pragma unroll
+                for (int q = 0; q < KC - 1; ++q) { tval[q] = tval[q + 1]; tidx[q] = tidx[q + 1]; }
+                tval[KC - 1] = -INFINITY; tidx[KC - 1] = INT_MAX;
+            }
+            if (lane == 0) { s_v[w * KC + r] = bv; s_i[w * KC + r] = bi; }
+        }
+    }
+    __syncthreads();
+    if (w == 0) {
+        // 4*KC <= 64 entries, one per lane, ranked by counting (lane id breaks ties among the padding)
+        const bool have = lane < 4 * KC;
+        const float v = have ? s_v[lane] : -INFINITY;
+        const int id = have ? s_i[lane] : INT_MAX;
+        int r = 0;
+#pragma unroll
+        for (int j = 0; j < 4 * KC; j += 4) {
+            const floatx4 ov = *reinterpret_cast<const floatx4*>(s_v + j);
+            const u32x4 oi = *reinterpret_cast<const u32x4*>(s_i + j);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int ij = (int)oi[e];
+                r += (ov[e] > v || (ov[e] == v && (ij < id || (ij == id && j + e < lane)))) ? 1 : 0;
+            }
+        }
+        const size_t pbase = (size_t)m * G + chunk;
+        if (have && r < KC) { part_val[pbase * KC + r] = v; part_idx[pbase * KC + r] = id; }
+        if (lane == 0) {
+            part_ms[pbase * 2 + 0] = bm;
+            part_ms[pbase * 2 + 1] = (s_s[0] + s_s[1]) + (s_s[2] + s_s[3]);
+        }
+    }
+}
+
 // One workgroup per (frontier row, sequence).  Each of the G partial lists is sorted, so an
 // entry can only be in the row's top k if its list's head is among the k best heads.  Heads,
 // surviving entries (<= k*KC) and new candidates (frontier) are all ranked by counting.  The workgroup that finishes last for a sequence (a counter in the workspace, zeroed
@@ -471,7 +806,7 @@ static int lm_grid(const eagle2_cfg* cfg) {
     return g < 1 ? 1 : g;
 }
 
-struct ExpandWs { size_t ms, val, idx, cnt, total; };
+struct ExpandWs { size_t ms, val, idx, cnt, logits, total; };
 static ExpandWs expand_layout(const eagle2_cfg* cfg) {
     const size_t mmax = (size_t)cfg->batch * cfg->topk;
     const size_t mblks = (mmax + 15) / 16;
@@ -480,7 +815,9 @@ static ExpandWs expand_layout(const eagle2_cfg* cfg) {
     w.val = w.ms + round_up(mblks * 16 * LM_GMAX * 2 * sizeof(float), 256);
     w.idx = w.val + round_up(mblks * 16 * LM_GMAX * EAGLE2_MAX_TOPK * sizeof(float), 256);
     w.cnt = w.idx + round_up(mblks * 16 * LM_GMAX * EAGLE2_MAX_TOPK * sizeof(int), 256);
-    w.total = w.cnt + round_up((size_t)cfg->batch * sizeof(unsigned), 256);
+    w.logits = w.cnt + round_up((size_t)cfg->batch * sizeof(unsigned), 256);
+    // dense [M, V] logits of the many-row path (used when the caller keeps no draft logits)
+    w.total = w.logits + (mmax > 16 ? round_up(mmax * (size_t)cfg->vocab * sizeof(float), 256) : 0);
     return w;
 }
 size_t expand_workspace(const eagle2_cfg* cfg) { return expand_layout(cfg).total; }
@@ -492,7 +829,6 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
     const int k = cfg->topk, F = d == 0 ? 1 : k, M = cfg->batch * F;
     const int row_bytes = cfg->hidden * elem_size(cfg);
     const int mblks = (M + 15) / 16;
-    const int G = lm_grid(cfg);
     const ExpandWs L = expand_layout(cfg);
     float* part_ms = reinterpret_cast<float*>(ws + L.ms);
     float* part_val = reinterpret_cast<float*>(ws + L.val);
@@ -500,17 +836,42 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
     unsigned* done_count = reinterpret_cast<unsigned*>(ws + L.cnt);
     const int64_t stride_el = h_seq_stride == 0 ? (int64_t)F * cfg->hidden : h_seq_stride;
 
-    const size_t smem = 4 * LM_STAGE;
-    static_assert(4 * LM_STAGE >= 2 * 16 * 16 * EAGLE2_MAX_TOPK * 4 + 16 * 16 * 2 * 4, "merge area must fit");
     const int R = n_draft_rows(cfg);
     const int row_base = d == 0 ? 0 : 1 + (d - 1) * k;
-    timing_begin(0, st);
-    hipLaunchKernelGGL((lmhead_kernel<BF16, KC>), dim3(G, mblks), dim3(LM_THREADS), smem, st,
-                       reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab,
-                       reinterpret_cast<const uint8_t*>(H), stride_el * elem_size(cfg), M, F, cfg->batch, done_count,
-                       part_ms, part_val, part_idx, draft_logits, R, row_base);
-    timing_end(0, st);
-    E2_HIP(hipGetLastError());
+    int G;
+    if (M > 16) {
+        // many rows: stream W once per 160 rows into raw logits, then per-row statistics
+        const int ntask = (cfg->vocab + LM_ROWS - 1) / LM_ROWS;
+        int gg = 2 * device_cu_count();
+        if (gg > ntask) gg = ntask;
+        const int ny = (mblks + GB_MBMAX - 1) / GB_MBMAX;
+        float* logits_ws = reinterpret_cast<float*>(ws + L.logits);
+        const int nmb_max = mblks < GB_MBMAX ? mblks : GB_MBMAX;
+        size_t gemm_smem = GB_WSTAGE + (size_t)nmb_max * 16 * GB_CHUNK;      // stage buffers, reused by the end-of-task exchange
+        if (gemm_smem < (size_t)GB_RED) gemm_smem = GB_RED;
+        timing_begin(0, st);
+        hipLaunchKernelGGL((lmhead_gemm_kernel<BF16>), dim3(gg, ny), dim3(LM_THREADS), gemm_smem, st,
+                           reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab,
+                           reinterpret_cast<const uint8_t*>(H), stride_el * elem_size(cfg), M, F, cfg->batch, done_count,
+                           logits_ws, draft_logits, R, row_base);
+        timing_end(0, st);
+        E2_HIP(hipGetLastError());
+        G = (cfg->vocab + RS_CHUNK - 1) / RS_CHUNK;
+        hipLaunchKernelGGL((row_stats_kernel<KC>), dim3(M, G), dim3(256), 0, st, cfg->vocab, F, logits_ws, draft_logits, R, row_base,
+                           part_ms, part_val, part_idx);
+        E2_HIP(hipGetLastError());
+    } else {
+        G = lm_grid(cfg);
+        const size_t smem = 4 * LM_STAGE;
+        static_assert(4 * LM_STAGE >= 2 * 16 * 16 * EAGLE2_MAX_TOPK * 4 + 16 * 16 * 2 * 4, "merge area must fit");
+        timing_begin(0, st);
+        hipLaunchKernelGGL((lmhead_kernel<BF16, KC>), dim3(G, mblks), dim3(LM_THREADS), smem, st,
+                           reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab,
+                           reinterpret_cast<const uint8_t*>(H), stride_el * elem_size(cfg), M, F, cfg->batch, done_count,
+                           part_ms, part_val, part_idx, draft_logits, R, row_base);
+        timing_end(0, st);
+        E2_HIP(hipGetLastError());
+    }
 
     hipLaunchKernelGGL((expand_merge_kernel<KC>), dim3(F, cfg->batch), dim3(MG_THREADS), 0, st,
                        d, F, k, cfg->depth, n_cand(cfg), G, (cfg->flags & EAGLE2_FLAG_RANK_BY_CONFIDENCE) ? 1 : 0, part_ms, part_val, part_idx,

@@ -70,8 +70,15 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     __shared__ __align__(16) uint8_t s_vt[DH * TA_KEYS * 2];
 
     SeqChunk sc;
-    if (!locate_chunk(blockIdx.x, B, chunk, kv_offsets, kv_len, sc)) return;
-    const int kvh = blockIdx.y / nmblk, mblk = blockIdx.y - kvh * nmblk;
+    // Workgroups start in linear order (x fastest) and are dealt round-robin to the 8 XCDs.  The
+    // linear id is re-cut as (chunk, row block, kv head) with the head fastest, so that the
+    // workgroups running at the same time read whole contiguous key rows (all heads of the same
+    // tokens) and the row blocks of one head, which re-read the same keys, start together on one
+    // XCD's L2 (when the head count is a multiple of 8).
+    const unsigned lin = blockIdx.x + gridDim.x * blockIdx.y;
+    const int flat = (int)(lin / gridDim.y), yy = (int)(lin - (unsigned)flat * gridDim.y);
+    if (!locate_chunk(flat, B, chunk, kv_offsets, kv_len, sc)) return;
+    const int mblk = yy / Hkv, kvh = yy - mblk * Hkv;
     const int grp = Hq / Hkv, rows = grp * N;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m16 = lane & 15, g4 = lane >> 4;
@@ -240,7 +247,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
         if (rho[rb] < rows) {
-            const size_t prow = ((size_t)blockIdx.x * Hkv + kvh) * rows_pad + rho[rb];
+            const size_t prow = ((size_t)flat * Hkv + kvh) * rows_pad + rho[rb];
 #pragma unroll
             for (int db = 0; db < DH / 16; ++db)
                 *reinterpret_cast<floatx4*>(part_o + prow * DH + db * 16 + g4 * 4) = acc[rb][db];

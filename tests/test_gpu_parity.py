@@ -47,6 +47,11 @@ SMALL = [
     _small("k16_n128", topk=16, depth=3, n_tree=128, vocab=2048, seed=4, accept="sample"),
     _small("no_prefix", prefix_lo=0, prefix_hi=0, seed=6),
     _small("temperature_0p7", accept="sample", temperature=0.7, seed=8),
+    # more than 16 frontier rows per pass: the logits-then-statistics path of the LM head
+    _small("batch20_rows100", batch=20, depth=3, n_tree=16, accept="mixed", prefix_lo=1, prefix_hi=90, seed=12),
+    _small("batch41_rows205_fp32", dtype="fp32", batch=41, depth=2, n_tree=12, hidden=256, vocab=4100, n_q_heads=2, n_kv_heads=2,
+           prefix_lo=0, prefix_hi=20, seed=13),
+    _small("batch5_k16_vocab2048", batch=5, topk=16, depth=2, n_tree=30, vocab=2048, seed=14, accept="sample"),
 ]
 
 
