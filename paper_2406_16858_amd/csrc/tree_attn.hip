@@ -56,14 +56,18 @@ __device__ __forceinline__ void locate_seq(int b, int chunk, const long long* kv
 template <int DH> __device__ __forceinline__ int k_swz(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
 __device__ __forceinline__ int v_swz(int row) { return (row & 15) ^ (((row >> 4) & 7) << 1); }
 
-template <int DH, int RBW>
-__global__ __launch_bounds__(TA_THREADS)
+template <int DH>
+__global__ __launch_bounds__(TA_THREADS, 2)
 void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kp, const uint16_t* __restrict__ Vp,
                            const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len,
                            const uint16_t* __restrict__ Kt,
                            const uint16_t* __restrict__ Vt, const unsigned long long* __restrict__ mask_bits,
                            int B, int N, int Hq, int Hkv, int chunk, int words, int nmblk, int rows_pad,
                            float scale_log2e, float* __restrict__ part_o, float* __restrict__ part_ml) {
+    // 16-row query blocks per wave.  Two blocks per wave (each K/V fragment feeding two MFMAs) were
+    // measured too: they need more registers than two resident waves per SIMD leave, and with the
+    // prefetch sacrificed for them they were no faster at the 640-rows-per-head shape.
+    constexpr int RBW = 1;
     constexpr int SLOTS = DH / 8;                  // 16-byte slots per K row
     constexpr int BM = 64 * RBW;                   // query rows per workgroup
     __shared__ __align__(16) uint8_t s_k[TA_KEYS * DH * 2];
@@ -122,25 +126,45 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     constexpr bool V_ALL = 16 * SLOTS >= TA_THREADS;            // every thread owns a V unit (dh 128)
     const bool v_owner = V_ALL || tid < 16 * SLOTS;
     const int v_c = tid % SLOTS, v_kg = tid / SLOTS;            // V unit: 8 dh (chunk v_c) x 4 keys (group v_kg)
-    u32x4 kr[NKP], vr[4];
-    auto fetch_tile = [&](int tile) {
+    // Two register sets, used alternately: tiles t+1 and t+2 are in flight while tile t is multiplied.
+    constexpr int DEPTH = 2;
+    u32x4 krA[NKP], vrA[4], krB[NKP], vrB[4];
+    // per-thread source pointers of the next tile to fetch, advanced by one tile per fetch (no 64-bit
+    // multiplies in the loop)
+    const uint16_t* kptr[NKP];
+    int kkey[NKP];
+#pragma unroll
+    for (int i = 0; i < NKP; ++i) {
+        const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
+        kkey[i] = key;
+        kptr[i] = kbase + (size_t)key * kv_stride + c * 8;
+    }
+    const uint16_t* vptr = vbase + (size_t)(v_kg * 4) * kv_stride + v_c * 8;
+    const size_t tile_step = (size_t)TA_KEYS * kv_stride;
+    auto fetch_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[4]) {
         const int key0 = tile * TA_KEYS;
+        if (key0 + TA_KEYS <= count) {                 // full tile (uniform): no bounds checks
 #pragma unroll
-        for (int i = 0; i < NKP; ++i) {
-            const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
-            kr[i] = key0 + key < count ? *reinterpret_cast<const u32x4*>(kbase + (size_t)(key0 + key) * kv_stride + c * 8)
-                                       : u32x4{0u, 0u, 0u, 0u};
+            for (int i = 0; i < NKP; ++i) kr[i] = *reinterpret_cast<const u32x4*>(kptr[i]);
+            if (v_owner) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) vr[i] = *reinterpret_cast<const u32x4*>(vptr + (size_t)i * kv_stride);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NKP; ++i)
+                kr[i] = key0 + kkey[i] < count ? *reinterpret_cast<const u32x4*>(kptr[i]) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                vr[i] = (v_owner && key0 + v_kg * 4 + i < count) ? *reinterpret_cast<const u32x4*>(vptr + (size_t)i * kv_stride)
+                                                                 : u32x4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int key = key0 + v_kg * 4 + i;
-            vr[i] = (v_owner && key < count) ? *reinterpret_cast<const u32x4*>(vbase + (size_t)key * kv_stride + v_c * 8)
-                                             : u32x4{0u, 0u, 0u, 0u};
-        }
+        for (int i = 0; i < NKP; ++i) kptr[i] += tile_step;
+        vptr += tile_step;
     };
     const int ntile = (count + TA_KEYS - 1) / TA_KEYS;
-    if (ntile > 0) fetch_tile(0);
-    for (int tile = 0; tile < ntile; ++tile) {
+    auto do_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[4]) {
         const int key0 = tile * TA_KEYS;
         __syncthreads();                           // previous tile fully consumed
         // K tile -> LDS, row-major, 16-byte slots swizzled by the row
@@ -164,56 +188,69 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
             }
         }
         __syncthreads();
-        if (tile + 1 < ntile) fetch_tile(tile + 1);
+        if (tile + DEPTH < ntile) fetch_tile(tile + DEPTH, kr, vr);
 
-        // S^T = K Q^T : s[rb][kb][i] = score(query row of this lane, key kb*16 + 4*g4 + i)
-        floatx4 s[RBW][4];
+        constexpr int KBH = TA_KEYS / 16, hh = 0;      // 16-key blocks of the tile
+        // S^T = K Q^T : s[rb][kq][i] = score(query row of this lane, key kb*16 + 4*g4 + i), kb = hh*KBH + kq
+        floatx4 s[RBW][KBH];
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) s[rb][kb] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int kq = 0; kq < KBH; ++kq) s[rb][kq] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
+        for (int t = 0; t < DH / 32; ++t) {            // t outside: consecutive MFMAs go to different accumulators
 #pragma unroll
-            for (int t = 0; t < DH / 32; ++t) {
-                const int row = kb * 16 + m16;
+            for (int kq = 0; kq < KBH; ++kq) {
+                const int row = (hh * KBH + kq) * 16 + m16;
                 const u32x4 kf = *reinterpret_cast<const u32x4*>(s_k + row * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>(row)) << 4));
 #pragma unroll
                 for (int rb = 0; rb < RBW; ++rb)
-                    s[rb][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8, kf), __builtin_bit_cast(bf16x8, qf[rb][t]), s[rb][kb], 0, 0, 0);
+                    s[rb][kq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, kf), __builtin_bit_cast(bf16x8, qf[rb][t]), s[rb][kq], 0, 0, 0);
             }
         }
 
-        bf16x8 pf[RBW][2];
+        bf16x8 pf[RBW][KBH / 2];
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb) {
             float mx = NEG_BIG;
+            if (!is_tree && key0 + TA_KEYS <= count) { // full prefix tile (uniform): every key is visible
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
+                for (int kq = 0; kq < KBH; ++kq) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int key = key0 + kb * 16 + g4 * 4 + i;
-                    bool vis = key < count;
-                    if (is_tree) vis = vis && (((key < 64 ? mrow[rb][0] : mrow[rb][1]) >> (key & 63)) & 1ull);
-                    const float v = vis ? s[rb][kb][i] * scale_log2e : -INFINITY;
-                    s[rb][kb][i] = v;
-                    mx = fmaxf(mx, v);
+                    for (int i = 0; i < 4; ++i) {
+                        mx = fmaxf(mx, s[rb][kq][i]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int kq = 0; kq < KBH; ++kq) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int key = key0 + (hh * KBH + kq) * 16 + g4 * 4 + i;
+                        bool vis = key < count;
+                        if (is_tree) vis = vis && (((key < 64 ? mrow[rb][0] : mrow[rb][1]) >> (key & 63)) & 1ull);
+                        const float v = vis ? s[rb][kq][i] : -INFINITY;
+                        s[rb][kq][i] = v;
+                        mx = fmaxf(mx, v);
+                    }
                 }
             }
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[rb], mx);
-            const float alpha = exp2f(m_run[rb] - m_new);
+            // scores stay raw: the (positive) scale and the running maximum go into one fma per element;
+            // the arguments of exp2 are <= 0, so the bare v_exp_f32 (tiny results flush to 0) is enough
+            const float m_new = fmaxf(m_run[rb], mx * scale_log2e);
+            const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);
             m_run[rb] = m_new;
             float psum = 0.f;
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
+            for (int kq = 0; kq < KBH; ++kq) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float p = exp2f(s[rb][kb][i] - m_new);
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rb][kq][i], scale_log2e, -m_new));
                     psum += p;
-                    pf[rb][kb >> 1][(kb & 1) * 4 + i] = (__bf16)p;
+                    pf[rb][kq >> 1][(kq & 1) * 4 + i] = (__bf16)p;
                 }
             }
             l_run[rb] = l_run[rb] * alpha + psum;
@@ -227,7 +264,8 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
 #pragma unroll
         for (int db = 0; db < DH / 16; ++db) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int uq = 0; uq < KBH / 2; ++uq) {
+                const int u = hh * (KBH / 2) + uq;
                 const int row = db * 16 + m16;
                 const u32x2 va = *reinterpret_cast<const u32x2*>(s_vt + row * (TA_KEYS * 2) + (((8 * u + g4) ^ v_swz(row)) << 3));
                 const u32x2 vb = *reinterpret_cast<const u32x2*>(s_vt + row * (TA_KEYS * 2) + (((8 * u + 4 + g4) ^ v_swz(row)) << 3));
@@ -235,9 +273,15 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
 #pragma unroll
                 for (int rb = 0; rb < RBW; ++rb)
                     acc[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8, vf), pf[rb][u], acc[rb][db], 0, 0, 0);
+                        __builtin_bit_cast(bf16x8, vf), pf[rb][uq], acc[rb][db], 0, 0, 0);
             }
         }
+    };
+    if (ntile > 0) fetch_tile(0, krA, vrA);
+    if (ntile > 1) fetch_tile(1, krB, vrB);
+    for (int tile = 0; tile < ntile; tile += 2) {
+        do_tile(tile, krA, vrA);
+        if (tile + 1 < ntile) do_tile(tile + 1, krB, vrB);
     }
 
     // partial results of this chunk: un-normalised O (lane holds dh db*16 + 4*g4 + i of its row), max, sum
@@ -382,18 +426,17 @@ void tree_attn_f32_kernel(const float* __restrict__ Q, const float* __restrict__
     }
 }
 
-struct AttnPlan { int rbw, bm, nmblk, rows_pad, chunk, max_chunks; size_t o_bytes, total; };
+struct AttnPlan { int bm, nmblk, rows_pad, chunk, max_chunks; size_t o_bytes, total; };
 static AttnPlan attn_plan(const eagle2_cfg* cfg, const eagle2_attn_cfg* a) {
     AttnPlan p;
     const int rows = a->n_q_heads / a->n_kv_heads * cfg->n_tree;
-    p.rbw = rows > 64 ? 2 : 1;
-    p.bm = 64 * p.rbw;
+    p.bm = 64;                                         // query rows per workgroup: 4 waves x 16
     p.nmblk = (rows + p.bm - 1) / p.bm;
     p.rows_pad = p.nmblk * p.bm;
-    // One resident round of workgroups: the wide variant keeps one workgroup per compute unit,
-    // the narrow one two.  Each sequence also has its tree chunk; at least two tiles per chunk.
+    // One resident round of workgroups (two per compute unit) when the prefix is short enough.
+    // Each sequence also has its tree chunk; at least two tiles per chunk.
     const long long wg_per_chunk = (long long)a->n_kv_heads * p.nmblk;
-    const long long target = (long long)device_cu_count() * (p.rbw == 2 ? 1 : 2);
+    const long long target = (long long)device_cu_count() * 2;
     long long budget = target / wg_per_chunk - cfg->batch;
     if (budget < 1) budget = 1;
     long long want = (a->total_prefix + budget - 1) / budget;
@@ -459,12 +502,11 @@ extern "C" int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* at
     const float sl2 = scale * 1.4426950408889634f;
     dim3 grid(p.max_chunks, Hkv * p.nmblk);
     timing_begin(1, st);
-#define E2_ATTN(DHV, RB)                                                                                              \
-    hipLaunchKernelGGL((tree_attn_bf16_kernel<DHV, RB>), grid, dim3(TA_THREADS), 0, st, (const uint16_t*)Q,            \
+#define E2_ATTN(DHV)                                                                                              \
+    hipLaunchKernelGGL((tree_attn_bf16_kernel<DHV>), grid, dim3(TA_THREADS), 0, st, (const uint16_t*)Q,            \
                        (const uint16_t*)K_prefix, (const uint16_t*)V_prefix, offs, kv_len, (const uint16_t*)K_tree,            \
                        (const uint16_t*)V_tree, mb, B, N, Hq, Hkv, p.chunk, words, p.nmblk, p.rows_pad, sl2, part_o, part_ml)
-    if (dh == 128) { if (p.rbw == 2) E2_ATTN(128, 2); else E2_ATTN(128, 1); }
-    else           { if (p.rbw == 2) E2_ATTN(64, 2); else E2_ATTN(64, 1); }
+    if (dh == 128) E2_ATTN(128); else E2_ATTN(64);
 #undef E2_ATTN
     timing_end(1, st);
     E2_HIP(hipGetLastError());
