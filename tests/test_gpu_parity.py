@@ -78,3 +78,11 @@ def test_cfg4_llama70b_layer_shape():
 
 def test_cfg5_batched_serving():
     run_and_check_round(wl.get_config(5), h_scale=6.0, plant=True, attn_seqs=[0, 5, 10, 15], attn_heads=[0, 13, 31])
+
+
+@pytest.mark.parametrize("idx", [6, 7])
+def test_other_published_settings(idx):
+    """Appendix A: 50 draft tokens at the 13B shape, 48 at the 70B shape."""
+    cfg = wl.get_config(idx)
+    assert cfg.n_tree == {6: 50, 7: 48}[idx] and cfg.depth == 6 and cfg.topk == 10
+    run_and_check_round(cfg, h_scale=6.0, plant=(cfg.accept == "greedy"), attn_heads=range(0, cfg.n_q_heads, 7))

@@ -1,4 +1,5 @@
-"""The five round configurations this repository is measured and checked on.
+"""The round configurations this repository is measured and checked on: the five of the
+benchmark contract plus the paper's other published settings (13B: 50 draft tokens; 70B: 48).
 
 Shapes follow the model families the paper evaluates (Section 5, "Models") and
 its hyper-parameters (Appendix A, "EAGLE-2": 60 draft tokens, depth 6, 10 nodes
@@ -63,6 +64,11 @@ CONFIGS: Tuple[RoundConfig, ...] = (
                 8192, 8192, 80, 0.02, "greedy", 1.0, _BASE_SEED + 4),
     RoundConfig("batched_serving", 5, "bf16", 16, 32000, 4096, 6, 10, 60, 32, 32, 128,
                 512, 16384, 1, 0.02, "mixed", 1.0, _BASE_SEED + 5),
+    # Appendix A: 50 draft tokens for the 13B models, 48 for the 70B models (depth 6, 10 nodes per layer)
+    RoundConfig("llama2_13b_m50", 6, "bf16", 1, 32000, 5120, 6, 10, 50, 40, 40, 128,
+                2048, 2048, 1, 0.02, "greedy", 1.0, _BASE_SEED + 6),
+    RoundConfig("llama2_70b_m48", 7, "bf16", 1, 32000, 8192, 6, 10, 48, 64, 8, 128,
+                4096, 4096, 1, 0.02, "sample", 1.0, _BASE_SEED + 7),
 )
 
 
