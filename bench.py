@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--with-draft-model", action="store_true",
+                    help="also run the draft model's decoder layer before every LM-head pass (not the headline metric)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -89,8 +91,23 @@ def main():
     root = (torch.arange(B, dtype=torch.int32) * 3 + 7).to(dev)
     plen_t = torch.tensor(plens, dtype=torch.int32, device=dev)
 
+    dm = None
+    if args.with_draft_model:
+        from paper_2406_16858_amd import DraftModel
+        dl = wl.DRAFT_LAYERS[cfg.name]
+        dcfg = wl.RoundConfig(**{**cfg.__dict__, "n_q_heads": dl.n_q_heads, "n_kv_heads": dl.n_kv_heads, "head_dim": dl.head_dim})
+        dm = DraftModel(rnd, wl.make_draft_weights(cfg, dl, dev), dl.n_q_heads, dl.n_kv_heads, dl.head_dim, dl.intermediate,
+                        dl.eps, dl.rope_theta, sum(plens))
+        _, dKp, dVp, _, _, doff = wl.make_attention_inputs(dcfg, dev, layer=97, prefix_lens=plens)
+        root_feat = H_all[:, 0, 0].contiguous()
+
     def one_round():
-        rnd.expand_all(H_all, W)
+        if dm is None:
+            rnd.expand_all(H_all, W)
+        else:
+            for d in range(D):
+                dm.forward(d, root, root_feat, plen_t, dKp, dVp, doff)
+                dm.expand(d, W)
         rnd.rerank(root, plen_t)
         for (Q, Kp, Vp, Kt, Vt, off) in layers:
             rnd.tree_attn(Q, Kp, Vp, off, Kt, Vt, O, None)
@@ -159,7 +176,10 @@ def main():
                "sample": f"one full round of sequence 0 of {cfg.name} (all {D} passes, 1 attention layer, accept), "
                          f"{c1 - c0:.1f} s of host time"}
 
-    out = {"metric": "draft_tree_rounds_per_sec_llama3_8b_shape" if cfg.index == 3 else f"draft_tree_rounds_per_sec_{cfg.name}",
+    name = "draft_tree_rounds_per_sec_llama3_8b_shape" if cfg.index == 3 else f"draft_tree_rounds_per_sec_{cfg.name}"
+    if dm is not None:
+        name += "_with_draft_model"
+    out = {"metric": name,
            "value": round(rounds_per_s, 2), "unit": "rounds/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
@@ -167,7 +187,7 @@ def main():
                                   f"Hq/Hkv={cfg.n_q_heads}/{cfg.n_kv_heads} dh={cfg.head_dim} P={cfg.prefix_lo}"
                                   f"{'' if cfg.prefix_lo == cfg.prefix_hi else '..' + str(cfg.prefix_hi)} "
                                   f"layers={cfg.n_layers} accept={cfg.accept}",
-                      "global_batch": B, "round": "6x expand + rerank + tree_attn + accept"},
+                      "global_batch": B, "round": ("6x (draft layer + expand)" if dm is not None else "6x expand") + " + rerank + tree_attn + accept"},
            "roofline": roofline, "cpu_baseline": cpu, **extra}
     print(json.dumps(out), flush=True)
 

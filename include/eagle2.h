@@ -282,6 +282,63 @@ int eagle2_commit_round(const eagle2_cfg* cfg, const int32_t* accept_len, const 
                         void* stream);
 
 /*
+ * Draft model forward between two expansion passes (Section 2.2, "Drafting Stage":
+ * autoregression at the feature level with the token sequence advanced by one
+ * step; Section 4.1: all nodes of the current layer pass through the draft model
+ * at once under tree attention).  The paper does not print the draft network: this
+ * is one LLaMA-style decoder layer -- RMSNorm, rotary grouped-query attention
+ * (half-split pairing), SwiGLU MLP, residual connections -- behind a linear fusion
+ * of [token embedding ; feature of the previous position].
+ *
+ * Pass d computes, for every sequence b and frontier slot s (F_d rows), the
+ * feature of the node in frontier[b,d,s] (d = 0: the root) from the node's token
+ * and the feature of its parent position (d = 0: root_feature, the verifying
+ * model's feature at the last committed position, e.g. eagle2_commit_round's
+ * next_hidden), attending to the sequence's draft KV prefix and to its own
+ * ancestors among the draft rows.  Draft row of (d, s): 0 for the root, else
+ * 1 + (d-1)k + s -- the row numbering of draft_logits.  The feature is written
+ * to draft_feature[b, row, :]; eagle2_expand(d) can read it in place with
+ * H = draft_feature + row_base*Hd and h_seq_stride = Rd*Hd.
+ * Rd = max(R, 2) rows per sequence; Rd <= 128.
+ *
+ *   weights      [out, in] row-major, dtype of cfg: embed [V, Hd]; fc [Hd, 2Hd];
+ *                wqkv [(Hq + 2Hkv)dh, Hd] (query rows, key rows, value rows);
+ *                wo [Hd, Hq dh]; wgu [2I, Hd] (gate rows, up rows); wdown [Hd, I];
+ *                g_attn, g_mlp [Hd] RMSNorm gains.  Every matrix row must be a
+ *                multiple of 1024 bytes.
+ *   cand_token, cand_parent, frontier   as left by the expand passes before d
+ *   root_token [B] int32, root_feature [B, Hd] dtype, prefix_len [B] int32
+ *   K_prefix, V_prefix [total_prefix, Hkv, dh] dtype, kv_offsets [B+1] int64: the
+ *                draft model's own KV cache, regions filled to prefix_len[b]
+ *   draft_feature [B, Rd, Hd] dtype in/out; K_draft, V_draft [B, Rd, Hkv, dh] dtype
+ *                in/out; draft_mask [B, Rd, ceil(Rd/64)] uint64 in/out (ancestor
+ *                bits over draft rows).  Pass 0 clears K_draft, V_draft and
+ *                draft_mask; passes must run in order on one stream.
+ *   workspace    at least eagle2_draft_workspace_bytes()
+ * Position of a row: prefix_len[b] + d.  Activations between the matrix products
+ * are rounded to dtype; the residual stream and all reductions are float32.
+ */
+typedef struct eagle2_draft_cfg {
+    int32_t n_q_heads, n_kv_heads, head_dim;   /* head_dim 64 or 128                 */
+    int32_t intermediate;                      /* I: width of the SwiGLU MLP          */
+    float   eps;                               /* RMSNorm epsilon                     */
+    float   rope_theta;                        /* rotary base                         */
+} eagle2_draft_cfg;
+
+typedef struct eagle2_draft_weights {          /* device pointers, see above          */
+    const void *embed, *fc, *g_attn, *wqkv, *wo, *g_mlp, *wgu, *wdown;
+} eagle2_draft_weights;
+
+size_t eagle2_draft_workspace_bytes(const eagle2_cfg* cfg, const eagle2_draft_cfg* draft, int64_t total_prefix);
+
+int eagle2_draft_forward(const eagle2_cfg* cfg, const eagle2_draft_cfg* draft, const eagle2_draft_weights* weights, int32_t d,
+                         const int32_t* cand_token, const int32_t* cand_parent, const int32_t* frontier,
+                         const int32_t* root_token, const void* root_feature, const int32_t* prefix_len,
+                         const void* K_prefix, const void* V_prefix, const int64_t* kv_offsets, int64_t total_prefix,
+                         void* draft_feature, void* K_draft, void* V_draft, uint64_t* draft_mask,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Kernel timing for benchmarks (not part of the method).  While enabled, every
  * eagle2_expand records a HIP event pair around its LM-head streaming kernel and
  * every eagle2_tree_attn around its split-KV kernel, on the caller's stream.

@@ -7,6 +7,11 @@ library has not been built the import of `binding` raises.
 """
 from .binding import (  # noqa: F401
     AttnCfg,
+    DraftCfg,
+    DraftWeights,
+    draft_weights,
+    eagle2_draft_forward,
+    eagle2_draft_workspace_bytes,
     Eagle2Error,
     FLAG_NO_RERANK,
     FLAG_RANK_BY_CONFIDENCE,
@@ -24,4 +29,4 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
 )
-from .round import DraftRound  # noqa: F401
+from .round import DraftModel, DraftRound  # noqa: F401

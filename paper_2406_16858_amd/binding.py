@@ -40,6 +40,17 @@ class AttnCfg(C.Structure):
                 ("scale", C.c_float), ("total_prefix", C.c_int64)]
 
 
+class DraftCfg(C.Structure):
+    """Mirror of eagle2_draft_cfg."""
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("intermediate", C.c_int32),
+                ("eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class DraftWeights(C.Structure):
+    """Mirror of eagle2_draft_weights (device pointers)."""
+    _fields_ = [(n, C.c_void_p) for n in ("embed", "fc", "g_attn", "wqkv", "wo", "g_mlp", "wgu", "wdown")]
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -70,6 +81,11 @@ def load_library():
     lib.eagle2_commit_kv.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg), i32, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
     lib.eagle2_commit_round.restype = C.c_int
     lib.eagle2_commit_round.argtypes = [C.POINTER(RoundCfg)] + [vp] * 9 + [vp]
+    lib.eagle2_draft_workspace_bytes.restype = sz
+    lib.eagle2_draft_workspace_bytes.argtypes = [C.POINTER(RoundCfg), C.POINTER(DraftCfg), i64]
+    lib.eagle2_draft_forward.restype = C.c_int
+    lib.eagle2_draft_forward.argtypes = ([C.POINTER(RoundCfg), C.POINTER(DraftCfg), C.POINTER(DraftWeights), i32] + [vp] * 9 +
+                                         [i64] + [vp] * 4 + [vp, sz, vp])
     lib.eagle2_kernel_timing_enable.restype = C.c_int
     lib.eagle2_kernel_timing_enable.argtypes = [i32]
     lib.eagle2_kernel_timing_read.restype = C.c_int
@@ -193,6 +209,31 @@ def eagle2_commit_round(cfg: RoundCfg, accept_len, accept_path, tree_token, bonu
                                    _ptr(target_hidden, el, "target_hidden"), _ptr(out_tokens, i32, "out_tokens"),
                                    _ptr(root_token, i32, "root_token"), _ptr(prefix_len, i32, "prefix_len"),
                                    _ptr(next_hidden, el, "next_hidden"), _stream(stream)))
+
+
+def eagle2_draft_workspace_bytes(cfg: RoundCfg, draft: DraftCfg, total_prefix: int) -> int:
+    return int(load_library().eagle2_draft_workspace_bytes(C.byref(cfg), C.byref(draft), total_prefix))
+
+
+def draft_weights(cfg: RoundCfg, tensors: dict) -> DraftWeights:
+    """Packs device tensors (keys as the struct's fields) into eagle2_draft_weights; the caller keeps them alive."""
+    el = _elem(cfg)
+    return DraftWeights(**{n: _ptr(tensors[n], el, n).value for n, _ in DraftWeights._fields_})
+
+
+def eagle2_draft_forward(cfg: RoundCfg, draft: DraftCfg, weights: DraftWeights, d: int, cand_token, cand_parent, frontier,
+                         root_token, root_feature, prefix_len, K_prefix, V_prefix, kv_offsets, total_prefix: int,
+                         draft_feature, K_draft, V_draft, draft_mask, workspace, stream=None):
+    lib = load_library()
+    el, i32 = _elem(cfg), torch.int32
+    wp, wb = _ws(workspace)
+    _check(lib.eagle2_draft_forward(C.byref(cfg), C.byref(draft), C.byref(weights), d, _ptr(cand_token, i32, "cand_token"),
+                                    _ptr(cand_parent, i32, "cand_parent"), _ptr(frontier, i32, "frontier"),
+                                    _ptr(root_token, i32, "root_token"), _ptr(root_feature, el, "root_feature"),
+                                    _ptr(prefix_len, i32, "prefix_len"), _ptr(K_prefix, el, "K_prefix"),
+                                    _ptr(V_prefix, el, "V_prefix"), _ptr(kv_offsets, torch.int64, "kv_offsets"), total_prefix,
+                                    _ptr(draft_feature, el, "draft_feature"), _ptr(K_draft, el, "K_draft"),
+                                    _ptr(V_draft, el, "V_draft"), _ptr(draft_mask, torch.int64, "draft_mask"), wp, wb, _stream(stream)))
 
 
 def eagle2_kernel_timing_enable(enable: bool):

@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_DIR = os.path.join(PKG_DIR, "_lib")
 LIB_PATH = os.path.join(LIB_DIR, "libeagle2_hip.so")
-SOURCES = ["api.hip", "expand.hip", "rerank.hip", "tree_attn.hip", "accept.hip", "commit.hip"]
+SOURCES = ["api.hip", "expand.hip", "rerank.hip", "tree_attn.hip", "accept.hip", "commit.hip", "draft.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -85,3 +85,41 @@ class DraftRound:
     def commit_round(self, out_tokens, root_token, prefix_len, target_hidden=None, next_hidden=None):
         _b.eagle2_commit_round(self.cfg, self.accept_len, self.accept_path, self.tree_token, self.bonus_token,
                                target_hidden, out_tokens, root_token, prefix_len, next_hidden)
+
+
+class DraftModel:
+    """Weights, draft-tree arrays and workspace of the draft model's forward (Section 2.2, drafting
+    stage) for one DraftRound.  forward(d) computes the features of pass d's rows; expand(d)
+    then reads them in place."""
+
+    def __init__(self, rnd: DraftRound, tensors: dict, n_q_heads: int, n_kv_heads: int, head_dim: int, intermediate: int,
+                 eps: float, rope_theta: float, total_prefix: int):
+        self.rnd = rnd
+        cfg = rnd.cfg
+        self.dcfg = _b.DraftCfg(n_q_heads, n_kv_heads, head_dim, intermediate, eps, rope_theta)
+        self.tensors = tensors                         # kept alive: the struct holds raw pointers
+        self.weights = _b.draft_weights(cfg, tensors)
+        self.total_prefix = total_prefix
+        B, Rd, dev = cfg.batch, max(cfg.n_draft_rows, 2), rnd.device
+        el = torch.float32 if cfg.dtype == _b.DTYPE_F32 else torch.bfloat16
+        self.rows = Rd
+        self.feature = torch.zeros((B, Rd, cfg.hidden), dtype=el, device=dev)
+        self.K = torch.zeros((B, Rd, n_kv_heads, head_dim), dtype=el, device=dev)
+        self.V = torch.zeros_like(self.K)
+        self.mask = torch.zeros((B, Rd, (Rd + 63) // 64), dtype=torch.int64, device=dev)
+        nbytes = _b.eagle2_draft_workspace_bytes(cfg, self.dcfg, total_prefix)
+        if nbytes == 0:
+            raise _b.Eagle2Error("unsupported draft shape: " + _b.load_library().eagle2_last_error().decode())
+        self.workspace = torch.empty((nbytes + 255) // 256 * 256, dtype=torch.uint8, device=dev)
+
+    def forward(self, d: int, root_token, root_feature, prefix_len, K_prefix, V_prefix, kv_offsets):
+        r = self.rnd
+        _b.eagle2_draft_forward(r.cfg, self.dcfg, self.weights, d, r.cand_token, r.cand_parent, r.frontier, root_token,
+                                root_feature, prefix_len, K_prefix, V_prefix, kv_offsets, self.total_prefix,
+                                self.feature, self.K, self.V, self.mask, self.workspace)
+
+    def expand(self, d: int, W: torch.Tensor):
+        """The LM-head pass of layer d on the features just computed (read in place)."""
+        k = self.rnd.cfg.topk
+        row_base = 0 if d == 0 else 1 + (d - 1) * k
+        self.rnd.expand(d, self.feature[:, row_base:], W, h_seq_stride=self.rows * self.rnd.cfg.hidden)

@@ -66,64 +66,72 @@ def _admissible(picked_vals: np.ndarray, all_vals: np.ndarray, picked_idx: np.nd
 FLAG_RANK_BY_CONFIDENCE, FLAG_NO_RERANK = 1, 2      # the C ABI's ablation switches (Section 5.2)
 
 
+def check_expand_pass(rnd, cfg, states, d: int, H64_d: np.ndarray, W64: np.ndarray, report: Report,
+                      check_logits: bool = True, flags: int = 0):
+    """Checks the GPU's expand pass d (already run; H64_d [B, F, Hd] are the hidden states it was
+    given, widened to float64) against the oracle, and continues the oracle states from the GPU's
+    choices."""
+    B, D, k = cfg.batch, cfg.depth, cfg.topk
+    rel_tol = REL_TOL[cfg.dtype]
+    by_value = not (flags & FLAG_RANK_BY_CONFIDENCE)
+    g_tok = rnd.cand_token.cpu().numpy()
+    g_score = rnd.cand_score.cpu().numpy()
+    g_par = rnd.cand_parent.cpu().numpy()
+    g_front = rnd.frontier.cpu().numpy()
+    F = 1 if d == 0 else k
+    base = orc.cand_base(d, k)
+    for b in range(B):
+        st = states[b]
+        ref = st.copy()
+        dl_ref = np.zeros((orc.n_draft_rows(D, k), cfg.vocab)) if (check_logits and rnd.draft_logits is not None) else None
+        logp = orc.expand(ref, d, H64_d[b, :F], W64, draft_logits=dl_ref, rank_by_value=by_value)
+        if dl_ref is not None:
+            rows = [orc.draft_row(d, s, k) for s in range(F)]
+            got = rnd.draft_logits[b, rows].cpu().numpy().astype(np.float64)
+            report.max_logit_rel = max(report.max_logit_rel, rel_err(got, dl_ref[rows]))
+        for s in range(F):
+            ids = base + s * k + np.arange(k)
+            picks = g_tok[b, ids].astype(np.int64)
+            assert picks.min() >= 0 and picks.max() < cfg.vocab, f"pass {d} row {s}: token out of range"
+            _admissible(logp[s, picks], logp[s], picks, f"seq {b} pass {d} row {s} top-k")
+            report.swaps_topk += int(np.sum(picks != ref.token[ids]))
+            par = -1 if d == 0 else int(st.frontier[d, s])
+            assert np.all(g_par[b, ids] == par), f"seq {b} pass {d} row {s}: parent ids differ"
+            par_score = 0.0 if d == 0 else float(st.score[par])
+            st.token[ids] = picks
+            st.parent[ids] = par
+            st.score[ids] = par_score + logp[s, picks]          # oracle values for the GPU's picks
+            st.own[ids] = logp[s, picks]
+            err = np.abs(g_score[b, ids] - st.score[ids])
+            report.max_score_err = max(report.max_score_err, float(err.max()))
+            assert np.all(err <= rel_tol * np.maximum(np.abs(st.score[ids]), 1.0)), \
+                f"seq {b} pass {d} row {s}: joint score error {err.max():.3e}"
+        if d + 1 < D:
+            new = base + np.arange(F * k)
+            gf = g_front[b, d + 1].astype(np.int64)
+            assert gf.min() >= base and gf.max() < base + F * k, f"seq {b} pass {d}: frontier outside the new layer"
+            key = st.score if by_value else st.own
+            _admissible(key[gf], key[new], gf - base, f"seq {b} pass {d} frontier")
+            want = new[np.lexsort((new, -key[new]))[:k]]
+            report.swaps_frontier += int(np.sum(gf != want))
+            st.frontier[d + 1] = gf
+
+
 def lockstep_expand(rnd, cfg, H_all: torch.Tensor, W: torch.Tensor, W64: np.ndarray = None,
                     report: Report = None, check_logits: bool = True, flags: int = 0):
     """Runs the D expand passes on the GPU, checking each against the oracle.
     Returns (oracle states continued from the GPU's choices, report)."""
     report = report or Report()
     B, D, k = cfg.batch, cfg.depth, cfg.topk
-    C = cfg.n_cand
     if W64 is None:
         W64 = f64(W)
     H64 = f64(H_all)
     states = [orc.DraftState(D, k) for _ in range(B)]
-    rel_tol = REL_TOL[cfg.dtype]
-    by_value = not (flags & FLAG_RANK_BY_CONFIDENCE)
     for d in range(D):
         rnd.expand(d, H_all[:, d], W, h_seq_stride=D * k * cfg.hidden)
         if H_all.is_cuda:
             torch.cuda.synchronize()
-        g_tok = rnd.cand_token.cpu().numpy()
-        g_score = rnd.cand_score.cpu().numpy()
-        g_par = rnd.cand_parent.cpu().numpy()
-        g_front = rnd.frontier.cpu().numpy()
-        F = 1 if d == 0 else k
-        base = orc.cand_base(d, k)
-        for b in range(B):
-            st = states[b]
-            ref = st.copy()
-            dl_ref = np.zeros((orc.n_draft_rows(D, k), cfg.vocab)) if (check_logits and rnd.draft_logits is not None) else None
-            logp = orc.expand(ref, d, H64[b, d, :F], W64, draft_logits=dl_ref, rank_by_value=by_value)
-            if dl_ref is not None:
-                rows = [orc.draft_row(d, s, k) for s in range(F)]
-                got = rnd.draft_logits[b, rows].cpu().numpy().astype(np.float64)
-                report.max_logit_rel = max(report.max_logit_rel, rel_err(got, dl_ref[rows]))
-            for s in range(F):
-                ids = base + s * k + np.arange(k)
-                picks = g_tok[b, ids].astype(np.int64)
-                assert picks.min() >= 0 and picks.max() < cfg.vocab, f"pass {d} row {s}: token out of range"
-                _admissible(logp[s, picks], logp[s], picks, f"seq {b} pass {d} row {s} top-k")
-                report.swaps_topk += int(np.sum(picks != ref.token[ids]))
-                par = -1 if d == 0 else int(st.frontier[d, s])
-                assert np.all(g_par[b, ids] == par), f"seq {b} pass {d} row {s}: parent ids differ"
-                par_score = 0.0 if d == 0 else float(st.score[par])
-                st.token[ids] = picks
-                st.parent[ids] = par
-                st.score[ids] = par_score + logp[s, picks]          # oracle values for the GPU's picks
-                st.own[ids] = logp[s, picks]
-                err = np.abs(g_score[b, ids] - st.score[ids])
-                report.max_score_err = max(report.max_score_err, float(err.max()))
-                assert np.all(err <= rel_tol * np.maximum(np.abs(st.score[ids]), 1.0)), \
-                    f"seq {b} pass {d} row {s}: joint score error {err.max():.3e}"
-            if d + 1 < D:
-                new = base + np.arange(F * k)
-                gf = g_front[b, d + 1].astype(np.int64)
-                assert gf.min() >= base and gf.max() < base + F * k, f"seq {b} pass {d}: frontier outside the new layer"
-                key = st.score if by_value else st.own
-                _admissible(key[gf], key[new], gf - base, f"seq {b} pass {d} frontier")
-                want = new[np.lexsort((new, -key[new]))[:k]]
-                report.swaps_frontier += int(np.sum(gf != want))
-                st.frontier[d + 1] = gf
+        check_expand_pass(rnd, cfg, states, d, H64[:, d], W64, report, check_logits, flags)
     return states, report
 
 

@@ -51,6 +51,24 @@ class RoundConfig:
         return replace(self, **kw)
 
 
+@dataclass(frozen=True)
+class DraftLayerConfig:
+    """Shape of the draft model's decoder layer (the models' own layer shape)."""
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    intermediate: int
+    eps: float = 1e-5
+    rope_theta: float = 10000.0
+
+
+# decoder-layer shapes of the model families behind the round configurations
+DRAFT_LAYERS = {
+    "llama3_8b": DraftLayerConfig(32, 8, 128, 14336, 1e-5, 500000.0),
+    "llama2_13b_m50": DraftLayerConfig(40, 40, 128, 13824, 1e-5, 10000.0),
+    "llama2_70b_m48": DraftLayerConfig(64, 8, 128, 28672, 1e-5, 10000.0),
+}
+
 _BASE_SEED = 20240616 * 10
 
 CONFIGS: Tuple[RoundConfig, ...] = (

@@ -13,7 +13,7 @@ from typing import List, Optional, Tuple
 
 import torch
 
-from .configs import RoundConfig
+from .configs import DraftLayerConfig, RoundConfig
 
 # stream ids
 _S_W, _S_H, _S_Q, _S_KP, _S_VP, _S_KT, _S_VT, _S_TL, _S_SPIKE, _S_UA, _S_UB, _S_PLEN = range(12)
@@ -112,3 +112,23 @@ def make_uniforms(cfg: RoundConfig, device="cpu") -> Tuple[torch.Tensor, torch.T
     ua = SeededStream(cfg, _S_UA, 0, device).uniform((cfg.batch, cfg.n_tree))
     ub = SeededStream(cfg, _S_UB, 0, device).uniform((cfg.batch, cfg.n_tree))
     return ua, ub
+
+
+def make_draft_weights(cfg: RoundConfig, dl: DraftLayerConfig, device="cpu") -> dict:
+    """Random weights of the draft layer, [out, in] row-major in the configuration's type:
+    N(0, 1/sqrt(fan_in)) matrices (activations keep unit scale), gains 1 + N(0, 0.1),
+    embeddings N(0, 1)."""
+    dt = _torch_dtype(cfg)
+    Hd, V = cfg.hidden, cfg.vocab
+    qd, kvd, inter = dl.n_q_heads * dl.head_dim, dl.n_kv_heads * dl.head_dim, dl.intermediate
+
+    def mat(stream, rows, cols):
+        return SeededStream(cfg, 32 + stream, 0, device).normal((rows, cols), cols ** -0.5, dt)
+
+    def gain(stream):
+        g = SeededStream(cfg, 32 + stream, 0, device).normal((Hd,), 0.1, torch.float32) + 1.0
+        return g.to(dt)
+
+    return {"embed": SeededStream(cfg, 32, 0, device).normal((V, Hd), 1.0, dt), "fc": mat(1, Hd, 2 * Hd), "g_attn": gain(2),
+            "wqkv": mat(3, qd + 2 * kvd, Hd), "wo": mat(4, Hd, qd), "g_mlp": gain(5), "wgu": mat(6, 2 * inter, Hd),
+            "wdown": mat(7, Hd, inter)}
