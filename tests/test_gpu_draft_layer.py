@@ -100,7 +100,13 @@ def _run(cfg, dl, verbose=True):
      wl.DraftLayerConfig(4, 4, 64, 768, 1e-6, 500000.0)),
     (_small("draft_bf16_dh128_k10", batch=3, vocab=4096, hidden=1024, depth=3, topk=10, n_tree=20, prefix_lo=0, prefix_hi=90, seed=53),
      wl.DraftLayerConfig(8, 8, 128, 1536, 1e-5, 10000.0)),
-], ids=["bf16_gqa_dh64", "fp32", "bf16_mha_dh128_rows30"])
+    (_small("draft_chain_k1", batch=2, vocab=2048, hidden=512, depth=6, topk=1, n_tree=7, prefix_lo=5, prefix_hi=70, seed=54),
+     wl.DraftLayerConfig(8, 2, 64, 1024, 1e-5, 10000.0)),
+    (_small("draft_depth1", batch=2, vocab=2048, hidden=512, depth=1, topk=5, n_tree=6, prefix_lo=5, prefix_hi=70, seed=55),
+     wl.DraftLayerConfig(8, 8, 64, 512, 1e-5, 10000.0)),
+    (_small("draft_k16_rows113", batch=1, vocab=2048, hidden=512, depth=8, topk=16, n_tree=64, prefix_lo=33, prefix_hi=33, seed=56),
+     wl.DraftLayerConfig(8, 4, 64, 1024, 1e-5, 10000.0)),
+], ids=["bf16_gqa_dh64", "fp32", "bf16_mha_dh128_rows30", "chain_k1", "depth1_two_row_minimum", "k16_113_draft_rows"])
 def test_draft_layer_small(cfg, dl):
     _run(cfg, dl)
 
