@@ -94,6 +94,9 @@ def main():
     dm = None
     if args.with_draft_model:
         from paper_2406_16858_amd import DraftModel
+        if cfg.name not in wl.DRAFT_LAYERS:
+            sys.exit(f"bench.py: no draft-layer shape is defined for {cfg.name}; --with-draft-model works with "
+                     f"{', '.join(wl.DRAFT_LAYERS)}")
         dl = wl.DRAFT_LAYERS[cfg.name]
         dcfg = wl.RoundConfig(**{**cfg.__dict__, "n_q_heads": dl.n_q_heads, "n_kv_heads": dl.n_kv_heads, "head_dim": dl.head_dim})
         dm = DraftModel(rnd, wl.make_draft_weights(cfg, dl, dev), dl.n_q_heads, dl.n_kv_heads, dl.head_dim, dl.intermediate,

@@ -290,8 +290,8 @@ void qkv_rope_kernel(int S, int m_pad, int d, int F, int k, int Rd, int Hq, int 
 // act = silu(gate) * up in the activation type.
 __global__ __launch_bounds__(DL_THREADS)
 void swiglu_kernel(int S, int m_pad, int inter, bool bf16, const float* __restrict__ part, void* __restrict__ act) {
-    const int m = blockIdx.y;
-    const int i = blockIdx.x * DL_THREADS + threadIdx.x;
+    const int m = blockIdx.x;
+    const int i = blockIdx.y * DL_THREADS + threadIdx.x;
     if (i >= inter) return;
     const float gt = sum_slices(part, S, m_pad, m, 2 * inter, i);
     const float up = sum_slices(part, S, m_pad, m, 2 * inter, inter + i);
@@ -302,8 +302,8 @@ void swiglu_kernel(int S, int m_pad, int inter, bool bf16, const float* __restri
 __global__ __launch_bounds__(DL_THREADS)
 void feature_out_kernel(int S, int m_pad, int d, int F, int k, int Rd, int Hd, bool bf16, const float* __restrict__ part,
                         const float* __restrict__ residual, void* __restrict__ draft_feature) {
-    const int m = blockIdx.y, b = m / F, s = m - b * F;
-    const int i = blockIdx.x * DL_THREADS + threadIdx.x;
+    const int m = blockIdx.x, b = m / F, s = m - b * F;
+    const int i = blockIdx.y * DL_THREADS + threadIdx.x;
     if (i >= Hd) return;
     const int row = draft_row_of(d, s, k);
     from_float(draft_feature, ((size_t)b * Rd + row) * Hd + i,
@@ -497,9 +497,9 @@ extern "C" int eagle2_draft_forward(const eagle2_cfg* cfg, const eagle2_draft_cf
     hipLaunchKernelGGL(sum_rmsnorm_kernel, dim3(M), dim3(RN_THREADS), 0, st, S, m_pad, Hd, dc->eps, bf, part, x0, wt->g_mlp, h1, nrm);
     // SwiGLU MLP
     E2_LIN(nrm, (int64_t)Hd * es, 1, wt->wgu, 2 * inter, Hd);
-    hipLaunchKernelGGL(swiglu_kernel, dim3((inter + DL_THREADS - 1) / DL_THREADS, M), dim3(DL_THREADS), 0, st, S, m_pad, inter, bf, part, act);
+    hipLaunchKernelGGL(swiglu_kernel, dim3(M, (inter + DL_THREADS - 1) / DL_THREADS), dim3(DL_THREADS), 0, st, S, m_pad, inter, bf, part, act);
     E2_LIN(act, (int64_t)inter * es, 1, wt->wdown, Hd, inter);
-    hipLaunchKernelGGL(feature_out_kernel, dim3((Hd + DL_THREADS - 1) / DL_THREADS, M), dim3(DL_THREADS), 0, st, S, m_pad, d, F, k, Rd,
+    hipLaunchKernelGGL(feature_out_kernel, dim3(M, (Hd + DL_THREADS - 1) / DL_THREADS), dim3(DL_THREADS), 0, st, S, m_pad, d, F, k, Rd,
                        Hd, bf, part, h1, draft_feature);
 #undef E2_LIN
     E2_HIP(hipGetLastError());
