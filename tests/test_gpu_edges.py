@@ -91,3 +91,41 @@ def test_errors_enqueue_nothing():
     assert torch.equal(before, rnd.cand_token)
     lib = b.load_library()
     assert lib.eagle2_kernel_timing_read(7, ctypes.byref(ctypes.c_double()), ctypes.byref(ctypes.c_int32())) == -1
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_partly_filled_kv_regions(dtype):
+    """prefix_len selects the filled part of each sequence's region: empty, partial, exactly full,
+    larger than the region (clamped) and negative (treated as empty) all equal the oracle on the
+    truncated prefix, and rows beyond the filled part have no influence."""
+    from oracle import eagle2_oracle as orc
+    from paper_2406_16858_amd import DraftRound
+    from tests import parity_utils as pu
+    cfg = _cfg("kv_regions", dtype=dtype, batch=5, hidden=512 if dtype == "bf16" else 256, n_tree=12, seed=77,
+               n_q_heads=4, n_kv_heads=2, head_dim=64)
+    B, N = cfg.batch, cfg.n_tree
+    region = [150, 150, 150, 150, 150]
+    plen = [0, 97, 150, 400, -3]
+    want_len = [0, 97, 150, 150, 0]
+    Q, Kp, Vp, Kt, Vt, off = wl.make_attention_inputs(cfg, "cuda", prefix_lens=region)
+    Kp[off[1] + 97: off[2]] = float("nan")             # unfilled rows of sequence 1 hold garbage
+    Vp[off[1] + 97: off[2]] = float("nan")
+    rnd = DraftRound(B, cfg.vocab, cfg.hidden, cfg.depth, cfg.topk, N, cfg.dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                     total_prefix=sum(region))
+    # a chain tree: row i sees rows 0..i
+    mask = np.tril(np.ones((N, N), dtype=bool))
+    bits = np.array([[sum(1 << j for j in range(i + 1))] for i in range(N)], dtype=np.uint64)
+    rnd.mask_bits.copy_(torch.from_numpy(np.tile(bits, (B, 1, 1)).view(np.int64)))
+    O = torch.full_like(Q, float("nan"))
+    lse = torch.full((B, N, cfg.n_q_heads), float("nan"), dtype=torch.float32, device="cuda")
+    rnd.tree_attn(Q, Kp, Vp, off, Kt, Vt, O, lse, prefix_len=torch.tensor(plen, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    assert not torch.isnan(O.float()).any()
+    offs = off.cpu().numpy()
+    for b in range(B):
+        lo = int(offs[b])
+        ref, ref_lse = orc.tree_attn(pu.f64(Q[b]), pu.f64(Kp[lo:lo + want_len[b]]), pu.f64(Vp[lo:lo + want_len[b]]),
+                                     pu.f64(Kt[b]), pu.f64(Vt[b]), mask)
+        e = pu.rel_err(pu.f64(O[b]), ref)
+        assert e <= pu.REL_TOL[dtype], f"seq {b} (prefix_len {plen[b]}): rel err {e:.2e}"
+        assert np.max(np.abs(pu.f64(lse[b]) - ref_lse)) <= pu.REL_TOL[dtype] * max(1.0, np.abs(ref_lse).max())
