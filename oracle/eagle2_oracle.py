@@ -139,7 +139,7 @@ class DraftState:
 # ----------------------------------------------------------------------------
 
 def expand(state: DraftState, d: int, H, W, draft_logits: Optional[np.ndarray] = None,
-           rank_by_value: bool = True) -> np.ndarray:
+           rank_by_value: bool = True, static_frontier: Optional[np.ndarray] = None) -> np.ndarray:
     """One expansion pass.
 
     H [F, Hd] are the hidden states of the layer-d frontier (F = 1 at d = 0, else
@@ -152,6 +152,11 @@ def expand(state: DraftState, d: int, H, W, draft_logits: Optional[np.ndarray] =
 
     rank_by_value=False is the "w/o value" ablation of Section 5.2: the next
     frontier is ranked by the nodes' own confidence instead of the path product.
+
+    static_frontier [k] (candidate ids, -1 = unused slot) is the fixed-shape tree the
+    method replaces (Section 2.2, differences between EAGLE and EAGLE-2): the nodes
+    expanded next are given by the shape instead of being selected; rows of unused
+    slots of the current frontier are skipped.
     """
     k, D = state.topk, state.depth
     Hm = np.asarray(H, dtype=np.float64)
@@ -169,6 +174,8 @@ def expand(state: DraftState, d: int, H, W, draft_logits: Optional[np.ndarray] =
             draft_logits[draft_row(d, s, k)] = x[s]
         best = np.lexsort((tok_ids, -logp[s]))[:k]           # most probable first, ties to the lower id
         par = -1 if d == 0 else int(state.frontier[d, s])
+        if d > 0 and par < 0:
+            continue                                         # unused slot of a fixed shape
         par_score = 0.0 if d == 0 else float(state.score[par])
         for r, v in enumerate(best):
             cid = base + s * k + r
@@ -177,10 +184,13 @@ def expand(state: DraftState, d: int, H, W, draft_logits: Optional[np.ndarray] =
             state.parent[cid] = par
             state.own[cid] = logp[s, v]
     if d + 1 < D:
-        new = np.arange(base, base + F * k)
-        key = state.score[new] if rank_by_value else state.own[new]
-        order = np.lexsort((new, -key))[:k]
-        state.frontier[d + 1] = new[order]
+        if static_frontier is not None:
+            state.frontier[d + 1] = np.asarray(static_frontier, dtype=np.int64)
+        else:
+            new = np.arange(base, base + F * k)
+            key = state.score[new] if rank_by_value else state.own[new]
+            order = np.lexsort((new, -key))[:k]
+            state.frontier[d + 1] = new[order]
     return logp
 
 
@@ -254,10 +264,41 @@ def flatten(state: DraftState, selected: np.ndarray, root_token: int, prefix_len
     return FlatTree(token, parent, depth, cand, prefix_len + depth, mask, bits)
 
 
+def static_shape(nodes, depth: int, topk: int):
+    """A fixed tree shape given as a list of (parent position in the list or -1, rank among the
+    parent's children), parents before children, as candidate ids: returns (ids of the nodes in
+    list order, frontier [depth, topk] with the expanded nodes of every layer in order of first
+    use, -1 padded)."""
+    ids: List[int] = []
+    node_depth: List[int] = []
+    frontier = np.full((depth, topk), -1, dtype=np.int64)
+    used = [0] * (depth + 1)
+    slot_of = {}
+    for par, rank in nodes:
+        assert 0 <= rank < topk and par < len(ids)
+        if par < 0:
+            ids.append(rank)
+            node_depth.append(1)
+            continue
+        d = node_depth[par]                                   # the parent's depth = the pass that expands it
+        assert d < depth, "a node of the deepest layer cannot have children"
+        if par not in slot_of:
+            assert used[d] < topk, "more than k expanded nodes in one layer"
+            slot_of[par] = used[d]
+            frontier[d, used[d]] = ids[par]
+            used[d] += 1
+        ids.append(cand_base(d, topk) + slot_of[par] * topk + rank)
+        node_depth.append(d + 1)
+    return np.array(ids, dtype=np.int64), frontier
+
+
 def rerank(state: DraftState, n_tree: int, root_token: int, prefix_len: int,
-           use_rerank: bool = True, rank_by_value: bool = True) -> FlatTree:
+           use_rerank: bool = True, rank_by_value: bool = True, static_sel=None) -> FlatTree:
     """Top-(n_tree - 1) of all candidates by value, flattened behind the root.
-    use_rerank=False: the expansion phase's own selection (n_tree is then D*k + 1)."""
+    use_rerank=False: the expansion phase's own selection (n_tree is then D*k + 1).
+    static_sel: the nodes of a fixed shape (Section 2.2), no selection at all."""
+    if static_sel is not None:
+        return flatten(state, np.asarray(static_sel, dtype=np.int64), root_token, prefix_len)
     sel = select_top(state, n_tree - 1) if use_rerank else select_frontiers(state, rank_by_value)
     return flatten(state, sel, root_token, prefix_len)
 

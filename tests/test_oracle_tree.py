@@ -332,3 +332,35 @@ def test_ablation_closed_forms_context_free():
         for c in range(orc.n_candidates(D, k)):
             if st.parent[c] >= 0:
                 assert abs(st.score[c] - (st.score[st.parent[c]] + st.own[c])) < 1e-12
+
+
+def test_static_shape_special_cases():
+    """Section 2.2: a fixed shape filled in by the drafting phase.  Two shapes have known answers:
+    the full k-ary tree equals the dynamic tree that keeps every candidate, and the rank-0 chain
+    equals greedy chain decoding (the k = 1 dynamic tree)."""
+    rng = np.random.default_rng(8)
+    V, Hd, D, k = 25, 6, 3, 3
+    W = rng.normal(size=(V, Hd))
+    Hs = [rng.normal(size=(1 if d == 0 else k, Hd)) * 2 for d in range(D)]
+    # full 3-ary tree of depth 2 inside a D = 2 round: every candidate is a node
+    nodes = [(-1, r) for r in range(k)] + [(p, r) for p in range(k) for r in range(k)]
+    ids, front = orc.static_shape(nodes, 2, k)
+    assert sorted(ids.tolist()) == list(range(orc.n_candidates(2, k))) and front[1].tolist() == [0, 1, 2]
+    a, b = orc.DraftState(2, k), orc.DraftState(2, k)
+    for d in range(2):
+        orc.expand(a, d, Hs[d], W, static_frontier=front[d + 1] if d + 1 < 2 else None)
+        orc.expand(b, d, Hs[d], W)
+    ta = orc.rerank(a, len(ids) + 1, 0, 0, static_sel=np.sort(ids))
+    tb = orc.rerank(b, orc.n_candidates(2, k) + 1, 0, 0)
+    assert np.array_equal(ta.token, tb.token) and np.array_equal(ta.parent, tb.parent) and np.array_equal(ta.mask, tb.mask)
+    # rank-0 chain of depth 3: slot 0 only; equals the k = 1 dynamic tree on slot 0's hidden states
+    ids, front = orc.static_shape([(-1, 0), (0, 0), (1, 0)], D, k)
+    assert ids.tolist() == [0, orc.cand_base(1, k), orc.cand_base(2, k)] and front[:, 0].tolist() == [-1, 0, orc.cand_base(1, k)]
+    c, g = orc.DraftState(D, k), orc.DraftState(D, 1)
+    for d in range(D):
+        orc.expand(c, d, Hs[d], W, static_frontier=front[d + 1] if d + 1 < D else None)
+        orc.expand(g, d, Hs[d][:1], W)
+    tc = orc.rerank(c, D + 1, 0, 0, static_sel=ids)
+    tg = orc.rerank(g, D + 1, 0, 0)
+    assert np.array_equal(tc.token, tg.token) and np.array_equal(tc.parent, tg.parent) and np.array_equal(tc.depth, tg.depth)
+    assert np.all(np.isneginf(c.score[orc.cand_base(1, k) + k: orc.cand_base(2, k)]))      # unused slots stay empty
