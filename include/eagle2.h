@@ -66,6 +66,12 @@ extern "C" {
  * re-selection; the tree then has exactly D*k + 1 rows. */
 #define EAGLE2_FLAG_RANK_BY_CONFIDENCE 1
 #define EAGLE2_FLAG_NO_RERANK          2
+/* STATIC_TREE: the fixed-shape draft tree the method replaces (Section 2.2, "Differences between
+ * EAGLE and EAGLE-2": the shape is fixed and the drafting phase fills in the positions).  The
+ * caller fixes the shape: frontier[b, d, :] holds the candidate ids expanded by pass d (unused
+ * slots -1) and is never written by eagle2_expand; eagle2_rerank takes its N-1 nodes from
+ * cfg->static_tree instead of selecting them.  Excludes the other two flags. */
+#define EAGLE2_FLAG_STATIC_TREE        4
 
 #define EAGLE2_MAX_TOPK    16
 #define EAGLE2_MAX_TREE    128
@@ -86,6 +92,9 @@ typedef struct eagle2_cfg {
     int32_t dtype;   /* EAGLE2_DTYPE_*: element type of H, W, Q, K, V and O      */
     int32_t flags;   /* 0 = the method as published; EAGLE2_FLAG_* select ablations;
                         with EAGLE2_FLAG_NO_RERANK n_tree must equal D*k + 1      */
+    const int32_t* static_tree;  /* device, [n_tree - 1] candidate ids in increasing order,
+                        closed under "parent of"; read only with
+                        EAGLE2_FLAG_STATIC_TREE (NULL otherwise)                  */
 } eagle2_cfg;
 
 /* Attention geometry.  Supported: head_dim 64 or 128; n_q_heads a multiple of

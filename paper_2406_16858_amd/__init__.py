@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     Eagle2Error,
     FLAG_NO_RERANK,
     FLAG_RANK_BY_CONFIDENCE,
+    FLAG_STATIC_TREE,
     RoundCfg,
     eagle2_accept,
     eagle2_commit_kv,

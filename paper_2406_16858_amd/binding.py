@@ -13,7 +13,7 @@ _lib = None
 
 DTYPE_F32, DTYPE_BF16 = 0, 1
 MODE_GREEDY, MODE_SAMPLE = 0, 1
-FLAG_RANK_BY_CONFIDENCE, FLAG_NO_RERANK = 1, 2
+FLAG_RANK_BY_CONFIDENCE, FLAG_NO_RERANK, FLAG_STATIC_TREE = 1, 2, 4
 
 
 class Eagle2Error(RuntimeError):
@@ -23,7 +23,8 @@ class Eagle2Error(RuntimeError):
 class RoundCfg(C.Structure):
     """Mirror of eagle2_cfg."""
     _fields_ = [("batch", C.c_int32), ("vocab", C.c_int32), ("hidden", C.c_int32), ("depth", C.c_int32),
-                ("topk", C.c_int32), ("n_tree", C.c_int32), ("dtype", C.c_int32), ("flags", C.c_int32)]
+                ("topk", C.c_int32), ("n_tree", C.c_int32), ("dtype", C.c_int32), ("flags", C.c_int32),
+                ("static_tree", C.c_void_p)]
 
     @property
     def n_cand(self) -> int:

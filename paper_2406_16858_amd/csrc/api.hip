@@ -31,8 +31,12 @@ int validate_cfg(const eagle2_cfg* c) {
     E2_REQUIRE(C <= EAGLE2_MAX_CAND, EAGLE2_ERR_SHAPE, "%lld candidates per round exceed %d", (long long)C, EAGLE2_MAX_CAND);
     E2_REQUIRE(c->n_tree >= 2 && c->n_tree <= EAGLE2_MAX_TREE && c->n_tree - 1 <= C, EAGLE2_ERR_SHAPE,
                "n_tree %d outside [2, min(%d, C+1 = %lld)]", c->n_tree, EAGLE2_MAX_TREE, (long long)C + 1);
-    E2_REQUIRE((c->flags & ~(EAGLE2_FLAG_RANK_BY_CONFIDENCE | EAGLE2_FLAG_NO_RERANK)) == 0, EAGLE2_ERR_ARG,
+    E2_REQUIRE((c->flags & ~(EAGLE2_FLAG_RANK_BY_CONFIDENCE | EAGLE2_FLAG_NO_RERANK | EAGLE2_FLAG_STATIC_TREE)) == 0, EAGLE2_ERR_ARG,
                "flags 0x%x contain unknown bits", c->flags);
+    if (c->flags & EAGLE2_FLAG_STATIC_TREE) {
+        E2_REQUIRE(c->flags == EAGLE2_FLAG_STATIC_TREE, EAGLE2_ERR_ARG, "EAGLE2_FLAG_STATIC_TREE excludes the other flags");
+        E2_REQUIRE(c->static_tree != nullptr, EAGLE2_ERR_ARG, "EAGLE2_FLAG_STATIC_TREE needs cfg->static_tree");
+    }
     if (c->flags & EAGLE2_FLAG_NO_RERANK)
         E2_REQUIRE(c->n_tree == c->depth * c->topk + 1, EAGLE2_ERR_SHAPE,
                    "without reranking the tree has depth*topk + 1 = %d rows, n_tree is %d", c->depth * c->topk + 1, c->n_tree);

@@ -379,6 +379,7 @@ static void draft_attn_cfgs(const eagle2_cfg* cfg, const eagle2_draft_cfg* dc, i
     *acfg = *cfg;
     acfg->n_tree = draft_rows(cfg);
     acfg->flags = 0;
+    acfg->static_tree = nullptr;
     ac->n_q_heads = dc->n_q_heads;
     ac->n_kv_heads = dc->n_kv_heads;
     ac->head_dim = dc->head_dim;

@@ -662,7 +662,7 @@ __device__ __forceinline__ int count_before(const T* sv, const int* si, int n, T
 
 template <int KC>
 __global__ __launch_bounds__(MG_THREADS)
-void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confidence,
+void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confidence, int static_tree,
                          const float* __restrict__ part_ms, const float* __restrict__ part_val,
                          const int* __restrict__ part_idx,
                          int* __restrict__ cand_token, double* __restrict__ cand_score,
@@ -770,7 +770,7 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
         __hip_atomic_store(cand_score + (size_t)b * C + cid, sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     }
-    if (d + 1 >= D) return;
+    if (d + 1 >= D || static_tree) return;               // a static shape fixes the frontiers beforehand
 
     // the last workgroup of this sequence picks the next frontier
     __syncthreads();
@@ -874,7 +874,8 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
     }
 
     hipLaunchKernelGGL((expand_merge_kernel<KC>), dim3(F, cfg->batch), dim3(MG_THREADS), 0, st,
-                       d, F, k, cfg->depth, n_cand(cfg), G, (cfg->flags & EAGLE2_FLAG_RANK_BY_CONFIDENCE) ? 1 : 0, part_ms, part_val, part_idx,
+                       d, F, k, cfg->depth, n_cand(cfg), G, (cfg->flags & EAGLE2_FLAG_RANK_BY_CONFIDENCE) ? 1 : 0,
+                       (cfg->flags & EAGLE2_FLAG_STATIC_TREE) ? 1 : 0, part_ms, part_val, part_idx,
                        cand_token, cand_score, cand_parent, frontier, done_count);
     E2_HIP(hipGetLastError());
     return EAGLE2_OK;

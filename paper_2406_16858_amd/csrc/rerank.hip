@@ -17,7 +17,7 @@ __global__ __launch_bounds__(RR_THREADS)
 void rerank_kernel(int C, int N, int k, int D, int words, int flags,
                    const int* __restrict__ cand_token, const double* __restrict__ cand_score,
                    const int* __restrict__ cand_parent, const int* __restrict__ frontier,
-                   const int* __restrict__ root_token,
+                   const int* __restrict__ static_tree, const int* __restrict__ root_token,
                    const int* __restrict__ prefix_len,
                    int* __restrict__ tree_token, int* __restrict__ tree_parent, int* __restrict__ tree_depth,
                    int* __restrict__ tree_cand, int* __restrict__ position_ids,
@@ -35,7 +35,16 @@ void rerank_kernel(int C, int N, int k, int D, int words, int flags,
     const int* cpar = cand_parent + (size_t)b * C;
 
     const int nsel = N - 1;
-    if (flags & EAGLE2_FLAG_NO_RERANK) {
+    if (flags & EAGLE2_FLAG_STATIC_TREE) {
+        // Section 2.2: a fixed shape whose positions the drafting phase has filled in
+        for (int i = tid; i < C; i += RR_THREADS) s_row_of[i] = -1;
+        for (int i = tid; i < nsel; i += RR_THREADS) {
+            int c = static_tree[i];
+            if (c < 0 || c >= C) c = 0;                   // a malformed shape stays in bounds
+            s_sel[i] = c;
+        }
+        __syncthreads();
+    } else if (flags & EAGLE2_FLAG_NO_RERANK) {
         // Section 5.2, "w/o reranking": the draft is what the expansion phase selected, i.e. the
         // frontiers of layers 1..D-1 and the k best nodes of layer D (nsel = D*k, checked by the host).
         const int last = k + (D - 2) * k * k;            // first id of layer D (D >= 2 here; D = 1 has no frontier rows)
@@ -171,7 +180,7 @@ extern "C" int eagle2_rerank(const eagle2_cfg* cfg,
     const int words = (cfg->n_tree + 63) / 64;
     hipLaunchKernelGGL(rerank_kernel, dim3(cfg->batch), dim3(RR_THREADS), 0, static_cast<hipStream_t>(stream),
                        C, cfg->n_tree, cfg->topk, cfg->depth, words, cfg->flags, cand_token, cand_score, cand_parent, frontier,
-                       root_token, prefix_len,
+                       cfg->static_tree, root_token, prefix_len,
                        tree_token, tree_parent, tree_depth, tree_cand, position_ids,
                        reinterpret_cast<unsigned long long*>(mask_bits));
     E2_HIP(hipGetLastError());

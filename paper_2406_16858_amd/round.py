@@ -18,10 +18,19 @@ from . import binding as _b
 class DraftRound:
     def __init__(self, batch: int, vocab: int, hidden: int, depth: int, topk: int, n_tree: int, dtype: str,
                  n_q_heads: int = 0, n_kv_heads: int = 0, head_dim: int = 0, total_prefix: int = 0,
-                 keep_draft_logits: bool = False, device="cuda", flags: int = 0):
+                 keep_draft_logits: bool = False, device="cuda", flags: int = 0,
+                 static_tree: Optional[torch.Tensor] = None):
+        """static_tree: [n_tree - 1] int32 device tensor of candidate ids (with FLAG_STATIC_TREE; the caller
+        also fills self.frontier with the candidate ids each pass expands)."""
         self.device = torch.device(device)
+        self.static_tree = static_tree                 # kept alive: the struct holds a raw pointer
+        st_ptr = None
+        if static_tree is not None:
+            if not static_tree.is_cuda or static_tree.dtype != torch.int32 or static_tree.numel() != n_tree - 1:
+                raise _b.Eagle2Error("static_tree must be an int32 device tensor of n_tree - 1 candidate ids")
+            st_ptr = static_tree.data_ptr()
         self.cfg = _b.RoundCfg(batch, vocab, hidden, depth, topk, n_tree,
-                               _b.DTYPE_F32 if dtype == "fp32" else _b.DTYPE_BF16, flags)
+                               _b.DTYPE_F32 if dtype == "fp32" else _b.DTYPE_BF16, flags, st_ptr)
         self.attn: Optional[_b.AttnCfg] = None
         if n_q_heads:
             self.attn = _b.AttnCfg(n_q_heads, n_kv_heads, head_dim, 0.0, total_prefix)

@@ -64,10 +64,11 @@ def _admissible(picked_vals: np.ndarray, all_vals: np.ndarray, picked_idx: np.nd
 
 
 FLAG_RANK_BY_CONFIDENCE, FLAG_NO_RERANK = 1, 2      # the C ABI's ablation switches (Section 5.2)
+FLAG_STATIC_TREE = 4                                # fixed-shape tree (Section 2.2)
 
 
 def check_expand_pass(rnd, cfg, states, d: int, H64_d: np.ndarray, W64: np.ndarray, report: Report,
-                      check_logits: bool = True, flags: int = 0):
+                      check_logits: bool = True, flags: int = 0, static_frontier=None):
     """Checks the GPU's expand pass d (already run; H64_d [B, F, Hd] are the hidden states it was
     given, widened to float64) against the oracle, and continues the oracle states from the GPU's
     choices."""
@@ -84,12 +85,15 @@ def check_expand_pass(rnd, cfg, states, d: int, H64_d: np.ndarray, W64: np.ndarr
         st = states[b]
         ref = st.copy()
         dl_ref = np.zeros((orc.n_draft_rows(D, k), cfg.vocab)) if (check_logits and rnd.draft_logits is not None) else None
-        logp = orc.expand(ref, d, H64_d[b, :F], W64, draft_logits=dl_ref, rank_by_value=by_value)
+        sf = None if static_frontier is None or d + 1 >= D else static_frontier[d + 1]
+        logp = orc.expand(ref, d, H64_d[b, :F], W64, draft_logits=dl_ref, rank_by_value=by_value, static_frontier=sf)
         if dl_ref is not None:
             rows = [orc.draft_row(d, s, k) for s in range(F)]
             got = rnd.draft_logits[b, rows].cpu().numpy().astype(np.float64)
             report.max_logit_rel = max(report.max_logit_rel, rel_err(got, dl_ref[rows]))
         for s in range(F):
+            if d > 0 and int(st.frontier[d, s]) < 0:
+                continue                                    # unused slot of a fixed shape: its candidates are never read
             ids = base + s * k + np.arange(k)
             picks = g_tok[b, ids].astype(np.int64)
             assert picks.min() >= 0 and picks.max() < cfg.vocab, f"pass {d} row {s}: token out of range"
@@ -106,7 +110,10 @@ def check_expand_pass(rnd, cfg, states, d: int, H64_d: np.ndarray, W64: np.ndarr
             report.max_score_err = max(report.max_score_err, float(err.max()))
             assert np.all(err <= rel_tol * np.maximum(np.abs(st.score[ids]), 1.0)), \
                 f"seq {b} pass {d} row {s}: joint score error {err.max():.3e}"
-        if d + 1 < D:
+        if d + 1 < D and static_frontier is not None:
+            assert np.array_equal(g_front[b, d + 1], static_frontier[d + 1]), f"seq {b} pass {d}: the fixed frontier was overwritten"
+            st.frontier[d + 1] = static_frontier[d + 1]
+        elif d + 1 < D:
             new = base + np.arange(F * k)
             gf = g_front[b, d + 1].astype(np.int64)
             assert gf.min() >= base and gf.max() < base + F * k, f"seq {b} pass {d}: frontier outside the new layer"
@@ -118,7 +125,7 @@ def check_expand_pass(rnd, cfg, states, d: int, H64_d: np.ndarray, W64: np.ndarr
 
 
 def lockstep_expand(rnd, cfg, H_all: torch.Tensor, W: torch.Tensor, W64: np.ndarray = None,
-                    report: Report = None, check_logits: bool = True, flags: int = 0):
+                    report: Report = None, check_logits: bool = True, flags: int = 0, static_frontier=None):
     """Runs the D expand passes on the GPU, checking each against the oracle.
     Returns (oracle states continued from the GPU's choices, report)."""
     report = report or Report()
@@ -131,11 +138,12 @@ def lockstep_expand(rnd, cfg, H_all: torch.Tensor, W: torch.Tensor, W64: np.ndar
         rnd.expand(d, H_all[:, d], W, h_seq_stride=D * k * cfg.hidden)
         if H_all.is_cuda:
             torch.cuda.synchronize()
-        check_expand_pass(rnd, cfg, states, d, H64[:, d], W64, report, check_logits, flags)
+        check_expand_pass(rnd, cfg, states, d, H64[:, d], W64, report, check_logits, flags, static_frontier)
     return states, report
 
 
-def check_rerank(rnd, cfg, states, root_token: np.ndarray, prefix_len: np.ndarray, report: Report, flags: int = 0):
+def check_rerank(rnd, cfg, states, root_token: np.ndarray, prefix_len: np.ndarray, report: Report, flags: int = 0,
+                 static_sel=None):
     """GPU rerank vs oracle: admissible selection, then bit-exact flattening of that selection."""
     B, N, k = cfg.batch, cfg.n_tree, cfg.topk
     t_tok = rnd.tree_token.cpu().numpy()
@@ -150,7 +158,10 @@ def check_rerank(rnd, cfg, states, root_token: np.ndarray, prefix_len: np.ndarra
         sel = t_cand[b, 1:].astype(np.int64)
         assert t_cand[b, 0] == -1 and sel.min() >= 0 and sel.max() < cfg.n_cand
         assert np.all(np.diff(sel) > 0), "flat order must be increasing candidate id"
-        if flags & FLAG_NO_RERANK:
+        if static_sel is not None:
+            assert np.array_equal(sel, np.sort(static_sel)), f"seq {b}: tree nodes differ from the fixed shape"
+            want = np.sort(static_sel)
+        elif flags & FLAG_NO_RERANK:
             # the expansion phase's own selection: every frontier, plus an admissible top-k of the last layer
             D = cfg.depth
             assert N == D * k + 1
@@ -249,7 +260,7 @@ def check_accept(rnd, cfg, trees, modes, target_logits, temperature, u_accept, u
 
 def run_and_check_round(cfg, device="cuda", h_scale: float = 1.0, plant: bool = False,
                         layers=(0,), attn_seqs=None, attn_heads=None, W=None, W64=None, verbose=True,
-                        round_factory=None, flags: int = 0):
+                        round_factory=None, flags: int = 0, static_nodes=None):
     """Runs one draft-plus-verify round of `cfg` on the GPU and checks every stage.
     plant=True plants the target's preferred tokens along a tree path so that sequence b
     accepts min(b mod (D+1), deepest available) tokens in greedy mode."""
@@ -268,15 +279,24 @@ def run_and_check_round(cfg, device="cuda", h_scale: float = 1.0, plant: bool = 
     H_all = wl.make_hidden_states(cfg, device, scale=h_scale)
     plens = wl.make_prefix_lengths(cfg)
     modes_l = {"greedy": [0] * B, "sample": [1] * B, "mixed": [b % 2 for b in range(B)]}[cfg.accept]
+    extra = {"flags": flags} if flags else {}
+    static_sel = static_front = None
+    if static_nodes is not None:
+        # a fixed shape (list of (parent position, rank)): the caller owns the frontiers and the node list
+        static_sel, static_front = orc.static_shape(static_nodes, D, k)
+        assert len(static_sel) == N - 1
+        extra["static_tree"] = torch.from_numpy(np.sort(static_sel).astype(np.int32)).to(device)
     rnd = round_factory(B, V, cfg.hidden, D, k, N, cfg.dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
-                     total_prefix=sum(plens), keep_draft_logits=any(modes_l), device=device, **({"flags": flags} if flags else {}))
-    states, rep = lockstep_expand(rnd, cfg, H_all, W, W64=W64, report=rep, flags=flags)
+                     total_prefix=sum(plens), keep_draft_logits=any(modes_l), device=device, **extra)
+    if static_front is not None:
+        rnd.frontier.copy_(torch.from_numpy(np.tile(static_front.astype(np.int32), (B, 1, 1))))
+    states, rep = lockstep_expand(rnd, cfg, H_all, W, W64=W64, report=rep, flags=flags, static_frontier=static_front)
 
     root = torch.arange(B, dtype=torch.int32) * 3 + 7
     plen_t = torch.tensor(plens, dtype=torch.int32)
     rnd.rerank(root.to(device), plen_t.to(device))
     sync()
-    trees = check_rerank(rnd, cfg, states, root.numpy(), plen_t.numpy(), rep, flags=flags)
+    trees = check_rerank(rnd, cfg, states, root.numpy(), plen_t.numpy(), rep, flags=flags, static_sel=static_sel)
 
     for layer in layers:
         Q, Kp, Vp, Kt, Vt, off = wl.make_attention_inputs(cfg, device, layer=layer, prefix_lens=plens)
