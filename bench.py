@@ -163,20 +163,27 @@ def main():
         Q, Kp, Vp, Kt, Vt, off = [t.float().cpu().numpy() if t.dtype != torch.int64 else t.cpu().numpy() for t in layers[0]]
         tl_h = tl[0].cpu().numpy()
         ua_h, ub_h = ua[0].cpu().numpy(), ub[0].cpu().numpy()
+        def oracle_round():
+            st = orc.DraftState(D, k)
+            dl = np.zeros((orc.n_draft_rows(D, k), V))
+            for d in range(D):
+                orc.expand(st, d, H_h[0, d, : (1 if d == 0 else k)], W_h, draft_logits=dl)
+            tree = orc.rerank(st, N, 7, plens[0])
+            orc.tree_attn(Q[0], Kp[: plens[0]], Vp[: plens[0]], Kt[0], Vt[0], tree.mask)
+            if modes_l[0] == 0:
+                orc.accept_greedy(tl_h, tree.token, tree.parent)
+            else:
+                orc.accept_sample(tl_h, dl, cfg.temperature, ua_h, ub_h, tree.token, tree.parent, tree.cand, k)
+
+        # repeat the round of sequence 0 until about 10 s of host time have passed (at most 16 rounds)
         c0 = time.perf_counter()
-        st = orc.DraftState(D, k)
-        dl = np.zeros((orc.n_draft_rows(D, k), V))
-        for d in range(D):
-            orc.expand(st, d, H_h[0, d, : (1 if d == 0 else k)], W_h, draft_logits=dl)
-        tree = orc.rerank(st, N, 7, plens[0])
-        orc.tree_attn(Q[0], Kp[: plens[0]], Vp[: plens[0]], Kt[0], Vt[0], tree.mask)
-        if modes_l[0] == 0:
-            orc.accept_greedy(tl_h, tree.token, tree.parent)
-        else:
-            orc.accept_sample(tl_h, dl, cfg.temperature, ua_h, ub_h, tree.token, tree.parent, tree.cand, k)
+        n_rounds = 0
+        while n_rounds < 16 and (n_rounds == 0 or time.perf_counter() - c0 < 10.0):
+            oracle_round()
+            n_rounds += 1
         c1 = time.perf_counter()
-        cpu = {"value": round(1.0 / (c1 - c0), 5), "unit": "rounds/s", "cores": int(cores), "kind": "oracle",
-               "sample": f"one full round of sequence 0 of {cfg.name} (all {D} passes, 1 attention layer, accept), "
+        cpu = {"value": round(n_rounds / (c1 - c0), 5), "unit": "rounds/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"{n_rounds} full rounds of sequence 0 of {cfg.name} (all {D} passes, 1 attention layer, accept), "
                          f"{c1 - c0:.1f} s of host time"}
 
     name = "draft_tree_rounds_per_sec_llama3_8b_shape" if cfg.index == 3 else f"draft_tree_rounds_per_sec_{cfg.name}"

@@ -691,7 +691,15 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     const float* pv = part_val + prow * G * KC;
     const int* pi = part_idx + prow * G * KC;
 
-    // loads first: heads of the G lists and the (max, sum-exp) pairs
+    // loads first: the parent and its score (two dependent global loads, needed only at the end),
+    // the heads of the G lists and the (max, sum-exp) pairs
+    int par = -1;
+    double ps = 0.0;
+    if (d > 0 && tid < k) {
+        par = frontier[((size_t)b * D + d) * k + slot];
+        if (par < 0 || par >= C) par = 0;               // garbage in the caller's frontier stays in bounds
+        ps = cand_score[(size_t)b * C + par];
+    }
     float my_m = -INFINITY, my_s = 0.f;
     if (tid < EAGLE2_MAX_TOPK) { s_ov[tid] = -INFINITY; s_oi[tid] = 0; }
     if (tid < G) {
@@ -758,9 +766,6 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
         for (int w = 0; w < NW; ++w) tot += s_d[w];
         const double log_sum = log(tot);
         const int cid = base + slot * k + tid;
-        int par = d == 0 ? -1 : frontier[((size_t)b * D + d) * k + slot];
-        if (d > 0 && (par < 0 || par >= C)) par = 0;       // garbage in the caller's frontier stays in bounds
-        const double ps = d == 0 ? 0.0 : cand_score[(size_t)b * C + par];
         const double sc = ps + (((double)s_ov[tid] - (double)mx) - log_sum);
         cand_token[(size_t)b * C + cid] = s_oi[tid];
         cand_parent[(size_t)b * C + cid] = par;
