@@ -33,9 +33,16 @@ static inline int elem_size(const eagle2_cfg* c) { return c->dtype == EAGLE2_DTY
 size_t expand_workspace(const eagle2_cfg* cfg);
 size_t rerank_workspace(const eagle2_cfg* cfg);
 size_t attn_workspace(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn);
+size_t attn_workspace_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int nq);   // nq query rows only
 size_t accept_workspace(const eagle2_cfg* cfg);
 
 int device_cu_count();
+
+// tree attention restricted to the query rows q0 .. q0+nq-1 (same arguments as eagle2_tree_attn otherwise)
+int tree_attn_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int q0, int nq,
+                   const void* Q, const void* K_prefix, const void* V_prefix, const int64_t* kv_offsets, const int32_t* kv_len,
+                   const void* K_tree, const void* V_tree, const uint64_t* mask_bits, void* O, float* lse,
+                   void* workspace, size_t workspace_bytes, void* stream);
 
 // ---- optional kernel timing ----------------------------------------------------
 // record_begin/end are no-ops unless timing is enabled.

@@ -310,9 +310,13 @@ void feature_out_kernel(int S, int m_pad, int d, int F, int k, int Rd, int Hd, b
                residual[(size_t)m * Hd + i] + sum_slices(part, S, m_pad, m, Hd, i), bf16);
 }
 
+struct ZeroJobs { unsigned* p[4]; size_t n4[4]; };
 __global__ __launch_bounds__(DL_THREADS)
-void zero_fill_kernel(unsigned* __restrict__ p, size_t n4) {
-    for (size_t i = (size_t)blockIdx.x * DL_THREADS + threadIdx.x; i < n4; i += (size_t)gridDim.x * DL_THREADS) p[i] = 0u;
+void zero_fill_kernel(ZeroJobs z) {                    // one launch clears all four arrays
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        for (size_t i = (size_t)blockIdx.x * DL_THREADS + threadIdx.x; i < z.n4[j]; i += (size_t)gridDim.x * DL_THREADS)
+            z.p[j][i] = 0u;
 }
 
 // ---- host side ---------------------------------------------------------------------------------
@@ -352,7 +356,9 @@ static DraftWs draft_layout(const eagle2_cfg* cfg, const eagle2_draft_cfg* dc, c
     w.q = take((size_t)cfg->batch * Rd * dc->n_q_heads * dc->head_dim * es);
     w.o = take((size_t)cfg->batch * Rd * dc->n_q_heads * dc->head_dim * es);
     w.pos = take(M * sizeof(int));
-    w.attn = take(attn_workspace(acfg, ac));
+    size_t aw = attn_workspace_rows(acfg, ac, 1);          // pass 0 has one query row, later passes k
+    const size_t aw_k = attn_workspace_rows(acfg, ac, cfg->topk < acfg->n_tree ? cfg->topk : acfg->n_tree);
+    w.attn = take(aw > aw_k ? aw : aw_k);
     w.total = o;
     return w;
 }
@@ -465,11 +471,12 @@ extern "C" int eagle2_draft_forward(const eagle2_cfg* cfg, const eagle2_draft_cf
 
     if (d == 0) {
         // rows of later passes are keys (masked) and queries (ignored) of this pass's attention: keep them finite
-        struct { void* p; size_t bytes; } z[] = {
-            {K_draft, (size_t)B * Rd * Hkv * dh * es}, {V_draft, (size_t)B * Rd * Hkv * dh * es},
-            {Q, (size_t)B * Rd * Hq * dh * es}, {draft_mask, (size_t)B * Rd * words * 8}};
-        for (auto& e : z)                                  // every size is a multiple of 4 bytes
-            hipLaunchKernelGGL(zero_fill_kernel, dim3(64), dim3(DL_THREADS), 0, st, static_cast<unsigned*>(e.p), e.bytes / 4);
+        ZeroJobs z;                                        // every size is a multiple of 4 bytes
+        z.p[0] = static_cast<unsigned*>(K_draft);  z.n4[0] = (size_t)B * Rd * Hkv * dh * es / 4;
+        z.p[1] = static_cast<unsigned*>(V_draft);  z.n4[1] = z.n4[0];
+        z.p[2] = static_cast<unsigned*>(Q);        z.n4[2] = (size_t)B * Rd * Hq * dh * es / 4;
+        z.p[3] = reinterpret_cast<unsigned*>(draft_mask);  z.n4[3] = (size_t)B * Rd * words * 2;
+        hipLaunchKernelGGL(zero_fill_kernel, dim3(64), dim3(DL_THREADS), 0, st, z);
         E2_HIP(hipGetLastError());
     }
     hipLaunchKernelGGL(draft_gather_kernel, dim3(M), dim3(DL_THREADS), 0, st, d, F, k, D, C, Hd, Rd, words, cfg->vocab, bf,
@@ -489,11 +496,12 @@ extern "C" int eagle2_draft_forward(const eagle2_cfg* cfg, const eagle2_draft_cf
     hipLaunchKernelGGL(qkv_rope_kernel, dim3(M, ((Hq + Hkv) * (dh / 2) + Hkv * dh + DL_THREADS - 1) / DL_THREADS), dim3(DL_THREADS), 0, st, S, m_pad, d, F, k, Rd, Hq, Hkv, dh,
                        log2f(dc->rope_theta), bf, part, pos, Q, K_draft, V_draft);
     E2_HIP(hipGetLastError());
-    rc = eagle2_tree_attn(&acfg, &ac, Q, K_prefix, V_prefix, kv_offsets, prefix_len, K_draft, V_draft, draft_mask, O, nullptr,
-                          ws + L.attn, L.total - L.attn, stream);
+    // only this pass's rows are queries; all draft rows are keys (later rows are zero and masked)
+    const int row_base = d == 0 ? 0 : 1 + (d - 1) * k;
+    rc = tree_attn_rows(&acfg, &ac, row_base, F, Q, K_prefix, V_prefix, kv_offsets, prefix_len, K_draft, V_draft, draft_mask, O,
+                        nullptr, ws + L.attn, L.total - L.attn, stream);
     if (rc != EAGLE2_OK) return rc;
     // output projection reads this pass's rows of O: row (b, s) at O + (b*Rd + row_base + s) * Hq*dh
-    const int row_base = d == 0 ? 0 : 1 + (d - 1) * k;
     E2_LIN(static_cast<const uint8_t*>(O) + (size_t)row_base * Hq * dh * es, (int64_t)Rd * Hq * dh * es, F, wt->wo, Hd, Hq * dh);
     hipLaunchKernelGGL(sum_rmsnorm_kernel, dim3(M), dim3(RN_THREADS), 0, st, S, m_pad, Hd, dc->eps, bf, part, x0, wt->g_mlp, h1, nrm);
     // SwiGLU MLP

@@ -62,7 +62,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
                            const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len,
                            const uint16_t* __restrict__ Kt,
                            const uint16_t* __restrict__ Vt, const unsigned long long* __restrict__ mask_bits,
-                           int B, int N, int Hq, int Hkv, int chunk, int words, int nmblk, int rows_pad,
+                           int B, int N, int q0, int nq, int Hq, int Hkv, int chunk, int words, int nmblk, int rows_pad,
                            float scale_log2e, float* __restrict__ part_o, float* __restrict__ part_ml) {
     // 16-row query blocks per wave.  Two blocks per wave (each K/V fragment feeding two MFMAs) were
     // measured too: they need more registers than two resident waves per SIMD leave, and with the
@@ -83,7 +83,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     const int flat = (int)(lin / gridDim.y), yy = (int)(lin - (unsigned)flat * gridDim.y);
     if (!locate_chunk(flat, B, chunk, kv_offsets, kv_len, sc)) return;
     const int mblk = yy / Hkv, kvh = yy - mblk * Hkv;
-    const int grp = Hq / Hkv, rows = grp * N;
+    const int grp = Hq / Hkv, rows = grp * nq;      // query rows: tree rows q0 .. q0+nq-1 of every head in the group
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m16 = lane & 15, g4 = lane >> 4;
     const bool is_tree = sc.c == sc.nc - 1;
@@ -102,7 +102,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     for (int rb = 0; rb < RBW; ++rb) {
         rho[rb] = mblk * BM + (w * RBW + rb) * 16 + m16;
         const bool ok = rho[rb] < rows;
-        const int n = ok ? rho[rb] / grp : 0, j = ok ? rho[rb] - n * grp : 0;
+        const int nr = ok ? rho[rb] / grp : 0, j = ok ? rho[rb] - nr * grp : 0, n = q0 + nr;
         const uint16_t* qrow = Q + (((size_t)sc.b * N + n) * Hq + kvh * grp + j) * DH;
 #pragma unroll
         for (int t = 0; t < DH / 32; ++t)
@@ -305,13 +305,13 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
 // partial outputs, whose loads are independent and issued four chunks at a time.
 template <int DH>
 __global__ __launch_bounds__(256)
-void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len, int N, int Hq, int Hkv, int chunk, int rows_pad,
+void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len, int N, int q0, int nq, int Hq, int Hkv, int chunk, int rows_pad,
                               const float* __restrict__ part_o, const float* __restrict__ part_ml,
                               uint16_t* __restrict__ O, float* __restrict__ lse) {
-    const int bn = blockIdx.x, b = bn / N, n = bn - b * N;
+    const int b = blockIdx.x / nq, nr = blockIdx.x - b * nq, n = q0 + nr, bn = b * N + n;
     const int h = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (h >= Hq) return;
-    const int grp = Hq / Hkv, kvh = h / grp, rho = n * grp + (h - kvh * grp);
+    const int grp = Hq / Hkv, kvh = h / grp, rho = nr * grp + (h - kvh * grp);
     int first, nc;
     locate_seq(b, chunk, kv_offsets, kv_len, first, nc);
     const size_t cstride = (size_t)Hkv * rows_pad;               // rows between consecutive chunks
@@ -368,9 +368,9 @@ void tree_attn_f32_kernel(const float* __restrict__ Q, const float* __restrict__
                           const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len,
                           const float* __restrict__ Kt,
                           const float* __restrict__ Vt, const unsigned long long* __restrict__ mask_bits,
-                          int N, int Hq, int Hkv, int words, float scale, float* __restrict__ O, float* __restrict__ lse) {
+                          int N, int q0, int nq, int Hq, int Hkv, int words, float scale, float* __restrict__ O, float* __restrict__ lse) {
     constexpr int E = DH / 64;
-    const int h = blockIdx.x % Hq, bn = blockIdx.x / Hq, b = bn / N;
+    const int h = blockIdx.x % Hq, bq = blockIdx.x / Hq, b = bq / nq, bn = b * N + q0 + (bq - b * nq);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int kvh = h / (Hq / Hkv);
     const long long off = kv_offsets[b];
@@ -427,9 +427,9 @@ void tree_attn_f32_kernel(const float* __restrict__ Q, const float* __restrict__
 }
 
 struct AttnPlan { int bm, nmblk, rows_pad, chunk, max_chunks; size_t o_bytes, total; };
-static AttnPlan attn_plan(const eagle2_cfg* cfg, const eagle2_attn_cfg* a) {
+static AttnPlan attn_plan(const eagle2_cfg* cfg, const eagle2_attn_cfg* a, int nq) {
     AttnPlan p;
-    const int rows = a->n_q_heads / a->n_kv_heads * cfg->n_tree;
+    const int rows = a->n_q_heads / a->n_kv_heads * nq;   // nq: tree rows that act as queries
     p.bm = 64;                                         // query rows per workgroup: 4 waves x 16
     p.nmblk = (rows + p.bm - 1) / p.bm;
     p.rows_pad = p.nmblk * p.bm;
@@ -449,8 +449,78 @@ static AttnPlan attn_plan(const eagle2_cfg* cfg, const eagle2_attn_cfg* a) {
     p.total = p.o_bytes + round_up((size_t)p.max_chunks * a->n_kv_heads * p.rows_pad * 2 * sizeof(float), 256);
     return p;
 }
+size_t attn_workspace_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int nq) {
+    return cfg->dtype == EAGLE2_DTYPE_BF16 ? attn_plan(cfg, attn, nq).total : 0;
+}
 size_t attn_workspace(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn) {
-    return cfg->dtype == EAGLE2_DTYPE_BF16 ? attn_plan(cfg, attn).total : 0;
+    return cfg->dtype == EAGLE2_DTYPE_BF16 ? attn_plan(cfg, attn, cfg->n_tree).total : 0;   // a window of rows needs no more
+}
+
+// Attention of the tree rows q0 .. q0+nq-1 (queries) over the prefix and all N tree keys under the
+// mask; the public entry point asks for every row, the draft model's forward for the rows of one pass.
+int tree_attn_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int q0, int nq,
+                   const void* Q, const void* K_prefix, const void* V_prefix,
+                   const int64_t* kv_offsets, const int32_t* kv_len,
+                   const void* K_tree, const void* V_tree,
+                   const uint64_t* mask_bits, void* O, float* lse,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = validate_cfg(cfg);
+    if (rc != EAGLE2_OK) return rc;
+    rc = validate_attn(cfg, attn);
+    if (rc != EAGLE2_OK) return rc;
+    E2_REQUIRE(Q && kv_offsets && K_tree && V_tree && mask_bits && O, EAGLE2_ERR_ARG, "eagle2_tree_attn: null pointer argument");
+    E2_REQUIRE(attn->total_prefix == 0 || (K_prefix && V_prefix), EAGLE2_ERR_ARG, "eagle2_tree_attn: null KV prefix");
+    E2_REQUIRE(aligned16(Q) && aligned16(K_prefix) && aligned16(V_prefix) && aligned16(K_tree) && aligned16(V_tree) && aligned16(O),
+               EAGLE2_ERR_ARG, "eagle2_tree_attn: tensors must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int B = cfg->batch, N = cfg->n_tree, Hq = attn->n_q_heads, Hkv = attn->n_kv_heads, dh = attn->head_dim;
+    E2_REQUIRE(q0 >= 0 && nq >= 1 && q0 + nq <= N, EAGLE2_ERR_ARG, "tree attention: query rows %d..%d outside the tree", q0, q0 + nq - 1);
+    const float scale = attn->scale > 0.f ? attn->scale : 1.0f / sqrtf((float)dh);
+    const int words = (N + 63) / 64;
+    const long long* offs = reinterpret_cast<const long long*>(kv_offsets);
+    const unsigned long long* mb = reinterpret_cast<const unsigned long long*>(mask_bits);
+
+    if (cfg->dtype == EAGLE2_DTYPE_F32) {
+        dim3 grid((unsigned)((size_t)B * nq * Hq));
+        timing_begin(1, st);
+        if (dh == 128)
+            hipLaunchKernelGGL((tree_attn_f32_kernel<128>), grid, dim3(256), 0, st, (const float*)Q, (const float*)K_prefix,
+                               (const float*)V_prefix, offs, kv_len, (const float*)K_tree, (const float*)V_tree, mb, N, q0, nq, Hq, Hkv, words,
+                               scale, (float*)O, lse);
+        else
+            hipLaunchKernelGGL((tree_attn_f32_kernel<64>), grid, dim3(256), 0, st, (const float*)Q, (const float*)K_prefix,
+                               (const float*)V_prefix, offs, kv_len, (const float*)K_tree, (const float*)V_tree, mb, N, q0, nq, Hq, Hkv, words,
+                               scale, (float*)O, lse);
+        timing_end(1, st);
+        E2_HIP(hipGetLastError());
+        return EAGLE2_OK;
+    }
+
+    const AttnPlan p = attn_plan(cfg, attn, nq);
+    E2_REQUIRE(workspace && workspace_bytes >= p.total, EAGLE2_ERR_WORKSPACE,
+               "eagle2_tree_attn: workspace of %zu bytes, need %zu", workspace_bytes, p.total);
+    float* part_o = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace));
+    float* part_ml = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + p.o_bytes);
+    const float sl2 = scale * 1.4426950408889634f;
+    dim3 grid(p.max_chunks, Hkv * p.nmblk);
+    timing_begin(1, st);
+#define E2_ATTN(DHV)                                                                                              \
+    hipLaunchKernelGGL((tree_attn_bf16_kernel<DHV>), grid, dim3(TA_THREADS), 0, st, (const uint16_t*)Q,            \
+                       (const uint16_t*)K_prefix, (const uint16_t*)V_prefix, offs, kv_len, (const uint16_t*)K_tree,            \
+                       (const uint16_t*)V_tree, mb, B, N, q0, nq, Hq, Hkv, p.chunk, words, p.nmblk, p.rows_pad, sl2, part_o, part_ml)
+    if (dh == 128) E2_ATTN(128); else E2_ATTN(64);
+#undef E2_ATTN
+    timing_end(1, st);
+    E2_HIP(hipGetLastError());
+    dim3 cgrid(B * nq, (Hq + 3) / 4);
+    if (dh == 128)
+        hipLaunchKernelGGL((tree_attn_combine_kernel<128>), cgrid, dim3(256), 0, st, offs, kv_len, N, q0, nq, Hq, Hkv, p.chunk, p.rows_pad,
+                           part_o, part_ml, (uint16_t*)O, lse);
+    else
+        hipLaunchKernelGGL((tree_attn_combine_kernel<64>), cgrid, dim3(256), 0, st, offs, kv_len, N, q0, nq, Hq, Hkv, p.chunk, p.rows_pad,
+                           part_o, part_ml, (uint16_t*)O, lse);
+    E2_HIP(hipGetLastError());
+    return EAGLE2_OK;
 }
 
 }  // namespace eagle2
@@ -463,60 +533,7 @@ extern "C" int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* at
                                 const void* K_tree, const void* V_tree,
                                 const uint64_t* mask_bits, void* O, float* lse,
                                 void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = validate_cfg(cfg);
-    if (rc != EAGLE2_OK) return rc;
-    rc = validate_attn(cfg, attn);
-    if (rc != EAGLE2_OK) return rc;
-    E2_REQUIRE(Q && kv_offsets && K_tree && V_tree && mask_bits && O, EAGLE2_ERR_ARG, "eagle2_tree_attn: null pointer argument");
-    E2_REQUIRE(attn->total_prefix == 0 || (K_prefix && V_prefix), EAGLE2_ERR_ARG, "eagle2_tree_attn: null KV prefix");
-    E2_REQUIRE(aligned16(Q) && aligned16(K_prefix) && aligned16(V_prefix) && aligned16(K_tree) && aligned16(V_tree) && aligned16(O),
-               EAGLE2_ERR_ARG, "eagle2_tree_attn: tensors must be 16-byte aligned");
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int B = cfg->batch, N = cfg->n_tree, Hq = attn->n_q_heads, Hkv = attn->n_kv_heads, dh = attn->head_dim;
-    const float scale = attn->scale > 0.f ? attn->scale : 1.0f / sqrtf((float)dh);
-    const int words = (N + 63) / 64;
-    const long long* offs = reinterpret_cast<const long long*>(kv_offsets);
-    const unsigned long long* mb = reinterpret_cast<const unsigned long long*>(mask_bits);
-
-    if (cfg->dtype == EAGLE2_DTYPE_F32) {
-        dim3 grid((unsigned)((size_t)B * N * Hq));
-        timing_begin(1, st);
-        if (dh == 128)
-            hipLaunchKernelGGL((tree_attn_f32_kernel<128>), grid, dim3(256), 0, st, (const float*)Q, (const float*)K_prefix,
-                               (const float*)V_prefix, offs, kv_len, (const float*)K_tree, (const float*)V_tree, mb, N, Hq, Hkv, words,
-                               scale, (float*)O, lse);
-        else
-            hipLaunchKernelGGL((tree_attn_f32_kernel<64>), grid, dim3(256), 0, st, (const float*)Q, (const float*)K_prefix,
-                               (const float*)V_prefix, offs, kv_len, (const float*)K_tree, (const float*)V_tree, mb, N, Hq, Hkv, words,
-                               scale, (float*)O, lse);
-        timing_end(1, st);
-        E2_HIP(hipGetLastError());
-        return EAGLE2_OK;
-    }
-
-    const AttnPlan p = attn_plan(cfg, attn);
-    E2_REQUIRE(workspace && workspace_bytes >= p.total, EAGLE2_ERR_WORKSPACE,
-               "eagle2_tree_attn: workspace of %zu bytes, need %zu", workspace_bytes, p.total);
-    float* part_o = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace));
-    float* part_ml = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + p.o_bytes);
-    const float sl2 = scale * 1.4426950408889634f;
-    dim3 grid(p.max_chunks, Hkv * p.nmblk);
-    timing_begin(1, st);
-#define E2_ATTN(DHV)                                                                                              \
-    hipLaunchKernelGGL((tree_attn_bf16_kernel<DHV>), grid, dim3(TA_THREADS), 0, st, (const uint16_t*)Q,            \
-                       (const uint16_t*)K_prefix, (const uint16_t*)V_prefix, offs, kv_len, (const uint16_t*)K_tree,            \
-                       (const uint16_t*)V_tree, mb, B, N, Hq, Hkv, p.chunk, words, p.nmblk, p.rows_pad, sl2, part_o, part_ml)
-    if (dh == 128) E2_ATTN(128); else E2_ATTN(64);
-#undef E2_ATTN
-    timing_end(1, st);
-    E2_HIP(hipGetLastError());
-    dim3 cgrid(B * N, (Hq + 3) / 4);
-    if (dh == 128)
-        hipLaunchKernelGGL((tree_attn_combine_kernel<128>), cgrid, dim3(256), 0, st, offs, kv_len, N, Hq, Hkv, p.chunk, p.rows_pad,
-                           part_o, part_ml, (uint16_t*)O, lse);
-    else
-        hipLaunchKernelGGL((tree_attn_combine_kernel<64>), cgrid, dim3(256), 0, st, offs, kv_len, N, Hq, Hkv, p.chunk, p.rows_pad,
-                           part_o, part_ml, (uint16_t*)O, lse);
-    E2_HIP(hipGetLastError());
-    return EAGLE2_OK;
+    E2_REQUIRE(cfg != nullptr, EAGLE2_ERR_ARG, "cfg is null");
+    return tree_attn_rows(cfg, attn, 0, cfg->n_tree, Q, K_prefix, V_prefix, kv_offsets, kv_len, K_tree, V_tree, mask_bits, O, lse,
+                          workspace, workspace_bytes, stream);
 }
