@@ -2,10 +2,11 @@
 the shape is fixed and the drafting phase fills in its positions).  The shape is the caller's: the
 expansion passes leave the frontiers alone and the flattening takes the shape's nodes as they are;
 attention and acceptance then run on that tree as on any other."""
+import dataclasses
+
 import numpy as np
 import pytest
 
-import workloads as wl
 from tests.parity_utils import FLAG_STATIC_TREE, run_and_check_round
 from tests.test_gpu_parity import _small
 
@@ -25,11 +26,13 @@ CHAIN = [(-1, 0), (0, 0), (1, 0), (2, 0)]
                                   _small("static_fp32", dtype="fp32", hidden=256, vocab=777, n_q_heads=4, n_kv_heads=4, seed=62)],
                          ids=["bf16_batch3_mixed", "fp32"])
 def test_static_tree(base, nodes, name):
-    import dataclasses
     cfg = dataclasses.replace(base, n_tree=len(nodes) + 1)
     rep, trees, _ = run_and_check_round(cfg, h_scale=6.0, plant=(cfg.accept == "greedy"), flags=FLAG_STATIC_TREE, static_nodes=nodes)
-    for t in trees:
-        assert t.token.shape[0] == len(nodes) + 1
+    depth = []
+    for par, _ in nodes:
+        depth.append(1 if par < 0 else depth[par] + 1)
+    for t in trees:                                         # the tree has exactly the shape's nodes per depth
+        assert np.bincount(t.depth).tolist() == [1] + np.bincount(depth)[1:].tolist()
     assert rep.swaps_frontier == 0 and rep.swaps_rerank == 0
 
 
