@@ -56,7 +56,7 @@ __device__ __forceinline__ void locate_seq(int b, int chunk, const long long* kv
 template <int DH> __device__ __forceinline__ int k_swz(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
 __device__ __forceinline__ int v_swz(int row) { return (row & 15) ^ (((row >> 4) & 7) << 1); }
 
-template <int DH>
+template <int DH, int RBW>
 __global__ __launch_bounds__(TA_THREADS, 2)
 void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kp, const uint16_t* __restrict__ Vp,
                            const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len,
@@ -67,11 +67,12 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     // 16-row query blocks per wave.  Two blocks per wave (each K/V fragment feeding two MFMAs) were
     // measured too: they need more registers than two resident waves per SIMD leave, and with the
     // prefetch sacrificed for them they were no faster at the 640-rows-per-head shape.
-    constexpr int RBW = 1;
     constexpr int SLOTS = DH / 8;                  // 16-byte slots per K row
     constexpr int BM = 64 * RBW;                   // query rows per workgroup
     __shared__ __align__(16) uint8_t s_k[TA_KEYS * DH * 2];
     __shared__ __align__(16) uint8_t s_vt[DH * TA_KEYS * 2];
+    // wide variant: the query fragments live in LDS (row-major, slots swizzled like K) instead of registers
+    __shared__ __align__(16) uint8_t s_q[RBW == 2 ? BM * DH * 2 : 16];
 
     SeqChunk sc;
     // Workgroups start in linear order (x fastest) and are dealt round-robin to the 8 XCDs.  The
@@ -96,7 +97,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
 
     // query fragments: lane (m16, g4) holds, for its row, dh elements 32t + 8*g4 .. +7
     u32x4 qf[RBW][DH / 32];
-    unsigned long long mrow[RBW][2];
+    const unsigned long long* mptr[RBW];          // the row's ancestor bits (tree chunk only; read per tile, not held)
     int rho[RBW];
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
@@ -107,8 +108,12 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
 #pragma unroll
         for (int t = 0; t < DH / 32; ++t)
             qf[rb][t] = ok ? *reinterpret_cast<const u32x4*>(qrow + t * 32 + g4 * 8) : u32x4{0u, 0u, 0u, 0u};
-        mrow[rb][0] = (ok && is_tree) ? mask_bits[((size_t)sc.b * N + n) * words] : 0ull;
-        mrow[rb][1] = (ok && is_tree && words > 1) ? mask_bits[((size_t)sc.b * N + n) * words + 1] : 0ull;
+        mptr[rb] = ok ? mask_bits + ((size_t)sc.b * N + n) * words : nullptr;
+        if constexpr (RBW == 2) {                      // park the fragments in LDS; the same lane reads them back
+#pragma unroll
+            for (int t = 0; t < DH / 32; ++t)
+                *reinterpret_cast<u32x4*>(s_q + ((w * RBW + rb) * 16 + m16) * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>((w * RBW + rb) * 16 + m16)) << 4)) = qf[rb][t];
+        }
     }
 
     floatx4 acc[RBW][DH / 16];
@@ -127,16 +132,14 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     const bool v_owner = V_ALL || tid < 16 * SLOTS;
     const int v_c = tid % SLOTS, v_kg = tid / SLOTS;            // V unit: 8 dh (chunk v_c) x 4 keys (group v_kg)
     // Two register sets, used alternately: tiles t+1 and t+2 are in flight while tile t is multiplied.
-    constexpr int DEPTH = 2;
+    constexpr int DEPTH = RBW == 1 ? 2 : 1;            // the wide variant has registers for one set only
     u32x4 krA[NKP], vrA[4], krB[NKP], vrB[4];
     // per-thread source pointers of the next tile to fetch, advanced by one tile per fetch (no 64-bit
     // multiplies in the loop)
     const uint16_t* kptr[NKP];
-    int kkey[NKP];
 #pragma unroll
     for (int i = 0; i < NKP; ++i) {
         const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
-        kkey[i] = key;
         kptr[i] = kbase + (size_t)key * kv_stride + c * 8;
     }
     const uint16_t* vptr = vbase + (size_t)(v_kg * 4) * kv_stride + v_c * 8;
@@ -153,7 +156,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
         } else {
 #pragma unroll
             for (int i = 0; i < NKP; ++i)
-                kr[i] = key0 + kkey[i] < count ? *reinterpret_cast<const u32x4*>(kptr[i]) : u32x4{0u, 0u, 0u, 0u};
+                kr[i] = key0 + (tid + i * TA_THREADS) / SLOTS < count ? *reinterpret_cast<const u32x4*>(kptr[i]) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 vr[i] = (v_owner && key0 + v_kg * 4 + i < count) ? *reinterpret_cast<const u32x4*>(vptr + (size_t)i * kv_stride)
@@ -199,6 +202,14 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
             for (int kq = 0; kq < KBH; ++kq) s[rb][kq] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int t = 0; t < DH / 32; ++t) {            // t outside: consecutive MFMAs go to different accumulators
+            u32x4 qv[RBW];
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) {
+                if constexpr (RBW == 2)
+                    qv[rb] = *reinterpret_cast<const u32x4*>(s_q + ((w * RBW + rb) * 16 + m16) * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>((w * RBW + rb) * 16 + m16)) << 4));
+                else
+                    qv[rb] = qf[rb][t];
+            }
 #pragma unroll
             for (int kq = 0; kq < KBH; ++kq) {
                 const int row = (hh * KBH + kq) * 16 + m16;
@@ -206,7 +217,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
 #pragma unroll
                 for (int rb = 0; rb < RBW; ++rb)
                     s[rb][kq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8, kf), __builtin_bit_cast(bf16x8, qf[rb][t]), s[rb][kq], 0, 0, 0);
+                        __builtin_bit_cast(bf16x8, kf), __builtin_bit_cast(bf16x8, qv[rb]), s[rb][kq], 0, 0, 0);
             }
         }
 
@@ -223,13 +234,15 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
                     }
                 }
             } else {
+                // a 64-key tile lies inside one 64-bit word of the row's mask
+                const unsigned long long mword = (is_tree && mptr[rb] != nullptr && (key0 >> 6) < words) ? mptr[rb][key0 >> 6] : 0ull;
 #pragma unroll
                 for (int kq = 0; kq < KBH; ++kq) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int key = key0 + (hh * KBH + kq) * 16 + g4 * 4 + i;
                         bool vis = key < count;
-                        if (is_tree) vis = vis && (((key < 64 ? mrow[rb][0] : mrow[rb][1]) >> (key & 63)) & 1ull);
+                        if (is_tree) vis = vis && ((mword >> (key & 63)) & 1ull);
                         const float v = vis ? s[rb][kq][i] : -INFINITY;
                         s[rb][kq][i] = v;
                         mx = fmaxf(mx, v);
@@ -278,10 +291,14 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
         }
     };
     if (ntile > 0) fetch_tile(0, krA, vrA);
-    if (ntile > 1) fetch_tile(1, krB, vrB);
-    for (int tile = 0; tile < ntile; tile += 2) {
-        do_tile(tile, krA, vrA);
-        if (tile + 1 < ntile) do_tile(tile + 1, krB, vrB);
+    if constexpr (DEPTH == 2) {
+        if (ntile > 1) fetch_tile(1, krB, vrB);
+        for (int tile = 0; tile < ntile; tile += 2) {
+            do_tile(tile, krA, vrA);
+            if (tile + 1 < ntile) do_tile(tile + 1, krB, vrB);
+        }
+    } else {
+        for (int tile = 0; tile < ntile; ++tile) do_tile(tile, krA, vrA);
     }
 
     // partial results of this chunk: un-normalised O (lane holds dh db*16 + 4*g4 + i of its row), max, sum
@@ -426,11 +443,12 @@ void tree_attn_f32_kernel(const float* __restrict__ Q, const float* __restrict__
     }
 }
 
-struct AttnPlan { int bm, nmblk, rows_pad, chunk, max_chunks; size_t o_bytes, total; };
+struct AttnPlan { int rbw, bm, nmblk, rows_pad, chunk, max_chunks; size_t o_bytes, total; };
 static AttnPlan attn_plan(const eagle2_cfg* cfg, const eagle2_attn_cfg* a, int nq) {
     AttnPlan p;
     const int rows = a->n_q_heads / a->n_kv_heads * nq;   // nq: tree rows that act as queries
-    p.bm = 64;                                         // query rows per workgroup: 4 waves x 16
+    p.rbw = rows > 256 ? 2 : 1;                        // 16-row blocks per wave: two pay only when the kernel is compute-bound
+    p.bm = 64 * p.rbw;                                 // query rows per workgroup
     p.nmblk = (rows + p.bm - 1) / p.bm;
     p.rows_pad = p.nmblk * p.bm;
     // One resident round of workgroups (two per compute unit) when the prefix is short enough.
@@ -504,11 +522,12 @@ int tree_attn_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int q0, i
     const float sl2 = scale * 1.4426950408889634f;
     dim3 grid(p.max_chunks, Hkv * p.nmblk);
     timing_begin(1, st);
-#define E2_ATTN(DHV)                                                                                              \
-    hipLaunchKernelGGL((tree_attn_bf16_kernel<DHV>), grid, dim3(TA_THREADS), 0, st, (const uint16_t*)Q,            \
+#define E2_ATTN(DHV, RB)                                                                                              \
+    hipLaunchKernelGGL((tree_attn_bf16_kernel<DHV, RB>), grid, dim3(TA_THREADS), 0, st, (const uint16_t*)Q,            \
                        (const uint16_t*)K_prefix, (const uint16_t*)V_prefix, offs, kv_len, (const uint16_t*)K_tree,            \
                        (const uint16_t*)V_tree, mb, B, N, q0, nq, Hq, Hkv, p.chunk, words, p.nmblk, p.rows_pad, sl2, part_o, part_ml)
-    if (dh == 128) E2_ATTN(128); else E2_ATTN(64);
+    if (dh == 128) { if (p.rbw == 2) E2_ATTN(128, 2); else E2_ATTN(128, 1); }
+    else           { if (p.rbw == 2) E2_ATTN(64, 2); else E2_ATTN(64, 1); }
 #undef E2_ATTN
     timing_end(1, st);
     E2_HIP(hipGetLastError());
