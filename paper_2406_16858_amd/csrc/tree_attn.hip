@@ -136,19 +136,16 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     u32x4 krA[NKP], vrA[4], krB[NKP], vrB[4];
     // per-thread source pointers of the next tile to fetch, advanced by one tile per fetch (no 64-bit
     // multiplies in the loop)
-    const uint16_t* kptr[NKP];
-#pragma unroll
-    for (int i = 0; i < NKP; ++i) {
-        const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
-        kptr[i] = kbase + (size_t)key * kv_stride + c * 8;
-    }
+    // piece i of a thread is (TA_THREADS / SLOTS) keys after piece i-1: one pointer, uniform offsets
+    const uint16_t* kptr = kbase + (size_t)(tid / SLOTS) * kv_stride + (tid % SLOTS) * 8;
+    const size_t kpiece = (size_t)(TA_THREADS / SLOTS) * kv_stride;
     const uint16_t* vptr = vbase + (size_t)(v_kg * 4) * kv_stride + v_c * 8;
     const size_t tile_step = (size_t)TA_KEYS * kv_stride;
     auto fetch_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[4]) {
         const int key0 = tile * TA_KEYS;
         if (key0 + TA_KEYS <= count) {                 // full tile (uniform): no bounds checks
 #pragma unroll
-            for (int i = 0; i < NKP; ++i) kr[i] = *reinterpret_cast<const u32x4*>(kptr[i]);
+            for (int i = 0; i < NKP; ++i) kr[i] = *reinterpret_cast<const u32x4*>(kptr + i * kpiece);
             if (v_owner) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) vr[i] = *reinterpret_cast<const u32x4*>(vptr + (size_t)i * kv_stride);
@@ -156,14 +153,13 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
         } else {
 #pragma unroll
             for (int i = 0; i < NKP; ++i)
-                kr[i] = key0 + (tid + i * TA_THREADS) / SLOTS < count ? *reinterpret_cast<const u32x4*>(kptr[i]) : u32x4{0u, 0u, 0u, 0u};
+                kr[i] = key0 + (tid + i * TA_THREADS) / SLOTS < count ? *reinterpret_cast<const u32x4*>(kptr + i * kpiece) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 vr[i] = (v_owner && key0 + v_kg * 4 + i < count) ? *reinterpret_cast<const u32x4*>(vptr + (size_t)i * kv_stride)
                                                                  : u32x4{0u, 0u, 0u, 0u};
         }
-#pragma unroll
-        for (int i = 0; i < NKP; ++i) kptr[i] += tile_step;
+        kptr += tile_step;
         vptr += tile_step;
     };
     const int ntile = (count + TA_KEYS - 1) / TA_KEYS;
