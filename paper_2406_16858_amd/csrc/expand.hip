@@ -322,28 +322,49 @@ __device__ __forceinline__ float* logit_row_ptr(int m, int F, int V, float* logi
     return logits_out + ((size_t)b * logit_rows_per_seq + logit_row_base + s) * (size_t)V;
 }
 
-// Workgroup = 4 waves, task = 64 vocab rows x the whole K; a stage is 256 bytes of K of the 64 W
-// rows and of all the frontier rows of this pass, staged through LDS (XOR-swizzled 16-byte
-// slots) and shared by the waves.  (Reading the frontier fragments straight from global memory
-// in MFMA order instead was measured slower: 16 rows per load instruction.)  Wave (kh, mh)
-// multiplies K half kh of the stage for half mh of the frontier blocks (at most five) with all
-// four 16-row W blocks: the four waves carry the same number of MFMAs, and a W fragment feeds
-// up to five of them.  At the end of a task the two K halves are added through LDS, each wave
-// finishing two of the four W blocks.  In registers, W runs two stages ahead of the
-// multiplication and the frontier rows one.
+// Frontier rows re-tiled into MFMA B-fragment order (a fragment = 16 rows x 64 bytes of K = 64 lanes
+// x 16 bytes, contiguous): Hp[block of 16 rows][64-byte K step][lane][16 B].  H is small (M x K), so
+// this pre-pass costs a few microseconds; it lets the GEMM's waves fetch their fragments with
+// fully coalesced 1 KiB loads straight into registers instead of staging H through LDS.
+__global__ __launch_bounds__(256)
+void pack_h_kernel(const uint8_t* __restrict__ Hraw, int64_t h_seq_bytes, int row_bytes, int M, int F,
+                   u32x4* __restrict__ Hp, size_t npieces) {
+    const int ksteps = row_bytes / 64;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < npieces; i += (size_t)gridDim.x * 256) {
+        const int lane = (int)(i & 63), m16 = lane & 15, g = lane >> 4;
+        const size_t frag = i >> 6;
+        const int kstep = (int)(frag % ksteps);
+        const int m = (int)(frag / ksteps) * 16 + m16;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (m < M) {
+            const int b = m / F, s = m - b * F;
+            v = *reinterpret_cast<const u32x4*>(Hraw + (int64_t)b * h_seq_bytes + (int64_t)s * row_bytes + (size_t)kstep * 64 + g * 16);
+        }
+        Hp[i] = v;
+    }
+}
+
+// Workgroup = 4 waves, task = 64 vocab rows x the whole K; a stage is 256 bytes of K.  The W stage
+// goes through LDS (XOR-swizzled 16-byte slots, two buffers, one barrier per stage) and is shared
+// by the waves; the frontier fragments come from the re-tiled copy Hp (L2 hits), each fragment
+// loaded by the one wave that needs it.  Wave (kh, mh) multiplies K half kh of the stage for half
+// mh of the frontier blocks (at most five) with all four 16-row W blocks: the four waves carry
+// the same number of MFMAs, and a W fragment feeds up to five of them.  At the end of a task the
+// two K halves are added through LDS, each wave finishing two of the four W blocks.  In registers,
+// W runs two stages ahead of the multiplication and the frontier fragments one.
 constexpr int GB_RED = 4 * (GB_MBMAX / 2) * 2 * 64 * 16;   // bytes of the end-of-task exchange area
+constexpr int GB_SMEM = 2 * GB_WSTAGE + GB_RED;
 
 template <bool BF16>
 __global__ __launch_bounds__(LM_THREADS, 2)
 void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
-                        const uint8_t* __restrict__ Hraw, int64_t h_seq_bytes, int M, int F, int B,
+                        const uint8_t* __restrict__ Hp, int M, int F, int B,
                         unsigned* __restrict__ done_count, float* __restrict__ logits_ws,
                         float* __restrict__ logits_out, int logit_rows_per_seq, int logit_row_base) {
     constexpr int MH = GB_MBMAX / 2;                   // frontier blocks per wave
     constexpr int TH = GB_CHUNK / 128;                 // 64-byte K fragments per wave per stage
     extern __shared__ __align__(16) uint8_t smem[];
-    uint8_t* sW = smem;
-    uint8_t* sH = smem + GB_WSTAGE;
+    floatx4* red = reinterpret_cast<floatx4*>(smem + 2 * GB_WSTAGE);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m16 = lane & 15, g = lane >> 4;          // MFMA lane coordinates
     const int r16 = tid >> 4, c16 = tid & 15;          // load coordinates: 16 rows x 256 B per instruction
@@ -354,6 +375,7 @@ void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     const int nlo = (nmb + 1) >> 1;
     const int mfirst = mh ? nlo : 0, mcnt = mh ? nmb - nlo : nlo;   // this wave's frontier blocks
     const int nst = row_bytes / GB_CHUNK;
+    const int ksteps = row_bytes / 64;
     const int ntask = (V + LM_ROWS - 1) / LM_ROWS;
     const int tq = ntask / G, tr = ntask - tq * G;
     const int my_tasks = tq + ((int)blockIdx.x < tr ? 1 : 0);
@@ -363,17 +385,8 @@ void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     if (blockIdx.x == 0 && blockIdx.y == 0)            // counters of the merge kernel's last-arrival test
         for (int i = tid; i < B; i += LM_THREADS) done_count[i] = 0u;
 
-    // frontier rows this thread stages (row r16 of block j) and the rows it stores
-    const uint8_t* hsrc[GB_MBMAX];
-#pragma unroll
-    for (int j = 0; j < GB_MBMAX; ++j) {
-        const int m = (mb0 + j) * 16 + r16;
-        hsrc[j] = nullptr;
-        if (j < nmb && m < M) {
-            const int b = m / F, s = m - b * F;
-            hsrc[j] = Hraw + (int64_t)b * h_seq_bytes + (int64_t)s * row_bytes + c16 * 16;
-        }
-    }
+    // this wave's fragments of stage 0 start here; block jj is ksteps KiB further, a stage 4 KiB
+    const uint8_t* hbase = Hp + ((size_t)(mb0 + mfirst) * ksteps + kh * TH) * 1024 + lane * 16;
     float* lrow[MH];
 #pragma unroll
     for (int jj = 0; jj < MH; ++jj) {
@@ -382,16 +395,18 @@ void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
                                         : nullptr;
     }
 
-    // W is fetched two stages ahead (two register sets, used alternately), the frontier rows (L2
-    // hits) one stage ahead and *before* the younger W loads: loads retire in order, so the wait
-    // for a stage's operands leaves the W loads of the stage after it in flight.
-    u32x4 RWa[4], RWb[4], RH[GB_MBMAX];
+    // W is fetched two stages ahead (two register sets, used alternately), the frontier fragments
+    // one stage ahead and *before* the younger W loads: loads retire in order, so the wait for a
+    // stage's operands leaves the W loads of the stage after it in flight.
+    u32x4 RWa[4], RWb[4], hn[MH][TH];
     auto issue_h = [&](int it) {
         const int st = it - (it / nst) * nst;
-        const size_t kb = (size_t)st * GB_CHUNK;
+        const uint8_t* src = hbase + (size_t)st * (GB_CHUNK / 64) * 1024;
 #pragma unroll
-        for (int j = 0; j < GB_MBMAX; ++j)
-            if (j < nmb) RH[j] = hsrc[j] ? *reinterpret_cast<const u32x4*>(hsrc[j] + kb) : u32x4{0u, 0u, 0u, 0u};
+        for (int jj = 0; jj < MH; ++jj)
+#pragma unroll
+            for (int tt = 0; tt < TH; ++tt)
+                if (jj < mcnt) hn[jj][tt] = *reinterpret_cast<const u32x4*>(src + ((size_t)jj * ksteps + tt) * 1024);
     };
     auto issue_w = [&](int it, u32x4 (&RW)[4]) {
         const int task = task_first + it / nst;
@@ -411,16 +426,18 @@ void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb) acc[jj][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    auto step = [&](int it, u32x4 (&RW)[4]) {
+    auto step = [&](int it, u32x4 (&RW)[4], uint8_t* sW) {
         const int ti = it / nst;
         const int st = it - ti * nst;
-        __syncthreads();                               // the previous stage has been multiplied
+        // this buffer was last read two stages ago, and every wave has passed a barrier since
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             *reinterpret_cast<u32x4*>(sW + (j * 16 + r16) * GB_CHUNK + ((c16 ^ r16) << 4)) = RW[j];
+        u32x4 hf[MH][TH];
 #pragma unroll
-        for (int j = 0; j < GB_MBMAX; ++j)
-            if (j < nmb) *reinterpret_cast<u32x4*>(sH + (j * 16 + r16) * GB_CHUNK + ((c16 ^ r16) << 4)) = RH[j];
+        for (int jj = 0; jj < MH; ++jj)
+#pragma unroll
+            for (int tt = 0; tt < TH; ++tt) hf[jj][tt] = hn[jj][tt];
         __syncthreads();
         if (it + 1 < total) issue_h(it + 1);
         if (it + 2 < total) issue_w(it + 2, RW);
@@ -435,18 +452,16 @@ void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
 #pragma unroll
             for (int jj = 0; jj < MH; ++jj) {
                 if (jj < mcnt) {                       // uniform over the wave
-                    const u32x4 hf = *reinterpret_cast<const u32x4*>(
-                        sH + ((mfirst + jj) * 16 + m16) * GB_CHUNK + (((t * 4 + g) ^ m16) << 4));
 #pragma unroll
                     for (int nb = 0; nb < 4; ++nb) {
                         if constexpr (BF16) {
                             acc[jj][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                __builtin_bit_cast(bf16x8, wf[nb]), __builtin_bit_cast(bf16x8, hf), acc[jj][nb], 0, 0, 0);
+                                __builtin_bit_cast(bf16x8, wf[nb]), __builtin_bit_cast(bf16x8, hf[jj][tt]), acc[jj][nb], 0, 0, 0);
                         } else {
 #pragma unroll
                             for (int e = 0; e < 4; ++e)
                                 acc[jj][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(
-                                    __uint_as_float(wf[nb][e]), __uint_as_float(hf[e]), acc[jj][nb], 0, 0, 0);
+                                    __uint_as_float(wf[nb][e]), __uint_as_float(hf[jj][tt][e]), acc[jj][nb], 0, 0, 0);
                         }
                     }
                 }
@@ -457,9 +472,8 @@ void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
             // Add the two K halves: wave kh finishes W blocks 2 kh and 2 kh + 1 (its accumulators 0, 1:
             // accumulator nb of wave kh belongs to W block (nb + 2 kh) mod 4, so that register
             // indices stay compile-time constants) and hands the other two to its partner through
-            // LDS (the stage buffers are idle after the barrier).
-            floatx4* red = reinterpret_cast<floatx4*>(smem);
-            __syncthreads();
+            // LDS.  The area is written again only after the next task's barriers, which every
+            // wave reaches after this read.
 #pragma unroll
             for (int jj = 0; jj < MH; ++jj)
 #pragma unroll
@@ -494,8 +508,8 @@ void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     if (total > 0) { issue_w(0, RWa); issue_h(0); }
     if (total > 1) issue_w(1, RWb);
     for (int it = 0; it < total; it += 2) {
-        step(it, RWa);
-        if (it + 1 < total) step(it + 1, RWb);
+        step(it, RWa, smem);
+        if (it + 1 < total) step(it + 1, RWb, smem + GB_WSTAGE);
     }
 }
 
@@ -811,7 +825,7 @@ static int lm_grid(const eagle2_cfg* cfg) {
     return g < 1 ? 1 : g;
 }
 
-struct ExpandWs { size_t ms, val, idx, cnt, logits, total; };
+struct ExpandWs { size_t ms, val, idx, cnt, logits, hp, total; };
 static ExpandWs expand_layout(const eagle2_cfg* cfg) {
     const size_t mmax = (size_t)cfg->batch * cfg->topk;
     const size_t mblks = (mmax + 15) / 16;
@@ -822,7 +836,9 @@ static ExpandWs expand_layout(const eagle2_cfg* cfg) {
     w.cnt = w.idx + round_up(mblks * 16 * LM_GMAX * EAGLE2_MAX_TOPK * sizeof(int), 256);
     w.logits = w.cnt + round_up((size_t)cfg->batch * sizeof(unsigned), 256);
     // dense [M, V] logits of the many-row path (used when the caller keeps no draft logits)
-    w.total = w.logits + (mmax > 16 ? round_up(mmax * (size_t)cfg->vocab * sizeof(float), 256) : 0);
+    w.hp = w.logits + (mmax > 16 ? round_up(mmax * (size_t)cfg->vocab * sizeof(float), 256) : 0);
+    // frontier rows re-tiled into fragment order for the many-row path
+    w.total = w.hp + (mmax > 16 ? round_up(mblks * 16 * (size_t)cfg->hidden * elem_size(cfg), 256) : 0);
     return w;
 }
 size_t expand_workspace(const eagle2_cfg* cfg) { return expand_layout(cfg).total; }
@@ -851,13 +867,15 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
         if (gg > ntask) gg = ntask;
         const int ny = (mblks + GB_MBMAX - 1) / GB_MBMAX;
         float* logits_ws = reinterpret_cast<float*>(ws + L.logits);
-        const int nmb_max = mblks < GB_MBMAX ? mblks : GB_MBMAX;
-        size_t gemm_smem = GB_WSTAGE + (size_t)nmb_max * 16 * GB_CHUNK;      // stage buffers, reused by the end-of-task exchange
-        if (gemm_smem < (size_t)GB_RED) gemm_smem = GB_RED;
+        uint8_t* Hp = ws + L.hp;
+        const size_t npieces = (size_t)mblks * 16 * row_bytes / 16;
+        hipLaunchKernelGGL(pack_h_kernel, dim3((unsigned)((npieces + 255) / 256)), dim3(256), 0, st,
+                           reinterpret_cast<const uint8_t*>(H), stride_el * elem_size(cfg), row_bytes, M, F,
+                           reinterpret_cast<u32x4*>(Hp), npieces);
+        E2_HIP(hipGetLastError());
         timing_begin(0, st);
-        hipLaunchKernelGGL((lmhead_gemm_kernel<BF16>), dim3(gg, ny), dim3(LM_THREADS), gemm_smem, st,
-                           reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab,
-                           reinterpret_cast<const uint8_t*>(H), stride_el * elem_size(cfg), M, F, cfg->batch, done_count,
+        hipLaunchKernelGGL((lmhead_gemm_kernel<BF16>), dim3(gg, ny), dim3(LM_THREADS), GB_SMEM, st,
+                           reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab, Hp, M, F, cfg->batch, done_count,
                            logits_ws, draft_logits, R, row_base);
         timing_end(0, st);
         E2_HIP(hipGetLastError());
