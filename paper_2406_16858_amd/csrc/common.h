@@ -38,6 +38,12 @@ size_t accept_workspace(const eagle2_cfg* cfg);
 
 int device_cu_count();
 
+// dense float32 out[M, N] = X[M, K] . W[N, K]^T for more than 16 rows, W streamed once per 160 rows
+// (X row (b, s) at X + b * x_seq_bytes + s * row_bytes; hp_ws: ceil(M/16)*16 * row_bytes bytes of scratch;
+// done_count[0 .. n_done) is zeroed as a side job, n_done may be 0)
+int gemm_rows(bool bf16, const void* X, int64_t x_seq_bytes, int M, int F, const void* W, int N, int row_bytes,
+              float* out, void* hp_ws, unsigned* done_count, int n_done, hipStream_t st);
+
 // tree attention restricted to the query rows q0 .. q0+nq-1 (same arguments as eagle2_tree_attn otherwise)
 int tree_attn_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int q0, int nq,
                    const void* Q, const void* K_prefix, const void* V_prefix, const int64_t* kv_offsets, const int32_t* kv_len,

@@ -333,7 +333,7 @@ static int pick_slices(int n_out, int64_t row_bytes) {
     return best;
 }
 
-struct DraftWs { size_t x_in, part, x0, h1, nrm, act, q, o, pos, attn, total; };
+struct DraftWs { size_t x_in, part, x0, h1, nrm, act, q, o, pos, hp, attn, total; };
 static DraftWs draft_layout(const eagle2_cfg* cfg, const eagle2_draft_cfg* dc, const eagle2_attn_cfg* ac, const eagle2_cfg* acfg) {
     const size_t M = (size_t)cfg->batch * cfg->topk, m_pad = (M + 15) / 16 * 16, es = elem_size(cfg);
     const size_t Hd = cfg->hidden, Rd = draft_rows(cfg);
@@ -356,6 +356,9 @@ static DraftWs draft_layout(const eagle2_cfg* cfg, const eagle2_draft_cfg* dc, c
     w.q = take((size_t)cfg->batch * Rd * dc->n_q_heads * dc->head_dim * es);
     w.o = take((size_t)cfg->batch * Rd * dc->n_q_heads * dc->head_dim * es);
     w.pos = take(M * sizeof(int));
+    size_t kmax = 2 * Hd > qd ? 2 * Hd : qd;               // widest input row of the five products
+    kmax = kmax > inter ? kmax : inter;
+    w.hp = take(M > 16 ? m_pad * kmax * es : 0);           // re-tiled input rows of the many-row path
     size_t aw = attn_workspace_rows(acfg, ac, 1);          // pass 0 has one query row, later passes k
     const size_t aw_k = attn_workspace_rows(acfg, ac, cfg->topk < acfg->n_tree ? cfg->topk : acfg->n_tree);
     w.attn = take(aw > aw_k ? aw : aw_k);
@@ -395,7 +398,13 @@ static void draft_attn_cfgs(const eagle2_cfg* cfg, const eagle2_draft_cfg* dc, i
 
 template <bool BF16>
 static int launch_linear(const void* X, int64_t x_seq_bytes, int M, int F, const void* W, int n_out, int64_t row_bytes,
-                         float* part, int m_pad, int* slices_out, hipStream_t st) {
+                         float* part, int m_pad, void* hp_ws, int* slices_out, hipStream_t st) {
+    if (M > 16) {
+        // many rows (batched serving): one pass over W for up to 160 rows instead of one per 16-row block;
+        // the output is dense [M, n_out], i.e. a single slice with row pitch n_out
+        *slices_out = 1;
+        return gemm_rows(BF16, X, x_seq_bytes, M, F, W, n_out, (int)row_bytes, part, hp_ws, nullptr, 0, st);
+    }
     const int S = pick_slices(n_out, row_bytes);
     const int ntask = (n_out + DL_ROWS - 1) / DL_ROWS;
     int G = 2 * device_cu_count();
@@ -485,8 +494,8 @@ extern "C" int eagle2_draft_forward(const eagle2_cfg* cfg, const eagle2_draft_cf
     E2_HIP(hipGetLastError());
     int S = 1;
 #define E2_LIN(X, XSEQ, FF, WT, NOUT, KIN)                                                                         \
-    rc = bf ? launch_linear<true>(X, XSEQ, M, FF, WT, NOUT, (int64_t)(KIN) * es, part, m_pad, &S, st)              \
-            : launch_linear<false>(X, XSEQ, M, FF, WT, NOUT, (int64_t)(KIN) * es, part, m_pad, &S, st);            \
+    rc = bf ? launch_linear<true>(X, XSEQ, M, FF, WT, NOUT, (int64_t)(KIN) * es, part, m_pad, ws + L.hp, &S, st)              \
+            : launch_linear<false>(X, XSEQ, M, FF, WT, NOUT, (int64_t)(KIN) * es, part, m_pad, ws + L.hp, &S, st);            \
     if (rc != EAGLE2_OK) return rc
     // fusion of [embedding ; feature], then the attention block
     E2_LIN(x_in, (int64_t)2 * Hd * es, 1, wt->fc, Hd, 2 * Hd);

@@ -817,6 +817,31 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     }
 }
 
+// out[M, N] (float32, dense) = X[M, K] . W[N, K]^T for M > 16 rows: pack_h_kernel + lmhead_gemm_kernel.
+// X row m = (b, s) lives at X + b * x_seq_bytes + s * row_bytes; hp_ws needs ceil(M/16)*16 * row_bytes bytes.
+int gemm_rows(bool bf16, const void* X, int64_t x_seq_bytes, int M, int F, const void* W, int N, int row_bytes,
+              float* out, void* hp_ws, unsigned* done_count, int n_done, hipStream_t st) {
+    const int mblks = (M + 15) / 16;
+    const int ntask = (N + LM_ROWS - 1) / LM_ROWS;
+    int gg = 2 * device_cu_count();
+    if (gg > ntask) gg = ntask;
+    const int ny = (mblks + GB_MBMAX - 1) / GB_MBMAX;
+    const size_t npieces = (size_t)mblks * 16 * row_bytes / 16;
+    hipLaunchKernelGGL(pack_h_kernel, dim3((unsigned)((npieces + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const uint8_t*>(X), x_seq_bytes, row_bytes, M, F, static_cast<u32x4*>(hp_ws), npieces);
+    E2_HIP(hipGetLastError());
+    if (bf16)
+        hipLaunchKernelGGL((lmhead_gemm_kernel<true>), dim3(gg, ny), dim3(LM_THREADS), GB_SMEM, st, static_cast<const uint8_t*>(W),
+                           row_bytes, N, static_cast<const uint8_t*>(hp_ws), M, F, n_done, done_count, out,
+                           static_cast<float*>(nullptr), 0, 0);
+    else
+        hipLaunchKernelGGL((lmhead_gemm_kernel<false>), dim3(gg, ny), dim3(LM_THREADS), GB_SMEM, st, static_cast<const uint8_t*>(W),
+                           row_bytes, N, static_cast<const uint8_t*>(hp_ws), M, F, n_done, done_count, out,
+                           static_cast<float*>(nullptr), 0, 0);
+    E2_HIP(hipGetLastError());
+    return EAGLE2_OK;
+}
+
 static int lm_grid(const eagle2_cfg* cfg) {
     const int ntask = (cfg->vocab + LM_ROWS - 1) / LM_ROWS;
     int g = 2 * device_cu_count();                     // two resident workgroups per compute unit

@@ -106,7 +106,13 @@ def _run(cfg, dl, verbose=True):
      wl.DraftLayerConfig(8, 8, 64, 512, 1e-5, 10000.0)),
     (_small("draft_k16_rows113", batch=1, vocab=2048, hidden=512, depth=8, topk=16, n_tree=64, prefix_lo=33, prefix_hi=33, seed=56),
      wl.DraftLayerConfig(8, 4, 64, 1024, 1e-5, 10000.0)),
-], ids=["bf16_gqa_dh64", "fp32", "bf16_mha_dh128_rows30", "chain_k1", "depth1_two_row_minimum", "k16_113_draft_rows"])
+    # more than 16 (and more than 160) rows per pass: the products run through the many-row GEMM
+    (_small("draft_rows200", batch=20, vocab=2048, hidden=512, depth=2, topk=10, n_tree=12, prefix_lo=0, prefix_hi=60, seed=57),
+     wl.DraftLayerConfig(8, 2, 64, 1024, 1e-5, 10000.0)),
+    (_small("draft_rows36_fp32", dtype="fp32", batch=9, vocab=777, hidden=256, depth=3, topk=4, n_tree=10, prefix_lo=5, prefix_hi=30, seed=58),
+     wl.DraftLayerConfig(4, 2, 64, 512, 1e-5, 10000.0)),
+], ids=["bf16_gqa_dh64", "fp32", "bf16_mha_dh128_rows30", "chain_k1", "depth1_two_row_minimum", "k16_113_draft_rows",
+        "rows200_bf16", "rows36_fp32"])
 def test_draft_layer_small(cfg, dl):
     _run(cfg, dl)
 
