@@ -314,7 +314,7 @@ int eagle2_commit_round(const eagle2_cfg* cfg, const int32_t* accept_len, const 
  *                wqkv [(Hq + 2Hkv)dh, Hd] (query rows, key rows, value rows);
  *                wo [Hd, Hq dh]; wgu [2I, Hd] (gate rows, up rows); wdown [Hd, I];
  *                g_attn, g_mlp [Hd] RMSNorm gains.  Every matrix row must be a
- *                multiple of 1024 bytes.
+ *                multiple of 256 bytes and at least 1024 bytes long.
  *   cand_token, cand_parent, frontier   as left by the expand passes before d
  *   root_token [B] int32, root_feature [B, Hd] dtype, prefix_len [B] int32
  *   K_prefix, V_prefix [total_prefix, Hkv, dh] dtype, kv_offsets [B+1] int64: the

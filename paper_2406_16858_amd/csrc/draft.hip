@@ -21,11 +21,11 @@ constexpr int DL_CHUNK = 256;                // bytes of K per row per stage per
 constexpr int DL_STAGE = DL_ROWS * DL_CHUNK;
 constexpr int DL_LOADS = DL_ROWS * DL_CHUNK / 1024;
 
-// part[slice][m_pad][N] (+)= X[M, K-slice] . W[N, K-slice]^T.  Input row m = (b, s) lives at
+// part[slice][m_pad][N] = X[M, K-slice] . W[N, K-slice]^T.  Input row m = (b, s) lives at
 // X + b * x_seq_bytes + s * row_bytes (the same addressing as the LM-head kernel's H).
 template <bool BF16>
 __global__ __launch_bounds__(DL_THREADS, 2)
-void linear_kernel(const uint8_t* __restrict__ W, int row_bytes, int N, int slice_bytes,
+void linear_kernel(const uint8_t* __restrict__ W, int row_bytes, int N,
                    const uint8_t* __restrict__ Xraw, int64_t x_seq_bytes, int M, int F,
                    float* __restrict__ part, int m_pad) {
     extern __shared__ __align__(16) uint8_t smem[];
@@ -33,9 +33,12 @@ void linear_kernel(const uint8_t* __restrict__ W, int row_bytes, int N, int slic
     const int m16 = lane & 15, g = lane >> 4;          // MFMA lane coordinates
     const int r_in = lane >> 4, c16 = lane & 15;       // load coordinates: 4 rows x 256 B per instruction
     const int G = gridDim.x, mblk = blockIdx.y, slice = blockIdx.z;
-    const int wave_bytes = slice_bytes >> 2;           // K bytes owned by this wave
-    const size_t kbase = (size_t)slice * slice_bytes + (size_t)w * wave_bytes;
-    const int nst = wave_bytes / DL_CHUNK;
+    // The row's 256-byte stages are dealt as evenly as possible to the 4 * slices (slice, wave) units,
+    // consecutive stages per unit: K need only be a multiple of 256 bytes (units differ by one stage at most).
+    const int stages = row_bytes / DL_CHUNK, units = 4 * (int)gridDim.z, unit = slice * 4 + w;
+    const int sq = stages / units, sr = stages - sq * units;
+    const int nst = sq + (unit < sr ? 1 : 0);          // >= 1: the host keeps 4 * slices <= stages
+    const size_t kbase = (size_t)(unit * sq + min(unit, sr)) * DL_CHUNK;
     const int ntask = (N + DL_ROWS - 1) / DL_ROWS;
     const int tq = ntask / G, tr = ntask - tq * G;
     const int my_tasks = tq + ((int)blockIdx.x < tr ? 1 : 0);
@@ -323,14 +326,15 @@ void zero_fill_kernel(ZeroJobs z) {                    // one launch clears all 
 
 static int draft_rows(const eagle2_cfg* c) { const int r = n_draft_rows(c); return r < 2 ? 2 : r; }
 
-// K slices per matrix: the largest divisor S of (row bytes / 1 KiB) with tasks * S <= 640 workgroups
+// K slices per matrix: as many as keep tasks * slices <= 640 workgroups, at most 32, and every wave of
+// every slice at least one 256-byte stage
 static int pick_slices(int n_out, int64_t row_bytes) {
     const int ntask = (n_out + DL_ROWS - 1) / DL_ROWS;
-    const int units = (int)(row_bytes / 1024);
-    int best = 1;
-    for (int s = 1; s <= units && s <= 32; ++s)
-        if (units % s == 0 && (int64_t)ntask * s <= 640) best = s;
-    return best;
+    const int stages = (int)(row_bytes / DL_CHUNK);
+    int s = 640 / ntask;
+    if (s > 32) s = 32;
+    if (s > stages / 4) s = stages / 4;
+    return s < 1 ? 1 : s;
 }
 
 struct DraftWs { size_t x_in, part, x0, h1, nrm, act, q, o, pos, hp, attn, total; };
@@ -372,10 +376,11 @@ static int validate_draft(const eagle2_cfg* cfg, const eagle2_draft_cfg* dc) {
     E2_REQUIRE(dc->n_kv_heads >= 1 && dc->n_q_heads % dc->n_kv_heads == 0 && dc->n_q_heads >= dc->n_kv_heads && dc->n_q_heads <= 1024,
                EAGLE2_ERR_SHAPE, "draft heads %d/%d", dc->n_q_heads, dc->n_kv_heads);
     const int64_t es = elem_size(cfg);
-    E2_REQUIRE(dc->intermediate >= 1 && ((int64_t)dc->intermediate * es) % 1024 == 0, EAGLE2_ERR_SHAPE,
-               "draft intermediate size %d: a row of the down projection must be a multiple of 1024 bytes", dc->intermediate);
-    E2_REQUIRE(((int64_t)dc->n_q_heads * dc->head_dim * es) % 1024 == 0, EAGLE2_ERR_SHAPE,
-               "draft n_q_heads*head_dim: a row of the output projection must be a multiple of 1024 bytes");
+    E2_REQUIRE(dc->intermediate >= 1 && ((int64_t)dc->intermediate * es) % 256 == 0 && (int64_t)dc->intermediate * es >= 1024,
+               EAGLE2_ERR_SHAPE, "draft intermediate size %d: a row of the down projection must be a multiple of 256 bytes (>= 1024)",
+               dc->intermediate);
+    E2_REQUIRE(((int64_t)dc->n_q_heads * dc->head_dim * es) % 256 == 0 && (int64_t)dc->n_q_heads * dc->head_dim * es >= 1024,
+               EAGLE2_ERR_SHAPE, "draft n_q_heads*head_dim: a row of the output projection must be a multiple of 256 bytes (>= 1024)");
     E2_REQUIRE(dc->eps > 0.f && dc->rope_theta > 1.f, EAGLE2_ERR_ARG, "draft eps / rope_theta out of range");
     E2_REQUIRE(draft_rows(cfg) <= EAGLE2_MAX_TREE, EAGLE2_ERR_SHAPE, "1 + (depth-1)*topk = %d draft rows exceed %d",
                n_draft_rows(cfg), EAGLE2_MAX_TREE);
@@ -411,7 +416,7 @@ static int launch_linear(const void* X, int64_t x_seq_bytes, int M, int F, const
     if (G > ntask) G = ntask;
     dim3 grid(G, m_pad / 16, S);
     hipLaunchKernelGGL((linear_kernel<BF16>), grid, dim3(DL_THREADS), 4 * DL_STAGE, st,
-                       static_cast<const uint8_t*>(W), (int)row_bytes, n_out, (int)(row_bytes / S),
+                       static_cast<const uint8_t*>(W), (int)row_bytes, n_out,
                        static_cast<const uint8_t*>(X), x_seq_bytes, M, F, part, m_pad);
     E2_HIP(hipGetLastError());
     *slices_out = S;

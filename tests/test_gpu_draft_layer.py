@@ -117,6 +117,16 @@ def test_draft_layer_small(cfg, dl):
     _run(cfg, dl)
 
 
+def test_draft_layer_uneven_k_split():
+    """An intermediate size whose rows are an odd number (43) of 256-byte stages, like the 7B models' 11008 (86 stages)."""
+    cfg = _small("draft_uneven", batch=1, vocab=2048, hidden=512, depth=3, topk=6, n_tree=12, prefix_lo=9, prefix_hi=9, seed=59)
+    _run(cfg, wl.DraftLayerConfig(8, 2, 64, 43 * 128, 1e-5, 10000.0))
+
+
+def test_draft_layer_llama2_7b_shape():
+    _run(wl.get_config(2), wl.DRAFT_LAYERS["llama2_7b"])
+
+
 def test_draft_layer_llama3_8b_shape():
     """The 8B decoder-layer shape with the headline round configuration (D = 6, k = 10)."""
     cfg = wl.get_config(3)
@@ -127,6 +137,7 @@ def test_draft_validation():
     from paper_2406_16858_amd import DraftCfg, RoundCfg, eagle2_draft_workspace_bytes, load_library
     cfg = RoundCfg(1, 32000, 4096, 6, 10, 60, 1)
     assert eagle2_draft_workspace_bytes(cfg, DraftCfg(32, 8, 128, 14336, 1e-5, 1e4), 4096) > 0
-    assert eagle2_draft_workspace_bytes(cfg, DraftCfg(32, 8, 128, 11008, 1e-5, 1e4), 4096) == 0     # 11008 * 2 B is not a multiple of 1 KiB
-    assert "1024" in load_library().eagle2_last_error().decode()
+    assert eagle2_draft_workspace_bytes(cfg, DraftCfg(32, 8, 128, 11008, 1e-5, 1e4), 4096) > 0      # 86 stages of 256 B: uneven split
+    assert eagle2_draft_workspace_bytes(cfg, DraftCfg(32, 8, 128, 11000, 1e-5, 1e4), 4096) == 0     # 22000 B is not a multiple of 256
+    assert "256" in load_library().eagle2_last_error().decode()
     assert eagle2_draft_workspace_bytes(cfg, DraftCfg(32, 5, 128, 14336, 1e-5, 1e4), 4096) == 0

@@ -64,6 +64,7 @@ class DraftLayerConfig:
 
 # decoder-layer shapes of the model families behind the round configurations
 DRAFT_LAYERS = {
+    "llama2_7b": DraftLayerConfig(32, 32, 128, 11008, 1e-5, 10000.0),
     "llama3_8b": DraftLayerConfig(32, 8, 128, 14336, 1e-5, 500000.0),
     "llama2_13b_m50": DraftLayerConfig(40, 40, 128, 13824, 1e-5, 10000.0),
     "llama2_70b_m48": DraftLayerConfig(64, 8, 128, 28672, 1e-5, 10000.0),
