@@ -2,11 +2,15 @@
 // frontier rows, log-softmax, per-row top-k, joint-score accumulation along the path
 // (value equation of Section 4.1, as a sum of logs) and selection of the next frontier.
 //
-// Two kernels per pass:
+// Two kernels per pass with at most 16 frontier rows:
 //   lmhead_kernel       streams W once from HBM; per workgroup and frontier row it
 //                       emits a partial (max, sum-exp, top-k) over the vocab rows it saw
 //   expand_merge_kernel merges the partials, appends the k children per row with their
 //                       joint scores and picks the next frontier
+// With more rows (batched serving) the first kernel is replaced by three:
+//   pack_h_kernel       re-tiles the frontier rows into MFMA fragment order
+//   lmhead_gemm_kernel  streams W once per 160 rows and writes the raw logits
+//   row_stats_kernel    turns each row's logits into the same partials
 //
 // lmhead_kernel layout.  The contraction runs on the matrix cores with the *weight tile*
 // as the 16-row A operand and the (zero-padded to 16) frontier rows as the B operand, so
