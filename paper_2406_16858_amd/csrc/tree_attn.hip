@@ -7,7 +7,7 @@
 // Hq/Hkv * N query rows of a KV head share each K/V tile.  Both products are computed
 // transposed so that every lane keeps a single query row:
 //     S^T = K . Q^T   (A = K tile from LDS, B = Q fragments held in registers)
-//     O^T = V^T . P^T (A = V^T tile from LDS, B = the probabilities just computed)
+//     O^T = V^T . P^T (A = V tile from LDS through the transposing read, B = the probabilities just computed)
 // The output registers of the first product are, lane for lane, the B operand of the
 // second (the contraction index of an MFMA may be permuted freely as long as A and B
 // agree), so P never goes through LDS.  The ancestor bitmask is applied to the tree
@@ -54,7 +54,16 @@ __device__ __forceinline__ void locate_seq(int b, int chunk, const long long* kv
 }
 
 template <int DH> __device__ __forceinline__ int k_swz(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
-__device__ __forceinline__ int v_swz(int row) { return (row & 15) ^ (((row >> 4) & 7) << 1); }
+// V rows are cut into 32-byte granules (16 dh: what one PV fragment covers); a row's granules are
+// permuted by its key index so that the four key rows one transpose read touches fall in different banks
+template <int DH> __device__ __forceinline__ int v_swz(int key) { return key & (DH / 16 - 1); }
+// LDS transpose read: within each 16 lanes, lane j passes the address of 4 consecutive 16-bit elements
+// D[j][0..3] and receives D[j/4 + 4i][j%4], i = 0..3
+typedef short short4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x2 lds_read_tr16(const uint8_t* p) {
+    const short4v r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)p);
+    return __builtin_bit_cast(u32x2, r);
+}
 
 template <int DH, int RBW>
 __global__ __launch_bounds__(TA_THREADS, 2)
@@ -70,7 +79,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     constexpr int SLOTS = DH / 8;                  // 16-byte slots per K row
     constexpr int BM = 64 * RBW;                   // query rows per workgroup
     __shared__ __align__(16) uint8_t s_k[TA_KEYS * DH * 2];
-    __shared__ __align__(16) uint8_t s_vt[DH * TA_KEYS * 2];
+    __shared__ __align__(16) uint8_t s_v[TA_KEYS * DH * 2];
     // wide variant: the query fragments live in LDS (row-major, slots swizzled like K) instead of registers
     __shared__ __align__(16) uint8_t s_q[RBW == 2 ? BM * DH * 2 : 16];
 
@@ -128,42 +137,36 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
 
     // The next tile's K and V are fetched into registers while the current tile is multiplied.
     constexpr int NKP = TA_KEYS * SLOTS / TA_THREADS;          // 16-byte K pieces per thread per tile
-    constexpr bool V_ALL = 16 * SLOTS >= TA_THREADS;            // every thread owns a V unit (dh 128)
-    const bool v_owner = V_ALL || tid < 16 * SLOTS;
-    const int v_c = tid % SLOTS, v_kg = tid / SLOTS;            // V unit: 8 dh (chunk v_c) x 4 keys (group v_kg)
     // Two register sets, used alternately: tiles t+1 and t+2 are in flight while tile t is multiplied.
     constexpr int DEPTH = RBW == 1 ? 2 : 1;            // the wide variant has registers for one set only
-    u32x4 krA[NKP], vrA[4], krB[NKP], vrB[4];
+    u32x4 krA[NKP], vrA[NKP], krB[NKP], vrB[NKP];
     // per-thread source pointers of the next tile to fetch, advanced by one tile per fetch (no 64-bit
     // multiplies in the loop)
     // piece i of a thread is (TA_THREADS / SLOTS) keys after piece i-1: one pointer, uniform offsets
     const uint16_t* kptr = kbase + (size_t)(tid / SLOTS) * kv_stride + (tid % SLOTS) * 8;
     const size_t kpiece = (size_t)(TA_THREADS / SLOTS) * kv_stride;
-    const uint16_t* vptr = vbase + (size_t)(v_kg * 4) * kv_stride + v_c * 8;
+    const uint16_t* vptr = vbase + (size_t)(tid / SLOTS) * kv_stride + (tid % SLOTS) * 8;
     const size_t tile_step = (size_t)TA_KEYS * kv_stride;
-    auto fetch_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[4]) {
+    auto fetch_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[NKP]) {
         const int key0 = tile * TA_KEYS;
         if (key0 + TA_KEYS <= count) {                 // full tile (uniform): no bounds checks
 #pragma unroll
             for (int i = 0; i < NKP; ++i) kr[i] = *reinterpret_cast<const u32x4*>(kptr + i * kpiece);
-            if (v_owner) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) vr[i] = *reinterpret_cast<const u32x4*>(vptr + (size_t)i * kv_stride);
-            }
+            for (int i = 0; i < NKP; ++i) vr[i] = *reinterpret_cast<const u32x4*>(vptr + i * kpiece);
         } else {
 #pragma unroll
-            for (int i = 0; i < NKP; ++i)
-                kr[i] = key0 + (tid + i * TA_THREADS) / SLOTS < count ? *reinterpret_cast<const u32x4*>(kptr + i * kpiece) : u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                vr[i] = (v_owner && key0 + v_kg * 4 + i < count) ? *reinterpret_cast<const u32x4*>(vptr + (size_t)i * kv_stride)
-                                                                 : u32x4{0u, 0u, 0u, 0u};
+            for (int i = 0; i < NKP; ++i) {
+                const bool in = key0 + (tid + i * TA_THREADS) / SLOTS < count;
+                kr[i] = in ? *reinterpret_cast<const u32x4*>(kptr + i * kpiece) : u32x4{0u, 0u, 0u, 0u};
+                vr[i] = in ? *reinterpret_cast<const u32x4*>(vptr + i * kpiece) : u32x4{0u, 0u, 0u, 0u};
+            }
         }
         kptr += tile_step;
         vptr += tile_step;
     };
     const int ntile = (count + TA_KEYS - 1) / TA_KEYS;
-    auto do_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[4]) {
+    auto do_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[NKP]) {
         const int key0 = tile * TA_KEYS;
         __syncthreads();                           // previous tile fully consumed
         // K tile -> LDS, row-major, 16-byte slots swizzled by the row
@@ -172,19 +175,11 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
             const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
             *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + ((c ^ k_swz<DH>(key)) << 4)) = kr[i];
         }
-        // V tile -> LDS transposed: 4 keys x 8 dh become 8 dh rows x 4 keys (8 bytes each)
-        if (v_owner) {
+        // V tile -> LDS, row-major as well (the PV operand is transposed by the LDS read itself)
 #pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                u32x2 lo, hi;                      // dh 2*e2 and 2*e2+1, keys 0..3
-                lo[0] = (vr[0][e2] & 0xffffu) | (vr[1][e2] << 16);
-                lo[1] = (vr[2][e2] & 0xffffu) | (vr[3][e2] << 16);
-                hi[0] = (vr[0][e2] >> 16) | (vr[1][e2] & 0xffff0000u);
-                hi[1] = (vr[2][e2] >> 16) | (vr[3][e2] & 0xffff0000u);
-                const int row0 = v_c * 8 + e2 * 2, row1 = row0 + 1;
-                *reinterpret_cast<u32x2*>(s_vt + row0 * (TA_KEYS * 2) + ((v_kg ^ v_swz(row0)) << 3)) = lo;
-                *reinterpret_cast<u32x2*>(s_vt + row1 * (TA_KEYS * 2) + ((v_kg ^ v_swz(row1)) << 3)) = hi;
-            }
+        for (int i = 0; i < NKP; ++i) {
+            const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
+            *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + ((((c >> 1) ^ v_swz<DH>(key)) << 5) | ((c & 1) << 4))) = vr[i];
         }
         __syncthreads();
         if (tile + DEPTH < ntile) fetch_tile(tile + DEPTH, kr, vr);
@@ -275,9 +270,11 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
 #pragma unroll
             for (int uq = 0; uq < KBH / 2; ++uq) {
                 const int u = hh * (KBH / 2) + uq;
-                const int row = db * 16 + m16;
-                const u32x2 va = *reinterpret_cast<const u32x2*>(s_vt + row * (TA_KEYS * 2) + (((8 * u + g4) ^ v_swz(row)) << 3));
-                const u32x2 vb = *reinterpret_cast<const u32x2*>(s_vt + row * (TA_KEYS * 2) + (((8 * u + 4 + g4) ^ v_swz(row)) << 3));
+                // lane (m16, g4) passes key row 32u (+16) + 4*g4 + m16/4, dh db*16 + 4*(m16%4) .. +3 and
+                // receives dh db*16 + m16 of keys 32u (+16) + 4*g4 + i
+                const int ka = 32 * u + 4 * g4 + (m16 >> 2), kb2 = ka + 16;
+                const u32x2 va = lds_read_tr16(s_v + ka * (DH * 2) + (((db ^ v_swz<DH>(ka)) << 5) | ((m16 & 3) << 3)));
+                const u32x2 vb = lds_read_tr16(s_v + kb2 * (DH * 2) + (((db ^ v_swz<DH>(kb2)) << 5) | ((m16 & 3) << 3)));
                 const u32x4 vf = {va[0], va[1], vb[0], vb[1]};
 #pragma unroll
                 for (int rb = 0; rb < RBW; ++rb)
