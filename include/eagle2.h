@@ -207,6 +207,30 @@ int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn,
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Tree attention (Section 4.2) over a prefix cache kept in 8 bits.  The paper keeps
+ * its cache in the model's 16-bit type; this variant halves the bytes of the
+ * prefix stream, which bounds the verification pass at long contexts.
+ *
+ * Same as eagle2_tree_attn (cfg->dtype must be bf16) except:
+ *   K_prefix8, V_prefix8  [total_prefix, Hkv, dh] uint8: E4M3 codes of the OCP 8-bit
+ *                floating point format (1 sign, 4 exponent bits of bias 7, 3
+ *                mantissa bits, no infinities, largest finite value 448); NaN
+ *                codes must not occur
+ *   k_scale, v_scale      [Hkv] float32 (device), positive: key (b, t, h, :) is
+ *                value(code) * k_scale[h], likewise for V
+ * The tree's own keys and values (K_tree, V_tree) stay bf16.  Codes are widened to
+ * bf16 exactly; the scales enter in float32 (k_scale with the softmax scale,
+ * v_scale on each chunk's partial output).
+ */
+int eagle2_tree_attn_fp8kv(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn,
+                           const void* Q, const void* K_prefix8, const void* V_prefix8,
+                           const float* k_scale, const float* v_scale,
+                           const int64_t* kv_offsets, const int32_t* prefix_len,
+                           const void* K_tree, const void* V_tree,
+                           const uint64_t* mask_bits, void* O, float* lse,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Acceptance (Sections 2.1 and 2.2).
  *
  * mode[b] = EAGLE2_MODE_GREEDY: the target's choice after a row is the arg-max of
@@ -269,6 +293,27 @@ int eagle2_commit_kv(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int32_t
                      const int64_t* kv_offsets, const int32_t* prefix_len,
                      const void* K_tree, const void* V_tree, int64_t tree_layer_stride,
                      void* K_cache, void* V_cache, int64_t cache_layer_stride, void* stream);
+
+/*
+ * eagle2_commit_kv into a cache of 8-bit codes (the cache eagle2_tree_attn_fp8kv
+ * reads; Section 2.1 and Appendix "Implementation Details" as above).  Every
+ * copied bf16 element x of KV head h, layer l becomes the E4M3 code nearest to
+ * x / scale[l, h]: the quotient is one correctly rounded float32 division, values
+ * beyond +-448 saturate, ties go to the even mantissa.
+ *
+ *   K_tree, V_tree      [n_layers][B, N, Hkv, dh] bf16, layers tree_layer_stride
+ *                       elements apart
+ *   K_cache8, V_cache8  [n_layers][total_prefix, Hkv, dh] uint8 in/out, layers
+ *                       cache_layer_stride bytes apart
+ *   k_scale, v_scale    [n_layers, Hkv] float32 (device), positive
+ * Everything else as for eagle2_commit_kv.
+ */
+int eagle2_commit_kv_fp8(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int32_t n_layers,
+                         const int32_t* accept_len, const int32_t* accept_path,
+                         const int64_t* kv_offsets, const int32_t* prefix_len,
+                         const void* K_tree, const void* V_tree, int64_t tree_layer_stride,
+                         void* K_cache8, void* V_cache8, int64_t cache_layer_stride,
+                         const float* k_scale, const float* v_scale, void* stream);
 
 /*
  * Commit of a round, part 2: tokens and bookkeeping (Section 2.1; Section 2.2,

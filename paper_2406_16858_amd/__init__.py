@@ -19,12 +19,14 @@ from .binding import (  # noqa: F401
     RoundCfg,
     eagle2_accept,
     eagle2_commit_kv,
+    eagle2_commit_kv_fp8,
     eagle2_commit_round,
     eagle2_expand,
     eagle2_kernel_timing_enable,
     eagle2_kernel_timing_read,
     eagle2_rerank,
     eagle2_tree_attn,
+    eagle2_tree_attn_fp8kv,
     eagle2_version,
     eagle2_workspace_bytes,
     lib_path,

@@ -76,10 +76,14 @@ def load_library():
     lib.eagle2_rerank.argtypes = [C.POINTER(RoundCfg)] + [vp] * 12 + [vp, sz, vp]
     lib.eagle2_tree_attn.restype = C.c_int
     lib.eagle2_tree_attn.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg)] + [vp] * 10 + [vp, sz, vp]
+    lib.eagle2_tree_attn_fp8kv.restype = C.c_int
+    lib.eagle2_tree_attn_fp8kv.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg)] + [vp] * 12 + [vp, sz, vp]
     lib.eagle2_accept.restype = C.c_int
     lib.eagle2_accept.argtypes = [C.POINTER(RoundCfg)] + [vp] * 12 + [vp, sz, vp]
     lib.eagle2_commit_kv.restype = C.c_int
     lib.eagle2_commit_kv.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg), i32, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
+    lib.eagle2_commit_kv_fp8.restype = C.c_int
+    lib.eagle2_commit_kv_fp8.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg), i32, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp]
     lib.eagle2_commit_round.restype = C.c_int
     lib.eagle2_commit_round.argtypes = [C.POINTER(RoundCfg)] + [vp] * 9 + [vp]
     lib.eagle2_draft_workspace_bytes.restype = sz
@@ -176,6 +180,19 @@ def eagle2_tree_attn(cfg: RoundCfg, attn: AttnCfg, Q, K_prefix, V_prefix, kv_off
                                 _ptr(lse, torch.float32, "lse"), wp, wb, _stream(stream)))
 
 
+def eagle2_tree_attn_fp8kv(cfg: RoundCfg, attn: AttnCfg, Q, K_prefix8, V_prefix8, k_scale, v_scale, kv_offsets, K_tree, V_tree,
+                           mask_bits, O, lse, workspace, stream=None, prefix_len=None):
+    lib = load_library()
+    el, u8, f32 = _elem(cfg), torch.uint8, torch.float32
+    wp, wb = _ws(workspace)
+    _check(lib.eagle2_tree_attn_fp8kv(C.byref(cfg), C.byref(attn), _ptr(Q, el, "Q"), _ptr(K_prefix8, u8, "K_prefix8"),
+                                      _ptr(V_prefix8, u8, "V_prefix8"), _ptr(k_scale, f32, "k_scale"), _ptr(v_scale, f32, "v_scale"),
+                                      _ptr(kv_offsets, torch.int64, "kv_offsets"), _ptr(prefix_len, torch.int32, "prefix_len"),
+                                      _ptr(K_tree, el, "K_tree"), _ptr(V_tree, el, "V_tree"),
+                                      _ptr(mask_bits, torch.int64, "mask_bits"), _ptr(O, el, "O"),
+                                      _ptr(lse, torch.float32, "lse"), wp, wb, _stream(stream)))
+
+
 def eagle2_accept(cfg: RoundCfg, mode, target_logits, draft_logits, temperature, u_accept, u_bonus,
                   tree_token, tree_parent, tree_cand, accept_len, accept_path, bonus_token, workspace, stream=None):
     lib = load_library()
@@ -199,6 +216,19 @@ def eagle2_commit_kv(cfg: RoundCfg, attn: AttnCfg, n_layers: int, accept_len, ac
                                 _ptr(prefix_len, i32, "prefix_len"), _ptr(K_tree, el, "K_tree"), _ptr(V_tree, el, "V_tree"),
                                 tree_layer_stride, _ptr(K_cache, el, "K_cache"), _ptr(V_cache, el, "V_cache"),
                                 cache_layer_stride, _stream(stream)))
+
+
+def eagle2_commit_kv_fp8(cfg: RoundCfg, attn: AttnCfg, n_layers: int, accept_len, accept_path, kv_offsets, prefix_len,
+                         K_tree, V_tree, tree_layer_stride: int, K_cache8, V_cache8, cache_layer_stride: int,
+                         k_scale, v_scale, stream=None):
+    lib = load_library()
+    el, i32, u8, f32 = _elem(cfg), torch.int32, torch.uint8, torch.float32
+    _check(lib.eagle2_commit_kv_fp8(C.byref(cfg), C.byref(attn), n_layers, _ptr(accept_len, i32, "accept_len"),
+                                    _ptr(accept_path, i32, "accept_path"), _ptr(kv_offsets, torch.int64, "kv_offsets"),
+                                    _ptr(prefix_len, i32, "prefix_len"), _ptr(K_tree, el, "K_tree"), _ptr(V_tree, el, "V_tree"),
+                                    tree_layer_stride, _ptr(K_cache8, u8, "K_cache8"), _ptr(V_cache8, u8, "V_cache8"),
+                                    cache_layer_stride, _ptr(k_scale, f32, "k_scale"), _ptr(v_scale, f32, "v_scale"),
+                                    _stream(stream)))
 
 
 def eagle2_commit_round(cfg: RoundCfg, accept_len, accept_path, tree_token, bonus_token, target_hidden,

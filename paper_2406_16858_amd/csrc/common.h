@@ -44,9 +44,11 @@ int device_cu_count();
 int gemm_rows(bool bf16, const void* X, int64_t x_seq_bytes, int M, int F, const void* W, int N, int row_bytes,
               float* out, void* hp_ws, unsigned* done_count, int n_done, hipStream_t st);
 
-// tree attention restricted to the query rows q0 .. q0+nq-1 (same arguments as eagle2_tree_attn otherwise)
+// tree attention restricted to the query rows q0 .. q0+nq-1 (same arguments as eagle2_tree_attn otherwise;
+// k_scale/v_scale non-null: the prefix keys/values are 8-bit E4M3 codes with these per-KV-head scales)
 int tree_attn_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int q0, int nq,
-                   const void* Q, const void* K_prefix, const void* V_prefix, const int64_t* kv_offsets, const int32_t* kv_len,
+                   const void* Q, const void* K_prefix, const void* V_prefix, const float* k_scale, const float* v_scale,
+                   const int64_t* kv_offsets, const int32_t* kv_len,
                    const void* K_tree, const void* V_tree, const uint64_t* mask_bits, void* O, float* lse,
                    void* workspace, size_t workspace_bytes, void* stream);
 
@@ -60,6 +62,7 @@ void timing_end(int which, hipStream_t s);
 typedef float    floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4   __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2   __attribute__((ext_vector_type(2)));
+typedef float    float2v __attribute__((ext_vector_type(2)));
 typedef __bf16   bf16x8  __attribute__((ext_vector_type(8)));
 
 // ---- wave-wide reductions on the DPP data path -------------------------------------------

@@ -512,7 +512,7 @@ extern "C" int eagle2_draft_forward(const eagle2_cfg* cfg, const eagle2_draft_cf
     E2_HIP(hipGetLastError());
     // only this pass's rows are queries; all draft rows are keys (later rows are zero and masked)
     const int row_base = d == 0 ? 0 : 1 + (d - 1) * k;
-    rc = tree_attn_rows(&acfg, &ac, row_base, F, Q, K_prefix, V_prefix, kv_offsets, prefix_len, K_draft, V_draft, draft_mask, O,
+    rc = tree_attn_rows(&acfg, &ac, row_base, F, Q, K_prefix, V_prefix, nullptr, nullptr, kv_offsets, prefix_len, K_draft, V_draft, draft_mask, O,
                         nullptr, ws + L.attn, L.total - L.attn, stream);
     if (rc != EAGLE2_OK) return rc;
     // output projection reads this pass's rows of O: row (b, s) at O + (b*Rd + row_base + s) * Hq*dh

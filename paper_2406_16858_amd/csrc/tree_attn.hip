@@ -65,9 +65,26 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const uint8_t* p) {
     return __builtin_bit_cast(u32x2, r);
 }
 
-template <int DH, int RBW>
+// four E4M3 codes -> four bf16 (exact: three mantissa bits fit, the exponent range is inside bf16's)
+__device__ __forceinline__ u32x2 e4m3x4_to_bf16(unsigned w) {
+    const float2v a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+    return u32x2{__builtin_amdgcn_perm(__float_as_uint(a[1]), __float_as_uint(a[0]), 0x07060302u),   // upper halves of both floats
+                 __builtin_amdgcn_perm(__float_as_uint(b[1]), __float_as_uint(b[0]), 0x07060302u)};
+}
+// sixteen codes -> two 16-byte slots of bf16
+__device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& c, u32x4& s0, u32x4& s1) {
+    const u32x2 a = e4m3x4_to_bf16(c[0]), b = e4m3x4_to_bf16(c[1]), d = e4m3x4_to_bf16(c[2]), e = e4m3x4_to_bf16(c[3]);
+    s0 = u32x4{a[0], a[1], b[0], b[1]};
+    s1 = u32x4{d[0], d[1], e[0], e[1]};
+}
+
+// KV8: the prefix keys/values are 8-bit E4M3 codes with one scale per KV head (the tree's own keys and
+// values stay bf16).  Codes are widened to bf16 on their way into LDS; the key scale joins the softmax
+// scale, the value scale multiplies the chunk's partial output.
+template <int DH, int RBW, bool KV8>
 __global__ __launch_bounds__(TA_THREADS, 2)
-void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kp, const uint16_t* __restrict__ Vp,
+void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restrict__ Kp, const void* __restrict__ Vp,
+                           const float* __restrict__ k_scale, const float* __restrict__ v_scale,
                            const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len,
                            const uint16_t* __restrict__ Kt,
                            const uint16_t* __restrict__ Vt, const unsigned long long* __restrict__ mask_bits,
@@ -98,11 +115,13 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     const int m16 = lane & 15, g4 = lane >> 4;
     const bool is_tree = sc.c == sc.nc - 1;
     const int count = is_tree ? N : (int)min((long long)chunk, sc.P - (long long)sc.c * chunk);
-    const size_t kv_stride = (size_t)Hkv * DH;     // elements between consecutive keys
-    const uint16_t* kbase = is_tree ? Kt + ((size_t)sc.b * N * Hkv + kvh) * DH
-                                    : Kp + ((size_t)(sc.off + (long long)sc.c * chunk) * Hkv + kvh) * DH;
-    const uint16_t* vbase = is_tree ? Vt + ((size_t)sc.b * N * Hkv + kvh) * DH
-                                    : Vp + ((size_t)(sc.off + (long long)sc.c * chunk) * Hkv + kvh) * DH;
+    const bool codes = KV8 && !is_tree;            // this chunk's keys/values are 8-bit codes (uniform)
+    const size_t esz = codes ? 1 : 2;
+    const size_t kv_stride = (size_t)Hkv * DH * esz;   // bytes between consecutive keys
+    const size_t first_key = is_tree ? (size_t)sc.b * N : (size_t)(sc.off + (long long)sc.c * chunk);
+    const uint8_t* kbase = reinterpret_cast<const uint8_t*>(is_tree ? (const void*)Kt : Kp) + (first_key * Hkv + kvh) * DH * esz;
+    const uint8_t* vbase = reinterpret_cast<const uint8_t*>(is_tree ? (const void*)Vt : Vp) + (first_key * Hkv + kvh) * DH * esz;
+    if constexpr (KV8) { if (codes) scale_log2e *= k_scale[kvh]; }
 
     // query fragments: lane (m16, g4) holds, for its row, dh elements 32t + 8*g4 .. +7
     u32x4 qf[RBW][DH / 32];
@@ -143,13 +162,22 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     // per-thread source pointers of the next tile to fetch, advanced by one tile per fetch (no 64-bit
     // multiplies in the loop)
     // piece i of a thread is (TA_THREADS / SLOTS) keys after piece i-1: one pointer, uniform offsets
-    const uint16_t* kptr = kbase + (size_t)(tid / SLOTS) * kv_stride + (tid % SLOTS) * 8;
-    const size_t kpiece = (size_t)(TA_THREADS / SLOTS) * kv_stride;
-    const uint16_t* vptr = vbase + (size_t)(tid / SLOTS) * kv_stride + (tid % SLOTS) * 8;
+    // (a row of codes has half as many 16-byte pieces, and a thread takes half as many pieces per tile)
+    const int spr = codes ? SLOTS / 2 : SLOTS;         // 16-byte pieces per key row in memory
+    const uint8_t* kptr = kbase + (size_t)(tid / spr) * kv_stride + (tid % spr) * 16;
+    const size_t kpiece = (size_t)(TA_THREADS / spr) * kv_stride;
+    const uint8_t* vptr = vbase + (size_t)(tid / spr) * kv_stride + (tid % spr) * 16;
     const size_t tile_step = (size_t)TA_KEYS * kv_stride;
     auto fetch_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[NKP]) {
         const int key0 = tile * TA_KEYS;
-        if (key0 + TA_KEYS <= count) {                 // full tile (uniform): no bounds checks
+        if (KV8 && codes) {
+#pragma unroll
+            for (int i = 0; i < NKP / 2; ++i) {
+                const bool in = key0 + (tid + i * TA_THREADS) / (SLOTS / 2) < count;
+                kr[i] = in ? *reinterpret_cast<const u32x4*>(kptr + i * kpiece) : u32x4{0u, 0u, 0u, 0u};
+                vr[i] = in ? *reinterpret_cast<const u32x4*>(vptr + i * kpiece) : u32x4{0u, 0u, 0u, 0u};
+            }
+        } else if (key0 + TA_KEYS <= count) {          // full tile (uniform): no bounds checks
 #pragma unroll
             for (int i = 0; i < NKP; ++i) kr[i] = *reinterpret_cast<const u32x4*>(kptr + i * kpiece);
 #pragma unroll
@@ -169,17 +197,32 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     auto do_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[NKP]) {
         const int key0 = tile * TA_KEYS;
         __syncthreads();                           // previous tile fully consumed
-        // K tile -> LDS, row-major, 16-byte slots swizzled by the row
+        if (KV8 && codes) {
+            // a piece of 16 codes becomes the two 16-byte slots 2*c8 and 2*c8+1 of its row
 #pragma unroll
-        for (int i = 0; i < NKP; ++i) {
-            const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
-            *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + ((c ^ k_swz<DH>(key)) << 4)) = kr[i];
-        }
-        // V tile -> LDS, row-major as well (the PV operand is transposed by the LDS read itself)
+            for (int i = 0; i < NKP / 2; ++i) {
+                const int p = tid + i * TA_THREADS, key = p / (SLOTS / 2), c8 = p - key * (SLOTS / 2);
+                u32x4 k0, k1, v0, v1;
+                e4m3x16_to_bf16(kr[i], k0, k1);
+                e4m3x16_to_bf16(vr[i], v0, v1);
+                *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + (((2 * c8) ^ k_swz<DH>(key)) << 4)) = k0;
+                *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + (((2 * c8 + 1) ^ k_swz<DH>(key)) << 4)) = k1;
+                *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + ((c8 ^ v_swz<DH>(key)) << 5)) = v0;
+                *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + (((c8 ^ v_swz<DH>(key)) << 5) | 16)) = v1;
+            }
+        } else {
+            // K tile -> LDS, row-major, 16-byte slots swizzled by the row
 #pragma unroll
-        for (int i = 0; i < NKP; ++i) {
-            const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
-            *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + ((((c >> 1) ^ v_swz<DH>(key)) << 5) | ((c & 1) << 4))) = vr[i];
+            for (int i = 0; i < NKP; ++i) {
+                const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
+                *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + ((c ^ k_swz<DH>(key)) << 4)) = kr[i];
+            }
+            // V tile -> LDS, row-major as well (the PV operand is transposed by the LDS read itself)
+#pragma unroll
+            for (int i = 0; i < NKP; ++i) {
+                const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
+                *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + ((((c >> 1) ^ v_swz<DH>(key)) << 5) | ((c & 1) << 4))) = vr[i];
+            }
         }
         __syncthreads();
         if (tile + DEPTH < ntile) fetch_tile(tile + DEPTH, kr, vr);
@@ -295,6 +338,8 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
     }
 
     // partial results of this chunk: un-normalised O (lane holds dh db*16 + 4*g4 + i of its row), max, sum
+    float o_scale = 1.f;
+    if constexpr (KV8) { if (codes) o_scale = v_scale[kvh]; }
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
         float l = l_run[rb];
@@ -304,7 +349,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __res
             const size_t prow = ((size_t)flat * Hkv + kvh) * rows_pad + rho[rb];
 #pragma unroll
             for (int db = 0; db < DH / 16; ++db)
-                *reinterpret_cast<floatx4*>(part_o + prow * DH + db * 16 + g4 * 4) = acc[rb][db];
+                *reinterpret_cast<floatx4*>(part_o + prow * DH + db * 16 + g4 * 4) = KV8 ? acc[rb][db] * o_scale : acc[rb][db];
             if (g4 == 0) { part_ml[prow * 2] = m_run[rb]; part_ml[prow * 2 + 1] = l; }
         }
     }
@@ -470,7 +515,7 @@ size_t attn_workspace(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn) {
 // Attention of the tree rows q0 .. q0+nq-1 (queries) over the prefix and all N tree keys under the
 // mask; the public entry point asks for every row, the draft model's forward for the rows of one pass.
 int tree_attn_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int q0, int nq,
-                   const void* Q, const void* K_prefix, const void* V_prefix,
+                   const void* Q, const void* K_prefix, const void* V_prefix, const float* k_scale, const float* v_scale,
                    const int64_t* kv_offsets, const int32_t* kv_len,
                    const void* K_tree, const void* V_tree,
                    const uint64_t* mask_bits, void* O, float* lse,
@@ -483,6 +528,11 @@ int tree_attn_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int q0, i
     E2_REQUIRE(attn->total_prefix == 0 || (K_prefix && V_prefix), EAGLE2_ERR_ARG, "eagle2_tree_attn: null KV prefix");
     E2_REQUIRE(aligned16(Q) && aligned16(K_prefix) && aligned16(V_prefix) && aligned16(K_tree) && aligned16(V_tree) && aligned16(O),
                EAGLE2_ERR_ARG, "eagle2_tree_attn: tensors must be 16-byte aligned");
+    const bool kv8 = k_scale != nullptr || v_scale != nullptr;
+    if (kv8) {
+        E2_REQUIRE(k_scale && v_scale, EAGLE2_ERR_ARG, "tree attention: 8-bit prefix needs both k_scale and v_scale");
+        E2_REQUIRE(cfg->dtype == EAGLE2_DTYPE_BF16, EAGLE2_ERR_SHAPE, "tree attention: the 8-bit prefix goes with dtype bf16 only");
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int B = cfg->batch, N = cfg->n_tree, Hq = attn->n_q_heads, Hkv = attn->n_kv_heads, dh = attn->head_dim;
     E2_REQUIRE(q0 >= 0 && nq >= 1 && q0 + nq <= N, EAGLE2_ERR_ARG, "tree attention: query rows %d..%d outside the tree", q0, q0 + nq - 1);
@@ -515,12 +565,14 @@ int tree_attn_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int q0, i
     const float sl2 = scale * 1.4426950408889634f;
     dim3 grid(p.max_chunks, Hkv * p.nmblk);
     timing_begin(1, st);
-#define E2_ATTN(DHV, RB)                                                                                              \
-    hipLaunchKernelGGL((tree_attn_bf16_kernel<DHV, RB>), grid, dim3(TA_THREADS), 0, st, (const uint16_t*)Q,            \
-                       (const uint16_t*)K_prefix, (const uint16_t*)V_prefix, offs, kv_len, (const uint16_t*)K_tree,            \
+#define E2_ATTN(DHV, RB, K8)                                                                                          \
+    hipLaunchKernelGGL((tree_attn_bf16_kernel<DHV, RB, K8>), grid, dim3(TA_THREADS), 0, st, (const uint16_t*)Q,        \
+                       K_prefix, V_prefix, k_scale, v_scale, offs, kv_len, (const uint16_t*)K_tree,                   \
                        (const uint16_t*)V_tree, mb, B, N, q0, nq, Hq, Hkv, p.chunk, words, p.nmblk, p.rows_pad, sl2, part_o, part_ml)
-    if (dh == 128) { if (p.rbw == 2) E2_ATTN(128, 2); else E2_ATTN(128, 1); }
-    else           { if (p.rbw == 2) E2_ATTN(64, 2); else E2_ATTN(64, 1); }
+#define E2_ATTN_RB(DHV, K8) do { if (p.rbw == 2) E2_ATTN(DHV, 2, K8); else E2_ATTN(DHV, 1, K8); } while (0)
+    if (dh == 128) { if (kv8) E2_ATTN_RB(128, true); else E2_ATTN_RB(128, false); }
+    else           { if (kv8) E2_ATTN_RB(64, true); else E2_ATTN_RB(64, false); }
+#undef E2_ATTN_RB
 #undef E2_ATTN
     timing_end(1, st);
     E2_HIP(hipGetLastError());
@@ -546,6 +598,19 @@ extern "C" int eagle2_tree_attn(const eagle2_cfg* cfg, const eagle2_attn_cfg* at
                                 const uint64_t* mask_bits, void* O, float* lse,
                                 void* workspace, size_t workspace_bytes, void* stream) {
     E2_REQUIRE(cfg != nullptr, EAGLE2_ERR_ARG, "cfg is null");
-    return tree_attn_rows(cfg, attn, 0, cfg->n_tree, Q, K_prefix, V_prefix, kv_offsets, kv_len, K_tree, V_tree, mask_bits, O, lse,
-                          workspace, workspace_bytes, stream);
+    return tree_attn_rows(cfg, attn, 0, cfg->n_tree, Q, K_prefix, V_prefix, nullptr, nullptr, kv_offsets, kv_len, K_tree, V_tree,
+                          mask_bits, O, lse, workspace, workspace_bytes, stream);
+}
+
+extern "C" int eagle2_tree_attn_fp8kv(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn,
+                                      const void* Q, const void* K_prefix8, const void* V_prefix8,
+                                      const float* k_scale, const float* v_scale,
+                                      const int64_t* kv_offsets, const int32_t* kv_len,
+                                      const void* K_tree, const void* V_tree,
+                                      const uint64_t* mask_bits, void* O, float* lse,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    E2_REQUIRE(cfg != nullptr, EAGLE2_ERR_ARG, "cfg is null");
+    E2_REQUIRE(k_scale && v_scale, EAGLE2_ERR_ARG, "eagle2_tree_attn_fp8kv: null scale pointer");
+    return tree_attn_rows(cfg, attn, 0, cfg->n_tree, Q, K_prefix8, V_prefix8, k_scale, v_scale, kv_offsets, kv_len, K_tree, V_tree,
+                          mask_bits, O, lse, workspace, workspace_bytes, stream);
 }

@@ -79,6 +79,11 @@ class DraftRound:
         _b.eagle2_tree_attn(self.cfg, self.attn, Q, K_prefix, V_prefix, kv_offsets, K_tree, V_tree, self.mask_bits,
                             O, lse, self.workspace, prefix_len=prefix_len)
 
+    def tree_attn_fp8kv(self, Q, K_prefix8, V_prefix8, k_scale, v_scale, kv_offsets, K_tree, V_tree, O, lse=None, prefix_len=None):
+        """Same with the prefix keys/values stored as 8-bit E4M3 codes (uint8) and one float scale per KV head."""
+        _b.eagle2_tree_attn_fp8kv(self.cfg, self.attn, Q, K_prefix8, V_prefix8, k_scale, v_scale, kv_offsets, K_tree, V_tree,
+                                  self.mask_bits, O, lse, self.workspace, prefix_len=prefix_len)
+
     # -- Sections 2.1 / 2.2 -----------------------------------------------------------
     def accept(self, mode, target_logits, temperature=None, u_accept=None, u_bonus=None):
         _b.eagle2_accept(self.cfg, mode, target_logits, self.draft_logits, temperature, u_accept, u_bonus,
@@ -90,6 +95,12 @@ class DraftRound:
                   tree_layer_stride: int = 0, cache_layer_stride: int = 0):
         _b.eagle2_commit_kv(self.cfg, self.attn, n_layers, self.accept_len, self.accept_path, kv_offsets, prefix_len,
                             K_tree, V_tree, tree_layer_stride, K_cache, V_cache, cache_layer_stride)
+
+    def commit_kv_fp8(self, kv_offsets, prefix_len, K_tree, V_tree, K_cache8, V_cache8, k_scale, v_scale, n_layers: int = 1,
+                      tree_layer_stride: int = 0, cache_layer_stride: int = 0):
+        """commit_kv into a cache of 8-bit codes; k_scale/v_scale are [n_layers, Hkv] float32."""
+        _b.eagle2_commit_kv_fp8(self.cfg, self.attn, n_layers, self.accept_len, self.accept_path, kv_offsets, prefix_len,
+                                K_tree, V_tree, tree_layer_stride, K_cache8, V_cache8, cache_layer_stride, k_scale, v_scale)
 
     def commit_round(self, out_tokens, root_token, prefix_len, target_hidden=None, next_hidden=None):
         _b.eagle2_commit_round(self.cfg, self.accept_len, self.accept_path, self.tree_token, self.bonus_token,

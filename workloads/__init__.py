@@ -8,6 +8,7 @@ from .configs import CONFIGS, DRAFT_LAYERS, DraftLayerConfig, RoundConfig, get_c
 from .generate import (  # noqa: F401
     SeededStream,
     make_attention_inputs,
+    make_fp8_prefix,
     make_draft_weights,
     make_hidden_states,
     make_lm_head,

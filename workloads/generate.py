@@ -95,6 +95,23 @@ def make_attention_inputs(cfg: RoundConfig, device="cpu", layer: int = 0,
     return q, kp, vp, kt, vt, off.to(device)
 
 
+def make_fp8_prefix(kp: torch.Tensor, vp: torch.Tensor):
+    """8-bit image of a prefix K/V pair [T, Hkv, dh] for the quantised-cache variant: per-KV-head scales
+    max|x| / 448 (the whole E4M3 range is used; 1 for an empty or all-zero head) and the codes PyTorch's own
+    float8_e4m3fn conversion gives for x / scale.  Returns (K codes, V codes) uint8 and (k_scale, v_scale)
+    float32 [Hkv], on the tensors' device."""
+    def one(x):
+        xf = x.detach().to("cpu", torch.float32)
+        amax = xf.abs().amax(dim=(0, 2)) if xf.shape[0] else torch.zeros(xf.shape[1])
+        scale = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax)).to(torch.float32)
+        q = (xf / scale[None, :, None]).clamp(-448.0, 448.0)
+        codes = q.to(torch.float8_e4m3fn).view(torch.uint8)
+        return codes.to(x.device), scale.to(x.device)
+    k8, ks = one(kp)
+    v8, vs = one(vp)
+    return k8, v8, ks, vs
+
+
 def make_target_logits(cfg: RoundConfig, device="cpu", std: float = 3.0,
                        spike: float = 8.0) -> Tuple[torch.Tensor, torch.Tensor]:
     """Target logits [B,N,V] fp32 ~ N(0, std) with `spike` added at one seeded
