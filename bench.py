@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-draft-model", action="store_true",
                     help="also run the draft model's decoder layer before every LM-head pass (not the headline metric)")
+    ap.add_argument("--fp8-kv", action="store_true",
+                    help="keep the prefix KV cache as 8-bit E4M3 codes (eagle2_tree_attn_fp8kv; a variant, not the headline metric)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -84,6 +86,14 @@ def main():
                      total_prefix=sum(plens), keep_draft_logits=any(modes_l), device=dev)
     layers = [wl.make_attention_inputs(cfg, dev, layer=l, prefix_lens=plens) for l in range(cfg.n_layers)]
     O = torch.empty_like(layers[0][0])
+    if args.fp8_kv:
+        if cfg.dtype != "bf16":
+            sys.exit("bench.py: --fp8-kv needs a bf16 configuration")
+        layers8 = []
+        for (Q, Kp, Vp, Kt, Vt, off) in layers:
+            K8, V8, ks, vs = wl.make_fp8_prefix(Kp, Vp)
+            layers8.append((Q, K8, V8, ks, vs, Kt, Vt, off))
+        del layers
     tl, _ = wl.make_target_logits(cfg, dev)
     ua, ub = wl.make_uniforms(cfg, dev)
     temp = torch.full((B,), cfg.temperature, dtype=torch.float32, device=dev)
@@ -112,8 +122,12 @@ def main():
                 dm.forward(d, root, root_feat, plen_t, dKp, dVp, doff)
                 dm.expand(d, W)
         rnd.rerank(root, plen_t)
-        for (Q, Kp, Vp, Kt, Vt, off) in layers:
-            rnd.tree_attn(Q, Kp, Vp, off, Kt, Vt, O, None)
+        if args.fp8_kv:
+            for (Q, K8, V8, ks, vs, Kt, Vt, off) in layers8:
+                rnd.tree_attn_fp8kv(Q, K8, V8, ks, vs, off, Kt, Vt, O, None)
+        else:
+            for (Q, Kp, Vp, Kt, Vt, off) in layers:
+                rnd.tree_attn(Q, Kp, Vp, off, Kt, Vt, O, None)
         rnd.accept(mode_t, tl, temp, ua, ub)
 
     for _ in range(args.warmup):
@@ -137,6 +151,8 @@ def main():
     at_ms, at_n = eagle2_kernel_timing_read(1)
     eagle2_kernel_timing_enable(False)
     lm_bytes, attn_bytes = algorithmic_bytes(cfg, plens)
+    if args.fp8_kv:                                    # the prefix rows are one byte per element
+        attn_bytes -= sum(2 * P * cfg.n_kv_heads * cfg.head_dim for P in plens)
     lm_avg_ms = lm_ms / max(lm_n, 1)
     achieved = lm_bytes / (lm_avg_ms * 1e-3) / 1e9
     round_bytes = D * lm_bytes + cfg.n_layers * attn_bytes
@@ -150,7 +166,7 @@ def main():
 
     # ---- the oracle on the host cores, same round, bounded sample ------------------
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.fp8_kv:
         import numpy as np
         from oracle import eagle2_oracle as orc
         from tests.parity_utils import f64
@@ -189,6 +205,8 @@ def main():
     name = "draft_tree_rounds_per_sec_llama3_8b_shape" if cfg.index == 3 else f"draft_tree_rounds_per_sec_{cfg.name}"
     if dm is not None:
         name += "_with_draft_model"
+    if args.fp8_kv:
+        name += "_fp8_prefix_kv"
     out = {"metric": name,
            "value": round(rounds_per_s, 2), "unit": "rounds/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,

@@ -154,79 +154,91 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         for (int db = 0; db < DH / 16; ++db) acc[rb][db] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // The next tile's K and V are fetched into registers while the current tile is multiplied.
-    constexpr int NKP = TA_KEYS * SLOTS / TA_THREADS;          // 16-byte K pieces per thread per tile
-    // Two register sets, used alternately: tiles t+1 and t+2 are in flight while tile t is multiplied.
-    constexpr int DEPTH = RBW == 1 ? 2 : 1;            // the wide variant has registers for one set only
-    u32x4 krA[NKP], vrA[NKP], krB[NKP], vrB[NKP];
+    // The next tiles' K and V are fetched into registers while the current tile is multiplied.
+    constexpr int NKP = TA_KEYS * SLOTS / TA_THREADS;          // 16-byte pieces of a bf16 K tile per thread
+    // Two register sets.  bf16 kernels: a set holds a whole tile; the narrow variant uses both alternately
+    // (tiles t+1 and t+2 in flight while tile t is multiplied), the wide one has registers for one.  8-bit
+    // kernels: a set is half as large, which is a whole tile of codes (two tiles in flight in both variants);
+    // their bf16 tree chunk spreads each tile over both sets.
+    constexpr int NH = KV8 ? NKP / 2 : NKP;            // pieces per register set
+    constexpr int DEPTH = RBW == 1 ? 2 : 1;            // bf16 kernels: tiles in flight
+    u32x4 krA[NH], vrA[NH], krB[NH], vrB[NH];
     // per-thread source pointers of the next tile to fetch, advanced by one tile per fetch (no 64-bit
-    // multiplies in the loop)
-    // piece i of a thread is (TA_THREADS / SLOTS) keys after piece i-1: one pointer, uniform offsets
-    // (a row of codes has half as many 16-byte pieces, and a thread takes half as many pieces per tile)
+    // multiplies in the loop); piece i of a thread is (TA_THREADS / spr) keys after piece i-1
     const int spr = codes ? SLOTS / 2 : SLOTS;         // 16-byte pieces per key row in memory
     const uint8_t* kptr = kbase + (size_t)(tid / spr) * kv_stride + (tid % spr) * 16;
     const size_t kpiece = (size_t)(TA_THREADS / spr) * kv_stride;
     const uint8_t* vptr = vbase + (size_t)(tid / spr) * kv_stride + (tid % spr) * 16;
     const size_t tile_step = (size_t)TA_KEYS * kv_stride;
-    auto fetch_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[NKP]) {
+    auto advance = [&]() { kptr += tile_step; vptr += tile_step; };
+    // pieces I0 .. I0+NH-1 of a bf16 tile
+    auto fetch_bf16 = [&](int tile, auto i0c, u32x4 (&kr)[NH], u32x4 (&vr)[NH]) {
+        constexpr int I0 = decltype(i0c)::value;
         const int key0 = tile * TA_KEYS;
-        if (KV8 && codes) {
+        if (key0 + TA_KEYS <= count) {                 // full tile (uniform): no bounds checks
+#pragma unroll
+            for (int i = 0; i < NH; ++i) kr[i] = *reinterpret_cast<const u32x4*>(kptr + (I0 + i) * kpiece);
+#pragma unroll
+            for (int i = 0; i < NH; ++i) vr[i] = *reinterpret_cast<const u32x4*>(vptr + (I0 + i) * kpiece);
+        } else {
+#pragma unroll
+            for (int i = 0; i < NH; ++i) {
+                const bool in = key0 + (tid + (I0 + i) * TA_THREADS) / SLOTS < count;
+                kr[i] = in ? *reinterpret_cast<const u32x4*>(kptr + (I0 + i) * kpiece) : u32x4{0u, 0u, 0u, 0u};
+                vr[i] = in ? *reinterpret_cast<const u32x4*>(vptr + (I0 + i) * kpiece) : u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+    };
+    auto stage_bf16 = [&](auto i0c, const u32x4 (&kr)[NH], const u32x4 (&vr)[NH]) {
+        constexpr int I0 = decltype(i0c)::value;
+        // K tile -> LDS, row-major, 16-byte slots swizzled by the row
+#pragma unroll
+        for (int i = 0; i < NH; ++i) {
+            const int p = tid + (I0 + i) * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
+            *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + ((c ^ k_swz<DH>(key)) << 4)) = kr[i];
+        }
+        // V tile -> LDS, row-major as well (the PV operand is transposed by the LDS read itself)
+#pragma unroll
+        for (int i = 0; i < NH; ++i) {
+            const int p = tid + (I0 + i) * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
+            *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + ((((c >> 1) ^ v_swz<DH>(key)) << 5) | ((c & 1) << 4))) = vr[i];
+        }
+    };
+    // a tile of codes: NKP / 2 pieces of 16 codes per thread
+    auto fetch_codes = [&](int tile, u32x4 (&kr)[NH], u32x4 (&vr)[NH]) {
+        const int key0 = tile * TA_KEYS;
+        if (key0 + TA_KEYS <= count) {
+#pragma unroll
+            for (int i = 0; i < NKP / 2; ++i) kr[i] = *reinterpret_cast<const u32x4*>(kptr + i * kpiece);
+#pragma unroll
+            for (int i = 0; i < NKP / 2; ++i) vr[i] = *reinterpret_cast<const u32x4*>(vptr + i * kpiece);
+        } else {
 #pragma unroll
             for (int i = 0; i < NKP / 2; ++i) {
                 const bool in = key0 + (tid + i * TA_THREADS) / (SLOTS / 2) < count;
                 kr[i] = in ? *reinterpret_cast<const u32x4*>(kptr + i * kpiece) : u32x4{0u, 0u, 0u, 0u};
                 vr[i] = in ? *reinterpret_cast<const u32x4*>(vptr + i * kpiece) : u32x4{0u, 0u, 0u, 0u};
             }
-        } else if (key0 + TA_KEYS <= count) {          // full tile (uniform): no bounds checks
-#pragma unroll
-            for (int i = 0; i < NKP; ++i) kr[i] = *reinterpret_cast<const u32x4*>(kptr + i * kpiece);
-#pragma unroll
-            for (int i = 0; i < NKP; ++i) vr[i] = *reinterpret_cast<const u32x4*>(vptr + i * kpiece);
-        } else {
-#pragma unroll
-            for (int i = 0; i < NKP; ++i) {
-                const bool in = key0 + (tid + i * TA_THREADS) / SLOTS < count;
-                kr[i] = in ? *reinterpret_cast<const u32x4*>(kptr + i * kpiece) : u32x4{0u, 0u, 0u, 0u};
-                vr[i] = in ? *reinterpret_cast<const u32x4*>(vptr + i * kpiece) : u32x4{0u, 0u, 0u, 0u};
-            }
         }
-        kptr += tile_step;
-        vptr += tile_step;
+    };
+    // a piece of 16 codes becomes the two 16-byte slots 2*c8 and 2*c8+1 of its row
+    auto stage_codes = [&](const u32x4 (&kr)[NH], const u32x4 (&vr)[NH]) {
+#pragma unroll
+        for (int i = 0; i < NKP / 2; ++i) {
+            const int p = tid + i * TA_THREADS, key = p / (SLOTS / 2), c8 = p - key * (SLOTS / 2);
+            u32x4 k0, k1, v0, v1;
+            e4m3x16_to_bf16(kr[i], k0, k1);
+            e4m3x16_to_bf16(vr[i], v0, v1);
+            *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + (((2 * c8) ^ k_swz<DH>(key)) << 4)) = k0;
+            *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + (((2 * c8 + 1) ^ k_swz<DH>(key)) << 4)) = k1;
+            *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + ((c8 ^ v_swz<DH>(key)) << 5)) = v0;
+            *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + (((c8 ^ v_swz<DH>(key)) << 5) | 16)) = v1;
+        }
     };
     const int ntile = (count + TA_KEYS - 1) / TA_KEYS;
-    auto do_tile = [&](int tile, u32x4 (&kr)[NKP], u32x4 (&vr)[NKP]) {
+    // the tile staged in LDS (keys tile*64 ..) against the query fragments
+    auto compute = [&](int tile) {
         const int key0 = tile * TA_KEYS;
-        __syncthreads();                           // previous tile fully consumed
-        if (KV8 && codes) {
-            // a piece of 16 codes becomes the two 16-byte slots 2*c8 and 2*c8+1 of its row
-#pragma unroll
-            for (int i = 0; i < NKP / 2; ++i) {
-                const int p = tid + i * TA_THREADS, key = p / (SLOTS / 2), c8 = p - key * (SLOTS / 2);
-                u32x4 k0, k1, v0, v1;
-                e4m3x16_to_bf16(kr[i], k0, k1);
-                e4m3x16_to_bf16(vr[i], v0, v1);
-                *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + (((2 * c8) ^ k_swz<DH>(key)) << 4)) = k0;
-                *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + (((2 * c8 + 1) ^ k_swz<DH>(key)) << 4)) = k1;
-                *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + ((c8 ^ v_swz<DH>(key)) << 5)) = v0;
-                *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + (((c8 ^ v_swz<DH>(key)) << 5) | 16)) = v1;
-            }
-        } else {
-            // K tile -> LDS, row-major, 16-byte slots swizzled by the row
-#pragma unroll
-            for (int i = 0; i < NKP; ++i) {
-                const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
-                *reinterpret_cast<u32x4*>(s_k + key * (DH * 2) + ((c ^ k_swz<DH>(key)) << 4)) = kr[i];
-            }
-            // V tile -> LDS, row-major as well (the PV operand is transposed by the LDS read itself)
-#pragma unroll
-            for (int i = 0; i < NKP; ++i) {
-                const int p = tid + i * TA_THREADS, key = p / SLOTS, c = p - key * SLOTS;
-                *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + ((((c >> 1) ^ v_swz<DH>(key)) << 5) | ((c & 1) << 4))) = vr[i];
-            }
-        }
-        __syncthreads();
-        if (tile + DEPTH < ntile) fetch_tile(tile + DEPTH, kr, vr);
-
         constexpr int KBH = TA_KEYS / 16, hh = 0;      // 16-key blocks of the tile
         // S^T = K Q^T : s[rb][kq][i] = score(query row of this lane, key kb*16 + 4*g4 + i), kb = hh*KBH + kq
         floatx4 s[RBW][KBH];
@@ -326,15 +338,59 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
             }
         }
     };
-    if (ntile > 0) fetch_tile(0, krA, vrA);
-    if constexpr (DEPTH == 2) {
-        if (ntile > 1) fetch_tile(1, krB, vrB);
-        for (int tile = 0; tile < ntile; tile += 2) {
-            do_tile(tile, krA, vrA);
-            if (tile + 1 < ntile) do_tile(tile + 1, krB, vrB);
+    using std::integral_constant;
+    if (KV8 && codes) {
+        if constexpr (KV8) {
+            if (ntile > 0) { fetch_codes(0, krA, vrA); advance(); }
+            if (ntile > 1) { fetch_codes(1, krB, vrB); advance(); }
+            for (int tile = 0; tile < ntile; tile += 2) {
+                __syncthreads();                       // previous tile fully consumed
+                stage_codes(krA, vrA);
+                __syncthreads();
+                if (tile + 2 < ntile) { fetch_codes(tile + 2, krA, vrA); advance(); }
+                compute(tile);
+                if (tile + 1 < ntile) {
+                    __syncthreads();
+                    stage_codes(krB, vrB);
+                    __syncthreads();
+                    if (tile + 3 < ntile) { fetch_codes(tile + 3, krB, vrB); advance(); }
+                    compute(tile + 1);
+                }
+            }
+        }
+    } else if constexpr (KV8) {                        // bf16 tree chunk of an 8-bit kernel: one tile across both sets
+        if (ntile > 0) { fetch_bf16(0, integral_constant<int, 0>{}, krA, vrA); fetch_bf16(0, integral_constant<int, NH>{}, krB, vrB); advance(); }
+        for (int tile = 0; tile < ntile; ++tile) {
+            __syncthreads();
+            stage_bf16(integral_constant<int, 0>{}, krA, vrA);
+            stage_bf16(integral_constant<int, NH>{}, krB, vrB);
+            __syncthreads();
+            if (tile + 1 < ntile) {
+                fetch_bf16(tile + 1, integral_constant<int, 0>{}, krA, vrA);
+                fetch_bf16(tile + 1, integral_constant<int, NH>{}, krB, vrB);
+                advance();
+            }
+            compute(tile);
         }
     } else {
-        for (int tile = 0; tile < ntile; ++tile) do_tile(tile, krA, vrA);
+        constexpr integral_constant<int, 0> z{};
+        auto do_tile = [&](int tile, u32x4 (&kr)[NH], u32x4 (&vr)[NH]) {
+            __syncthreads();                           // previous tile fully consumed
+            stage_bf16(z, kr, vr);
+            __syncthreads();
+            if (tile + DEPTH < ntile) { fetch_bf16(tile + DEPTH, z, kr, vr); advance(); }
+            compute(tile);
+        };
+        if (ntile > 0) { fetch_bf16(0, z, krA, vrA); advance(); }
+        if constexpr (DEPTH == 2) {
+            if (ntile > 1) { fetch_bf16(1, z, krB, vrB); advance(); }
+            for (int tile = 0; tile < ntile; tile += 2) {
+                do_tile(tile, krA, vrA);
+                if (tile + 1 < ntile) do_tile(tile + 1, krB, vrB);
+            }
+        } else {
+            for (int tile = 0; tile < ntile; ++tile) do_tile(tile, krA, vrA);
+        }
     }
 
     // partial results of this chunk: un-normalised O (lane holds dh db*16 + 4*g4 + i of its row), max, sum
