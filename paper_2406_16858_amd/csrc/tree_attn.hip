@@ -65,6 +65,16 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const uint8_t* p) {
     return __builtin_bit_cast(u32x2, r);
 }
 
+// Maximum over the four lanes m16, m16+16, m16+32, m16+48 (the lanes that share a query row), left in
+// all four: gfx950's row and half-wave swaps stay on the vector ALU, where a shuffle goes through the
+// LDS crossbar.  permlane16_swap(x, x) returns (rows 0,0,2,2 ; rows 1,1,3,3) of x, permlane32_swap(x, x)
+// (lower half twice ; upper half twice).
+__device__ __forceinline__ float max_over_lane_groups(float x) {
+    u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 // four E4M3 codes -> four bf16 (exact: three mantissa bits fit, the exponent range is inside bf16's)
 __device__ __forceinline__ u32x2 e4m3x4_to_bf16(unsigned w) {
     const float2v a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
@@ -295,8 +305,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                     }
                 }
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mx = max_over_lane_groups(mx);
             // scores stay raw: the (positive) scale and the running maximum go into one fma per element;
             // the arguments of exp2 are <= 0, so the bare v_exp_f32 (tiny results flush to 0) is enough
             const float m_new = fmaxf(m_run[rb], mx * scale_log2e);
