@@ -137,6 +137,8 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     u32x4 qf[RBW][DH / 32];
     const unsigned long long* mptr[RBW];          // the row's ancestor bits (tree chunk only; read per tile, not held)
     int rho[RBW];
+    // (called after the first K/V tiles have been requested, so that the two latencies overlap)
+    auto load_queries = [&]() {
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
         rho[rb] = mblk * BM + (w * RBW + rb) * 16 + m16;
@@ -153,6 +155,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                 *reinterpret_cast<u32x4*>(s_q + ((w * RBW + rb) * 16 + m16) * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>((w * RBW + rb) * 16 + m16)) << 4)) = qf[rb][t];
         }
     }
+    };
 
     floatx4 acc[RBW][DH / 16];
     float m_run[RBW], l_run[RBW];
@@ -352,6 +355,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         if constexpr (KV8) {
             if (ntile > 0) { fetch_codes(0, krA, vrA); advance(); }
             if (ntile > 1) { fetch_codes(1, krB, vrB); advance(); }
+            load_queries();
             for (int tile = 0; tile < ntile; tile += 2) {
                 __syncthreads();                       // previous tile fully consumed
                 stage_codes(krA, vrA);
@@ -369,6 +373,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         }
     } else if constexpr (KV8) {                        // bf16 tree chunk of an 8-bit kernel: one tile across both sets
         if (ntile > 0) { fetch_bf16(0, integral_constant<int, 0>{}, krA, vrA); fetch_bf16(0, integral_constant<int, NH>{}, krB, vrB); advance(); }
+        load_queries();
         for (int tile = 0; tile < ntile; ++tile) {
             __syncthreads();
             stage_bf16(integral_constant<int, 0>{}, krA, vrA);
@@ -393,11 +398,13 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         if (ntile > 0) { fetch_bf16(0, z, krA, vrA); advance(); }
         if constexpr (DEPTH == 2) {
             if (ntile > 1) { fetch_bf16(1, z, krB, vrB); advance(); }
+            load_queries();
             for (int tile = 0; tile < ntile; tile += 2) {
                 do_tile(tile, krA, vrA);
                 if (tile + 1 < ntile) do_tile(tile + 1, krB, vrB);
             }
         } else {
+            load_queries();
             for (int tile = 0; tile < ntile; ++tile) do_tile(tile, krA, vrA);
         }
     }
