@@ -12,6 +12,7 @@
 // second (the contraction index of an MFMA may be permuted freely as long as A and B
 // agree), so P never goes through LDS.  The ancestor bitmask is applied to the tree
 // chunk only.  A second kernel combines the chunks' (max, sum, O) triples.
+// The prefix keys/values may also be 8-bit E4M3 codes with per-head scales (KV8 instantiations).
 //
 // fp32 path: a plain one-query-row-per-workgroup kernel in float32 (small shapes only).
 
@@ -100,9 +101,10 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                            const uint16_t* __restrict__ Vt, const unsigned long long* __restrict__ mask_bits,
                            int B, int N, int q0, int nq, int Hq, int Hkv, int chunk, int words, int nmblk, int rows_pad,
                            float scale_log2e, float* __restrict__ part_o, float* __restrict__ part_ml) {
-    // 16-row query blocks per wave.  Two blocks per wave (each K/V fragment feeding two MFMAs) were
-    // measured too: they need more registers than two resident waves per SIMD leave, and with the
-    // prefetch sacrificed for them they were no faster at the 640-rows-per-head shape.
+    // RBW 16-row query blocks per wave.  One block (narrow): query fragments in registers, two tiles
+    // of K/V in flight.  Two blocks (wide; every K/V fragment feeds two MFMAs and a tile is staged
+    // once per 128 rows): to fit two resident waves per SIMD the query fragments are parked in LDS
+    // and one tile is in flight; pays when a KV head has more than 256 query rows.
     constexpr int SLOTS = DH / 8;                  // 16-byte slots per K row
     constexpr int BM = 64 * RBW;                   // query rows per workgroup
     __shared__ __align__(16) uint8_t s_k[TA_KEYS * DH * 2];
