@@ -204,3 +204,26 @@ def test_binding_refuses_host_tensors():
     t = torch.zeros(4)
     with pytest.raises(b.Eagle2Error):
         b.eagle2_expand(cfg, 0, t, t, t, t, t, t, None, None)
+
+
+def test_fp8_prefix_generator_uses_the_whole_code_range_and_stays_close():
+    """workloads.make_fp8_prefix: per-head scales map the head's largest magnitude to 448, codes hold
+    no NaN, and value(code) * scale is within half a code step of the tensor it came from."""
+    import torch
+    import workloads as wl
+    from oracle import fp8_kv_oracle as f8
+    g = torch.Generator().manual_seed(3)
+    kp = torch.randn((70, 3, 64), generator=g).to(torch.bfloat16)
+    vp = (torch.randn((70, 3, 64), generator=g) * torch.tensor([0.1, 1.0, 30.0])[None, :, None]).to(torch.bfloat16)
+    k8, v8, ks, vs = wl.make_fp8_prefix(kp, vp)
+    assert k8.dtype == torch.uint8 and k8.shape == kp.shape and ks.shape == (3,) and ks.dtype == torch.float32
+    for x, c, s in ((kp, k8, ks), (vp, v8, vs)):
+        codes, scale = c.numpy(), s.numpy()
+        assert not np.any((codes & 0x7f) == 0x7f)
+        back = f8.dequantize(codes, scale)
+        ref = x.to(torch.float64).numpy()
+        assert np.all(np.abs(back - ref) <= np.maximum(np.abs(ref) * 2.0 ** -4, scale[None, :, None] * 2.0 ** -10) * 1.001)
+        assert np.allclose(np.abs(back).max(axis=(0, 2)), np.abs(ref).max(axis=(0, 2)), rtol=2.0 ** -4)
+    empty = torch.zeros((0, 3, 64), dtype=torch.bfloat16)
+    e8, _, es, _ = wl.make_fp8_prefix(empty, empty)
+    assert e8.shape == (0, 3, 64) and torch.all(es == 1.0)
