@@ -160,11 +160,15 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     };
 
     floatx4 acc[RBW][DH / 16];
-    float m_run[RBW], l_run[RBW];
+    floatx4 accl[RBW];                            // element 0 of lanes g4 == 0: the row's running sum of P
+    float m_run[RBW];
+    // A operand whose row 0 is all ones (bf16 1.0 = 0x3f80) and whose other rows are zero
+    const unsigned one2 = m16 == 0 ? 0x3f803f80u : 0u;
+    const u32x4 ones_row = {one2, one2, one2, one2};
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
         m_run[rb] = NEG_BIG;
-        l_run[rb] = 0.f;
+        accl[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int db = 0; db < DH / 16; ++db) acc[rb][db] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
@@ -283,6 +287,29 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         }
 
         bf16x8 pf[RBW][KBH / 2];
+        // from the block's score maximum to its probabilities (called from both branches below, so that
+        // neither has to move the scores into the other's registers)
+        auto finish_block = [&](int rb, float mx, const floatx4 (&sv)[KBH]) {
+            mx = max_over_lane_groups(mx);
+            // scores stay raw: the (positive) scale and the running maximum go into one fma per element;
+            // the arguments of exp2 are <= 0, so the bare v_exp_f32 (tiny results flush to 0) is enough
+            const float m_new = fmaxf(m_run[rb], mx * scale_log2e);
+            const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);
+            m_run[rb] = m_new;
+#pragma unroll
+            for (int kq = 0; kq < KBH; ++kq) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[kq][i], scale_log2e, -m_new));
+                    pf[rb][kq >> 1][(kq & 1) * 4 + i] = (__bf16)p;
+                }
+            }
+            if (__any(alpha != 1.f)) {                 // the running maximum rarely moves after the first tiles
+#pragma unroll
+                for (int db = 0; db < DH / 16; ++db) acc[rb][db] *= alpha;
+                accl[rb] *= alpha;
+            }
+        };
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb) {
             float mx = NEG_BIG;
@@ -294,9 +321,11 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                         mx = fmaxf(mx, s[rb][kq][i]);
                     }
                 }
+                finish_block(rb, mx, s[rb]);
             } else {
                 // a 64-key tile lies inside one 64-bit word of the row's mask
                 const unsigned long long mword = (is_tree && mptr[rb] != nullptr && (key0 >> 6) < words) ? mptr[rb][key0 >> 6] : 0ull;
+                floatx4 sm[KBH];
 #pragma unroll
                 for (int kq = 0; kq < KBH; ++kq) {
 #pragma unroll
@@ -305,31 +334,11 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                         bool vis = key < count;
                         if (is_tree) vis = vis && ((mword >> (key & 63)) & 1ull);
                         const float v = vis ? s[rb][kq][i] : -INFINITY;
-                        s[rb][kq][i] = v;
+                        sm[kq][i] = v;
                         mx = fmaxf(mx, v);
                     }
                 }
-            }
-            mx = max_over_lane_groups(mx);
-            // scores stay raw: the (positive) scale and the running maximum go into one fma per element;
-            // the arguments of exp2 are <= 0, so the bare v_exp_f32 (tiny results flush to 0) is enough
-            const float m_new = fmaxf(m_run[rb], mx * scale_log2e);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);
-            m_run[rb] = m_new;
-            float psum = 0.f;
-#pragma unroll
-            for (int kq = 0; kq < KBH; ++kq) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rb][kq][i], scale_log2e, -m_new));
-                    psum += p;
-                    pf[rb][kq >> 1][(kq & 1) * 4 + i] = (__bf16)p;
-                }
-            }
-            l_run[rb] = l_run[rb] * alpha + psum;
-            if (__any(alpha != 1.f)) {                 // the running maximum rarely moves after the first tiles
-#pragma unroll
-                for (int db = 0; db < DH / 16; ++db) acc[rb][db] *= alpha;
+                finish_block(rb, mx, sm);
             }
         }
 
@@ -351,6 +360,13 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                         __builtin_bit_cast(bf16x8, vf), pf[rb][uq], acc[rb][db], 0, 0, 0);
             }
         }
+        // the row sums of P come out of the same product with a row of ones in place of a V^T row: the
+        // normaliser is the sum of exactly the rounded probabilities the numerator used
+#pragma unroll
+        for (int uq = 0; uq < KBH / 2; ++uq)
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb)
+                accl[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones_row), pf[rb][uq], accl[rb], 0, 0, 0);
     };
     using std::integral_constant;
     if (KV8 && codes) {
@@ -416,9 +432,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     if constexpr (KV8) { if (codes) o_scale = v_scale[kvh]; }
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
-        float l = l_run[rb];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
+        const float l = accl[rb][0];                // valid in the lanes that write it (g4 == 0)
         if (rho[rb] < rows) {
             const size_t prow = ((size_t)flat * Hkv + kvh) * rows_pad + rho[rb];
 #pragma unroll
