@@ -67,16 +67,21 @@ def test_every_code_decodes_exactly():
     assert np.array_equal(got, f8.e4m3_decode(codes[:, 0]))
 
 
-@pytest.mark.parametrize("shape", ["narrow_dh64", "narrow_dh128", "wide_dh128", "wide_dh64", "partly_filled"])
+@pytest.mark.parametrize("shape", ["narrow_dh64", "narrow_dh128", "wide_dh128", "wide_dh64", "partly_filled", "two_mask_words",
+                                   "no_prefix"])
 def test_fp8_prefix_attention_parity(shape):
     kw = dict(narrow_dh64=dict(batch=4, n_tree=24, n_q_heads=8, n_kv_heads=2, head_dim=64),
               narrow_dh128=dict(batch=3, n_tree=60, n_q_heads=8, n_kv_heads=2, head_dim=128),
               wide_dh128=dict(batch=2, n_tree=40, n_q_heads=16, n_kv_heads=2, head_dim=128),
               wide_dh64=dict(batch=2, n_tree=80, n_q_heads=16, n_kv_heads=2, head_dim=64),
-              partly_filled=dict(batch=4, n_tree=24, n_q_heads=8, n_kv_heads=2, head_dim=128))[shape]
+              partly_filled=dict(batch=4, n_tree=24, n_q_heads=8, n_kv_heads=2, head_dim=128),
+              two_mask_words=dict(batch=2, n_tree=128, topk=16, depth=3, n_q_heads=8, n_kv_heads=2, head_dim=128),
+              no_prefix=dict(batch=3, n_tree=24, n_q_heads=8, n_kv_heads=2, head_dim=128))[shape]
     cfg = _cfg("fp8_" + shape, seed=91, **kw)
     B, N = cfg.batch, cfg.n_tree
     region = {4: [0, 77, 2300, 64], 3: [513, 1, 190], 2: [700, 129]}[B]
+    if shape == "no_prefix":
+        region = [0, 0, 0]
     Q, Kp, Vp, Kt, Vt, off = wl.make_attention_inputs(cfg, "cuda", prefix_lens=region)
     K8, V8, ks, vs = wl.make_fp8_prefix(Kp, Vp)
     plen = None
