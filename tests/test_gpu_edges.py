@@ -129,3 +129,40 @@ def test_partly_filled_kv_regions(dtype):
         e = pu.rel_err(pu.f64(O[b]), ref)
         assert e <= pu.REL_TOL[dtype], f"seq {b} (prefix_len {plen[b]}): rel err {e:.2e}"
         assert np.max(np.abs(pu.f64(lse[b]) - ref_lse)) <= pu.REL_TOL[dtype] * max(1.0, np.abs(ref_lse).max())
+
+
+@pytest.mark.parametrize("fp8", [False, True], ids=["bf16_prefix", "fp8_prefix"])
+def test_long_context_prefix_many_chunks(fp8):
+    """A 300k-token prefix: more than 64 key chunks per sequence (the combine kernel walks them in
+    batches of 64), next to a short sequence in the same launch."""
+    from oracle import eagle2_oracle as orc
+    from oracle import fp8_kv_oracle as f8
+    from paper_2406_16858_amd import DraftRound
+    from tests import parity_utils as pu
+    cfg = _cfg("long_ctx", batch=2, n_tree=24, n_q_heads=2, n_kv_heads=1, head_dim=128, seed=88)
+    B, N = cfg.batch, cfg.n_tree
+    region = [300_001, 70]
+    Q, Kp, Vp, Kt, Vt, off = wl.make_attention_inputs(cfg, "cuda", prefix_lens=region)
+    rnd = DraftRound(B, cfg.vocab, cfg.hidden, cfg.depth, cfg.topk, N, cfg.dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                     total_prefix=sum(region))
+    mask = np.tril(np.ones((N, N), dtype=bool))
+    bits = np.array([[sum(1 << j for j in range(i + 1))] for i in range(N)], dtype=np.uint64)
+    rnd.mask_bits.copy_(torch.from_numpy(np.tile(bits, (B, 1, 1)).view(np.int64)))
+    O = torch.full_like(Q, float("nan"))
+    lse = torch.full((B, N, cfg.n_q_heads), float("nan"), dtype=torch.float32, device="cuda")
+    if fp8:
+        K8, V8, ks, vs = wl.make_fp8_prefix(Kp, Vp)
+        rnd.tree_attn_fp8kv(Q, K8, V8, ks, vs, off, Kt, Vt, O, lse)
+        Kd = torch.from_numpy(f8.dequantize(K8.cpu().numpy(), ks.cpu().numpy()))
+        Vd = torch.from_numpy(f8.dequantize(V8.cpu().numpy(), vs.cpu().numpy()))
+    else:
+        rnd.tree_attn(Q, Kp, Vp, off, Kt, Vt, O, lse)
+        Kd, Vd = Kp, Vp
+    torch.cuda.synchronize()
+    offs = off.cpu().numpy()
+    for b in range(B):
+        lo, hi = int(offs[b]), int(offs[b + 1])
+        ref, ref_lse = orc.tree_attn(pu.f64(Q[b]), pu.f64(Kd[lo:hi]), pu.f64(Vd[lo:hi]), pu.f64(Kt[b]), pu.f64(Vt[b]), mask)
+        e = pu.rel_err(pu.f64(O[b]), ref)
+        assert e <= pu.REL_TOL["bf16"], f"seq {b}: rel err {e:.2e}"
+        assert np.max(np.abs(pu.f64(lse[b]) - ref_lse)) <= pu.REL_TOL["bf16"] * max(1.0, np.abs(ref_lse).max())
