@@ -40,6 +40,14 @@ def test_many_sequences_ragged_and_long_prefix():
     run_and_check_round(cfg, h_scale=6.0, plant=True)
 
 
+def test_many_small_sequences():
+    # 257 sequences: more sequences than compute units, 514 frontier rows (four passes of the many-row LM head
+    # per expansion), one sampling workgroup per sequence
+    cfg = _cfg("batch257", batch=257, vocab=300, hidden=512, depth=2, topk=2, n_tree=5, n_q_heads=2, n_kv_heads=1,
+               head_dim=64, prefix_lo=0, prefix_hi=40, accept="mixed", seed=31)
+    run_and_check_round(cfg, h_scale=4.0, verbose=False)
+
+
 def test_bitwise_determinism():
     from paper_2406_16858_amd import DraftRound
     cfg = wl.get_config(2)
