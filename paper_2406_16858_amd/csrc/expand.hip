@@ -658,24 +658,45 @@ void row_stats_kernel(int V, int F, const float* __restrict__ logits_ws, const f
 
 // One workgroup per (frontier row, sequence).  Each of the G partial lists is sorted, so an
 // entry can only be in the row's top k if its list's head is among the k best heads.  Heads,
-// surviving entries (<= k*KC) and new candidates (frontier) are all ranked by counting.  The workgroup that finishes last for a sequence (a counter in the workspace, zeroed
-// by lmhead_kernel) also selects the next frontier.
+// surviving entries (<= k*KC) and new candidates (frontier) are all ranked by counting.  The
+// workgroup that finishes last for a sequence (a counter in the workspace, zeroed by
+// lmhead_kernel) also selects the next frontier.
 constexpr int MG_THREADS = 1024;
+constexpr int MG_MAXN = EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK;   // most keys ranked at once
 
-// number of the n LDS entries that precede (v, i) in the order "higher value, then lower
-// index"; the reads are issued eight at a time so the loop is not a chain of LDS latencies
-template <typename T>
-__device__ __forceinline__ int count_before(const T* sv, const int* si, int n, T v, int i) {
-    int r = 0, j = 0;
-    for (; j + 8 <= n; j += 8) {
-        T a[8]; int c[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) { a[u] = sv[j + u]; c[u] = si[j + u]; }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) r += ranks_before(a[u], c[u], v, i) ? 1 : 0;
+// Orders are turned into single unsigned 64-bit comparisons.  (value, id) with "higher value first,
+// then lower id": the float's bits mapped monotonically to an unsigned, above the complemented id.
+__device__ __forceinline__ unsigned long long order_key(float v, int id) {
+    const unsigned b = __float_as_uint(v + 0.f);       // -0 and +0 are one value
+    const unsigned u = b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
+    return ((unsigned long long)u << 32) | (unsigned)~id;
+}
+__device__ __forceinline__ unsigned long long order_key(double v) {      // ties are broken by position
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v + 0.0);
+    return b ^ ((b >> 63) ? ~0ull : 0x8000000000000000ull);
+}
+__device__ __forceinline__ float key_value(unsigned long long key) {
+    const unsigned u = (unsigned)(key >> 32);
+    return __uint_as_float(u ^ ((u >> 31) ? 0x80000000u : 0xffffffffu));
+}
+__device__ __forceinline__ int key_id(unsigned long long key) { return (int)~(unsigned)key; }
+
+// Ranks of n <= MG_MAXN keys in LDS (descending; equal keys: lower position first), by all-pairs
+// counting spread over the whole workgroup: with P = MG_THREADS / n threads per key, thread
+// (i, part) counts the keys j = part, part + P, ... that precede key i, and the partial counts meet
+// in an LDS atomic.  rank[0..n) must be zero on entry; the caller synchronises before reading it.
+__device__ __forceinline__ void rank_keys(const unsigned long long* keys, int n, int* rank, int tid) {
+    const int P = MG_THREADS / n;
+    const int i = tid / P, part = tid - i * P;
+    if (i >= n) return;
+    const unsigned long long ki = keys[i];
+    int cnt = 0;
+#pragma unroll 4
+    for (int j = part; j < n; j += P) {
+        const unsigned long long kj = keys[j];
+        cnt += (kj > ki || (kj == ki && j < i)) ? 1 : 0;
     }
-    for (; j < n; ++j) r += ranks_before(sv[j], si[j], v, i) ? 1 : 0;
-    return r;
+    if (cnt) atomicAdd(rank + i, cnt);
 }
 
 template <int KC>
@@ -689,18 +710,15 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     constexpr int NW = MG_THREADS / 64;
     __shared__ float s_f[NW];
     __shared__ double s_d[NW];
-    __shared__ float s_hv[LM_GMAX];                     // list heads
-    __shared__ int s_hi[LM_GMAX];
-    __shared__ float s_wv[(MG_THREADS / 64) * EAGLE2_MAX_TOPK];   // per-wave winners: value, token, list
-    __shared__ int s_wi[(MG_THREADS / 64) * EAGLE2_MAX_TOPK], s_wl[(MG_THREADS / 64) * EAGLE2_MAX_TOPK];
+    __shared__ unsigned long long s_wk[NW * EAGLE2_MAX_TOPK];   // per-wave winners among the list heads: key, list
+    __shared__ int s_wl[NW * EAGLE2_MAX_TOPK];
     __shared__ int s_live[EAGLE2_MAX_TOPK];
-    __shared__ float s_cv[EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK];
-    __shared__ int s_ci[EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK];
-    __shared__ float s_ov[EAGLE2_MAX_TOPK];
-    __shared__ int s_oi[EAGLE2_MAX_TOPK];
-    __shared__ double s_fs[EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK];   // new candidates' scores (frontier selection)
-    __shared__ int s_fi[EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK];
+    __shared__ unsigned long long s_ck[MG_MAXN];        // entries of the surviving lists
+    __shared__ unsigned long long s_ok[EAGLE2_MAX_TOPK];   // the row's k best
+    __shared__ unsigned long long s_fk[MG_MAXN];        // new candidates' scores (frontier selection)
+    __shared__ int s_rank[3][MG_MAXN];                  // one set of counters per ranking, zeroed once
     __shared__ int s_last;
+    static_assert(NW * EAGLE2_MAX_TOPK <= MG_MAXN, "the per-wave winners are ranked like the other key sets");
     const int slot = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int base = d == 0 ? 0 : k + (d - 1) * k * k;
@@ -719,13 +737,14 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
         ps = cand_score[(size_t)b * C + par];
     }
     float my_m = -INFINITY, my_s = 0.f;
-    if (tid < EAGLE2_MAX_TOPK) { s_ov[tid] = -INFINITY; s_oi[tid] = 0; }
+    unsigned long long hk = 0ull;                       // this thread's list head (0 ranks after every real key)
     if (tid < G) {
-        s_hv[tid] = pv[(size_t)tid * KC];
-        s_hi[tid] = pi[(size_t)tid * KC];
+        hk = order_key(pv[(size_t)tid * KC], pi[(size_t)tid * KC]);
         my_m = ms[tid * 2];
         my_s = ms[tid * 2 + 1];
     }
+    if (tid < EAGLE2_MAX_TOPK) { s_ok[tid] = 0ull; s_live[tid] = -1; }
+    if (tid < MG_MAXN) { s_rank[0][tid] = 0; s_rank[1][tid] = 0; s_rank[2][tid] = 0; s_wk[tid] = 0ull; s_ck[tid] = 0ull; }
     // log-sum-exp over the G partial pairs
     float mloc = wave_max(my_m);
     if (lane == 0) s_f[wave] = mloc;
@@ -737,45 +756,44 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     sloc = wave_sum(sloc);
     if (lane == 0) s_d[wave] = sloc;
 
-    // the k best heads, by counting instead of sorting: inside every wave each head counts the
-    // heads of the other 63 lanes that precede it (broadcast with v_readlane, no LDS); the at
-    // most k survivors per wave are then ranked against each other through LDS
+    // the k best heads: inside every wave each head counts the heads of the other lanes that precede
+    // it (broadcast with v_readlane, no LDS); the at most k survivors per wave are then ranked
+    // against each other
     const int nlive = G < k ? G : k;
     const int nwv = (G + 63) >> 6;                          // waves that hold heads
-    if (tid < NW * EAGLE2_MAX_TOPK) { s_wv[tid] = -INFINITY; s_wi[tid] = INT_MAX; s_wl[tid] = 0; }
-    __syncthreads();
     if (wave < nwv) {
-        const float hv = tid < G ? s_hv[tid] : -INFINITY;
-        const int hi = tid < G ? s_hi[tid] : INT_MAX;
+        const int klo = (int)(unsigned)hk, khi = (int)(unsigned)(hk >> 32);
         int r = 0;
 #pragma unroll
-        for (int j = 0; j < 64; ++j) r += ranks_before(read_lane(hv, j), read_lane(hi, j), hv, hi) ? 1 : 0;
-        if (r < nlive && tid < G) { s_wv[wave * nlive + r] = hv; s_wi[wave * nlive + r] = hi; s_wl[wave * nlive + r] = tid; }
-    }
-    __syncthreads();
-    {
-        const int n2 = nwv * nlive;                         // <= 256 survivors, compact in s_w*
-        if (tid < n2) {
-            const int r = count_before(s_wv, s_wi, n2, s_wv[tid], s_wi[tid]);
-            if (r < nlive && s_wi[tid] != INT_MAX) s_live[r] = s_wl[tid];
+        for (int j = 0; j < 64; ++j) {
+            const unsigned long long kj = ((unsigned long long)(unsigned)read_lane(khi, j) << 32) | (unsigned)read_lane(klo, j);
+            r += (kj > hk || (kj == hk && j < lane)) ? 1 : 0;
         }
+        if (r < nlive && tid < G) { s_wk[wave * nlive + r] = hk; s_wl[wave * nlive + r] = tid; }
     }
     __syncthreads();
-    // gather the surviving lists: nlive * KC candidates
+    const int n2 = nwv * nlive;                             // <= MG_MAXN survivors, compact in s_wk
+    rank_keys(s_wk, n2, s_rank[0], tid);
+    __syncthreads();
+    if (tid < n2) {
+        const int r = s_rank[0][tid];
+        if (r < nlive && s_wk[tid] != 0ull) s_live[r] = s_wl[tid];
+    }
+    __syncthreads();
+    // the entries of the surviving lists: nlive * KC candidates
     const int ncand = nlive * KC;
     if (tid < ncand) {
-        int l = s_live[tid / KC];
-        if (l < 0 || l >= G) l = 0;
+        const int l = s_live[tid / KC];
         const int j = tid - (tid / KC) * KC;
-        s_cv[tid] = pv[(size_t)l * KC + j];
-        s_ci[tid] = pi[(size_t)l * KC + j];
+        if (l >= 0 && l < G) s_ck[tid] = order_key(pv[(size_t)l * KC + j], pi[(size_t)l * KC + j]);
     }
     __syncthreads();
+    rank_keys(s_ck, ncand, s_rank[1], tid);
+    __syncthreads();
     if (tid < ncand) {
-        const float cv = s_cv[tid];
-        const int ci = s_ci[tid];
-        const int r = count_before(s_cv, s_ci, ncand, cv, ci);
-        if (r < k && ci != INT_MAX) { s_ov[r] = cv; s_oi[r] = ci; }
+        const int r = s_rank[1][tid];
+        const unsigned long long key = s_ck[tid];
+        if (r < k && key != 0ull && key_id(key) != INT_MAX) s_ok[r] = key;
     }
     __syncthreads();
     if (tid < k) {
@@ -784,8 +802,10 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
         for (int w = 0; w < NW; ++w) tot += s_d[w];
         const double log_sum = log(tot);
         const int cid = base + slot * k + tid;
-        const double sc = ps + (((double)s_ov[tid] - (double)mx) - log_sum);
-        cand_token[(size_t)b * C + cid] = s_oi[tid];
+        const unsigned long long key = s_ok[tid];
+        const float ov = key != 0ull ? key_value(key) : -INFINITY;
+        const double sc = ps + (((double)ov - (double)mx) - log_sum);
+        cand_token[(size_t)b * C + cid] = key != 0ull ? key_id(key) : 0;
         cand_parent[(size_t)b * C + cid] = par;
         // The score is also read by the workgroup that picks the next frontier, possibly on
         // another XCD: store it at device scope and wait for the acknowledgement, instead of a
@@ -803,7 +823,7 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     }
     __syncthreads();
     if (!s_last) return;
-    const int nn = F * k;                               // <= 256 new candidates, ranked by counting
+    const int nn = F * k;                               // <= MG_MAXN new candidates, in candidate-id order
     if (tid < nn) {
         double key = __hip_atomic_load(cand_score + (size_t)b * C + base + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (by_confidence && d > 0) {                   // "w/o value" (Section 5.2): the node's own log confidence
@@ -811,12 +831,13 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
             if (par < 0 || par >= C) par = 0;
             key -= cand_score[(size_t)b * C + par];     // written by an earlier pass
         }
-        s_fs[tid] = key;
-        s_fi[tid] = base + tid;
+        s_fk[tid] = order_key(key);
     }
     __syncthreads();
+    rank_keys(s_fk, nn, s_rank[2], tid);
+    __syncthreads();
     if (tid < nn) {
-        const int r = count_before(s_fs, s_fi, nn, s_fs[tid], s_fi[tid]);
+        const int r = s_rank[2][tid];
         if (r < k) frontier[((size_t)b * D + d + 1) * k + r] = base + tid;
     }
 }
