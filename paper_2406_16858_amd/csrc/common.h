@@ -85,6 +85,20 @@ template <int CTRL> __device__ __forceinline__ double dpp_mov(double v) {
     const int lo = dpp_mov<CTRL>(__double2loint(v)), hi = dpp_mov<CTRL>(__double2hiint(v));
     return __hiloint2double(hi, lo);
 }
+// The value of lane^16 / lane^32, on the vector ALU (gfx950's row and half-wave swaps) instead of the
+// LDS crossbar a shuffle uses.  permlane16_swap(x, x) returns (rows 0,0,2,2 ; rows 1,1,3,3) of x, so an
+// even row finds its neighbour in the second result and an odd row in the first; permlane32_swap(x, x)
+// returns (lower half twice ; upper half twice).
+__device__ __forceinline__ int lane_xor16(int v) {
+    const u32x2 r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+    return (int)((threadIdx.x & 16) ? r[0] : r[1]);
+}
+__device__ __forceinline__ int lane_xor32(int v) {
+    const u32x2 r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+    return (int)((threadIdx.x & 32) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float lane_xor16(float v) { return __int_as_float(lane_xor16(__float_as_int(v))); }
+__device__ __forceinline__ float lane_xor32(float v) { return __int_as_float(lane_xor32(__float_as_int(v))); }
 __device__ __forceinline__ int read_lane(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
 // lane index held in a register (must be wave-uniform)
 __device__ __forceinline__ int read_lane_dyn(int v, int l) { return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(l)); }

@@ -245,7 +245,7 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
         // (max, sum-exp) over lanes m16, m16+16, m16+32, m16+48
 #pragma unroll
         for (int o = 16; o <= 32; o <<= 1) {
-            const float om = __shfl_xor(run_m, o, 64), os = __shfl_xor(run_s, o, 64);
+            const float om = o == 16 ? lane_xor16(run_m) : lane_xor32(run_m), os = o == 16 ? lane_xor16(run_s) : lane_xor32(run_s);
             const float nm = fmaxf(run_m, om);
             const float a = run_m > -INFINITY ? run_s * __expf(run_m - nm) : 0.f;
             const float c = om > -INFINITY ? os * __expf(om - nm) : 0.f;
@@ -259,8 +259,8 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
             float bv = tval[0]; int bi = tidx[0];
 #pragma unroll
             for (int o = 16; o <= 32; o <<= 1) {
-                const float ov = __shfl_xor(bv, o, 64);
-                const int oi = __shfl_xor(bi, o, 64);
+                const float ov = o == 16 ? lane_xor16(bv) : lane_xor32(bv);
+                const int oi = o == 16 ? lane_xor16(bi) : lane_xor32(bi);
                 if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
             }
             if (tval[0] == bv && tidx[0] == bi) {
