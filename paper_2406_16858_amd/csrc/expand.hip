@@ -712,7 +712,6 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     __shared__ double s_d[NW];
     __shared__ unsigned long long s_wk[NW * EAGLE2_MAX_TOPK];   // per-wave winners among the list heads: key, list
     __shared__ int s_wl[NW * EAGLE2_MAX_TOPK];
-    __shared__ int s_live[EAGLE2_MAX_TOPK];
     __shared__ unsigned long long s_ck[MG_MAXN];        // entries of the surviving lists
     __shared__ unsigned long long s_ok[EAGLE2_MAX_TOPK];   // the row's k best
     __shared__ unsigned long long s_fk[MG_MAXN];        // new candidates' scores (frontier selection)
@@ -743,8 +742,8 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
         my_m = ms[tid * 2];
         my_s = ms[tid * 2 + 1];
     }
-    if (tid < EAGLE2_MAX_TOPK) { s_ok[tid] = 0ull; s_live[tid] = -1; }
-    if (tid < MG_MAXN) { s_rank[0][tid] = 0; s_rank[1][tid] = 0; s_rank[2][tid] = 0; s_wk[tid] = 0ull; s_ck[tid] = 0ull; }
+    if (tid < EAGLE2_MAX_TOPK) s_ok[tid] = 0ull;
+    if (tid < MG_MAXN) { s_rank[0][tid] = 0; s_rank[1][tid] = 0; s_rank[2][tid] = 0; s_wk[tid] = 0ull; s_ck[tid] = 0ull; s_wl[tid] = 0; }
     // log-sum-exp over the G partial pairs
     float mloc = wave_max(my_m);
     if (lane == 0) s_f[wave] = mloc;
@@ -767,7 +766,7 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
 #pragma unroll
         for (int j = 0; j < 64; ++j) {
             const unsigned long long kj = ((unsigned long long)(unsigned)read_lane(khi, j) << 32) | (unsigned)read_lane(klo, j);
-            r += (kj > hk || (kj == hk && j < lane)) ? 1 : 0;
+            r += kj > hk ? 1 : 0;                       // equal keys are empty lists only, which never contribute
         }
         if (r < nlive && tid < G) { s_wk[wave * nlive + r] = hk; s_wl[wave * nlive + r] = tid; }
     }
@@ -775,17 +774,14 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     const int n2 = nwv * nlive;                             // <= MG_MAXN survivors, compact in s_wk
     rank_keys(s_wk, n2, s_rank[0], tid);
     __syncthreads();
-    if (tid < n2) {
-        const int r = s_rank[0][tid];
-        if (r < nlive && s_wk[tid] != 0ull) s_live[r] = s_wl[tid];
-    }
-    __syncthreads();
-    // the entries of the surviving lists: nlive * KC candidates
+    // a winner of rank r < nlive brings in its list: nlive * KC candidates in all
     const int ncand = nlive * KC;
-    if (tid < ncand) {
-        const int l = s_live[tid / KC];
-        const int j = tid - (tid / KC) * KC;
-        if (l >= 0 && l < G) s_ck[tid] = order_key(pv[(size_t)l * KC + j], pi[(size_t)l * KC + j]);
+    if (tid < n2) {
+        const int r = s_rank[0][tid], l = s_wl[tid];
+        if (r < nlive && s_wk[tid] != 0ull && l >= 0 && l < G) {
+#pragma unroll
+            for (int j = 0; j < KC; ++j) s_ck[r * KC + j] = order_key(pv[(size_t)l * KC + j], pi[(size_t)l * KC + j]);
+        }
     }
     __syncthreads();
     rank_keys(s_ck, ncand, s_rank[1], tid);
