@@ -377,12 +377,18 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
         block_max2(mt, md, s_red);
         double st = 0.0, sd = 0.0;
         if constexpr (CACHED) {
+            // the exponentials relative to this workgroup's maxima are kept: the global maxima and the
+            // normalisers turn them into probabilities with one multiplication each
 #pragma unroll
             for (int e = 0; e < SAMPLE_MAXE; ++e) {
+                pe[e] = 0.0;
+                qe[e] = 0.0;
                 if (t_lo + e < t_hi) {
-                    st += exp((double)zte[e] * inv_t - mt);
-                    if (has_q) sd += exp((double)zde[e] - md);
+                    pe[e] = exp((double)zte[e] * inv_t - mt);
+                    if (has_q) qe[e] = exp((double)zde[e] - md);
                 }
+                st += pe[e];
+                sd += qe[e];
             }
         } else {
             for (int v = t_lo; v < t_hi; ++v) {
@@ -390,6 +396,7 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
                 if (has_q) sd += exp((double)zd_row[v] - md);
             }
         }
+        const double wg_mt = mt, wg_md = md;               // this workgroup's maxima (uniform after block_max2)
         block_sum2(st, sd, s_red);
         {
             const double mine[SAMPLE_NPART] = {mt, st, md, sd};
@@ -411,11 +418,10 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
         __syncthreads();
         if (tid < nkids) initial_state(ns, s_ztx[tid], s_zdx[tid], s_pk[tid], s_qk[tid]);
         if constexpr (CACHED) {
+            const double fp = wg_mt > -INFINITY ? exp(wg_mt - ns.mt) * ns.ist : 0.0;
+            const double fq = (has_q && wg_md > -INFINITY) ? exp(wg_md - ns.md) * ns.isd : 0.0;
 #pragma unroll
-            for (int e = 0; e < SAMPLE_MAXE; ++e) {
-                if (t_lo + e < t_hi) initial_state(ns, zte[e], has_q ? zde[e] : 0.f, pe[e], qe[e]);
-                else { pe[e] = 0.0; qe[e] = 0.0; }
-            }
+            for (int e = 0; e < SAMPLE_MAXE; ++e) { pe[e] *= fp; qe[e] *= fq; }
         }
         __syncthreads();
 
