@@ -317,6 +317,9 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
     const int per_th = (v_hi - v_lo + SAMPLE_THREADS - 1) / SAMPLE_THREADS;
     const int t_lo = min(v_hi, v_lo + tid * per_th), t_hi = min(v_hi, t_lo + per_th);
 
+    // every thread's chunk starts on a 16-byte boundary of the (16-byte aligned) logit rows
+    const bool vec_ok = CACHED && (V & 3) == 0 && (per_wg & 3) == 0 && (per_th & 3) == 0 && SAMPLE_MAXE % 4 == 0 &&
+                        ((reinterpret_cast<size_t>(target_logits) | reinterpret_cast<size_t>(draft_logits)) & 15) == 0;
     double pe[CACHED ? SAMPLE_MAXE : 1], qe[CACHED ? SAMPLE_MAXE : 1];
 
     int cur = 0, len = 0;
@@ -357,11 +360,26 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
         float zte[CACHED ? SAMPLE_MAXE : 1], zde[CACHED ? SAMPLE_MAXE : 1];
         double mt = -INFINITY, md = -INFINITY;
         if constexpr (CACHED) {
+            if (vec_ok) {                                     // uniform: 16-byte loads, four per row and thread
 #pragma unroll
-            for (int e = 0; e < SAMPLE_MAXE; ++e) {            // all loads in flight together
-                const int v = t_lo + e;
-                zte[e] = v < t_hi ? zt_row[v] : -INFINITY;
-                zde[e] = (v < t_hi && has_q) ? zd_row[v] : -INFINITY;
+                for (int e4 = 0; e4 < SAMPLE_MAXE / 4; ++e4) {
+                    const int v = t_lo + e4 * 4;
+                    const bool in = v < t_hi;
+                    const floatx4 a = in ? *reinterpret_cast<const floatx4*>(zt_row + v) : floatx4{0.f, 0.f, 0.f, 0.f};
+                    const floatx4 c = (in && has_q) ? *reinterpret_cast<const floatx4*>(zd_row + v) : floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        zte[e4 * 4 + i] = v + i < t_hi ? a[i] : -INFINITY;
+                        zde[e4 * 4 + i] = (v + i < t_hi && has_q) ? c[i] : -INFINITY;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < SAMPLE_MAXE; ++e) {        // all loads in flight together
+                    const int v = t_lo + e;
+                    zte[e] = v < t_hi ? zt_row[v] : -INFINITY;
+                    zde[e] = (v < t_hi && has_q) ? zd_row[v] : -INFINITY;
+                }
             }
 #pragma unroll
             for (int e = 0; e < SAMPLE_MAXE; ++e) {
