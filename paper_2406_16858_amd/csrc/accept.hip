@@ -24,6 +24,8 @@ constexpr int SAMPLE_THREADS = 256;
 constexpr int SAMPLE_NPART = 4;          // doubles exchanged per workgroup per pass
 constexpr int SAMPLE_SLOT = 8;           // 64-bit words per exchange slot: two tagged halves per double
 constexpr unsigned SPIN_LIMIT = 1u << 22;
+constexpr int SAMPLE_WAVES = SAMPLE_THREADS / 64;
+constexpr int SAMPLE_WORDS = 2 * SAMPLE_WGS * SAMPLE_SLOT;   // words of exchange slots per sequence (two sets)
 
 struct AcceptWs { size_t choice, bar, part, total; };
 static AcceptWs accept_layout(const eagle2_cfg* cfg) {
@@ -31,7 +33,7 @@ static AcceptWs accept_layout(const eagle2_cfg* cfg) {
     w.choice = 0;
     w.bar = round_up((size_t)cfg->batch * cfg->n_tree * sizeof(int), 256);
     w.part = w.bar + round_up((size_t)cfg->batch * sizeof(unsigned), 256);
-    w.total = w.part + round_up((size_t)cfg->batch * 2 * SAMPLE_WGS * SAMPLE_SLOT * sizeof(unsigned long long), 256);
+    w.total = w.part + round_up((size_t)cfg->batch * SAMPLE_WORDS * sizeof(unsigned long long), 256);
     return w;
 }
 size_t accept_workspace(const eagle2_cfg* cfg) { return accept_layout(cfg).total; }
@@ -172,6 +174,52 @@ __device__ bool exchange(SampleCtx& cx, const double (&mine)[SAMPLE_NPART], doub
     return *s_ok != 0;
 }
 
+// The rejection loop's exchange: sums two doubles per wave over all waves of all workgroups of a
+// sequence with two barriers.  Every wave drops its pair into s_red; after the first barrier wave 0
+// publishes the workgroup's pair (four tagged words, the first half of its slot) and the first
+// nwg * 4 threads each wait for one word of one workgroup; after the second barrier every wave adds
+// the gathered pairs itself, in the same order everywhere.  *s_ok must be 1 on entry and is cleared
+// for good when a bounded wait expires.
+__device__ bool exchange_sum2(SampleCtx& cx, double a, double b, double* s_red /*2 per wave*/, double* out /*LDS, 2 per wg*/,
+                              int* s_ok, double& ga, double& gb) {
+    const int wg = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    unsigned long long* buf = cx.slots + (size_t)(cx.pass & 1) * SAMPLE_WGS * SAMPLE_SLOT;
+    const unsigned tagw = (unsigned)cx.pass + 1u;
+    if (lane == 0) { s_red[wave * 2] = a; s_red[wave * 2 + 1] = b; }
+    __syncthreads();                                   // also: the previous exchange's `out` is no longer read
+    if (tid < 4) {
+        double v = 0.0;
+#pragma unroll
+        for (int w = 0; w < SAMPLE_WAVES; ++w) v += s_red[w * 2 + (tid >> 1)];
+        const unsigned half = (tid & 1) ? (unsigned)__double2hiint(v) : (unsigned)__double2loint(v);
+        __hip_atomic_store(buf + wg * SAMPLE_SLOT + tid, ((unsigned long long)tagw << 32) | half, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (tid < cx.nwg * 4) {
+        const unsigned long long* src = buf + (tid >> 2) * SAMPLE_SLOT + (tid & 3);
+        unsigned spins = 0;
+        bool ok = true;
+        unsigned long long wv;
+        while (((wv = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 32) != tagw) {
+            __builtin_amdgcn_s_sleep(1);
+            if ((++spins & 1023u) == 0u &&
+                (spins > SPIN_LIMIT || __hip_atomic_load(cx.fail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
+                ok = false;
+                atomicExch(cx.fail, 1u);
+                break;
+            }
+        }
+        if (ok) reinterpret_cast<unsigned*>(out)[tid] = (unsigned)wv;     // workgroup g: doubles 2g, 2g + 1
+        else *s_ok = 0;
+    }
+    __syncthreads();
+    cx.pass += 1;
+    if (*s_ok == 0) return false;
+    ga = wave_sum(lane < cx.nwg ? out[lane * 2] : 0.0);
+    gb = wave_sum(lane < cx.nwg ? out[lane * 2 + 1] : 0.0);
+    return true;
+}
+
 __device__ __forceinline__ double block_sum(double v, double* s_red) {
     v = wave_sum(v);
     __syncthreads();
@@ -295,7 +343,7 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
 
     SampleCtx cx;
     cx.fail = fails + b;
-    cx.slots = slots + (size_t)b * 2 * SAMPLE_WGS * SAMPLE_SLOT;
+    cx.slots = slots + (size_t)b * SAMPLE_WORDS;
     cx.pass = 0;
     cx.nwg = nwg;
 
@@ -434,62 +482,86 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
             }
         }
         __syncthreads();
-        if (tid < nkids) initial_state(ns, s_ztx[tid], s_zdx[tid], s_pk[tid], s_qk[tid]);
+        bool moved = false, failed = false;
         if constexpr (CACHED) {
+            // Every wave walks the children on its own: lane c keeps child c's current (p, q) and a
+            // decision is read off lane ci, so a rejection costs one exchange (two barriers).
             const double fp = wg_mt > -INFINITY ? exp(wg_mt - ns.mt) * ns.ist : 0.0;
             const double fq = (has_q && wg_md > -INFINITY) ? exp(wg_md - ns.md) * ns.isd : 0.0;
 #pragma unroll
             for (int e = 0; e < SAMPLE_MAXE; ++e) { pe[e] *= fp; qe[e] *= fq; }
-        }
-        __syncthreads();
-
-        bool moved = false, failed = false;
-        for (int ci = 0; ci < nkids; ++ci) {
-            const int c = s_kids[ci];
-            const int x = s_tok[c];
-            if (tid == 0) s_decision = (x >= 0 && x < V && (double)s_ua[c] < s_pk[ci] / s_qk[ci]) ? 1 : 0;
-            __syncthreads();
-            if (s_decision) { cur = c; ++len; moved = true; if (wg == 0 && tid == 0 && len <= D) path[len] = c; break; }
-            // rejected: residual mass and remaining draft mass
-            double tot = 0.0, qs = 0.0;
-            if constexpr (CACHED) {
+            const int lane = tid & 63;
+            double pk = 0.0, qk = 0.0;
+            int xk = -1;
+            if (lane < nkids) {
+                initial_state(ns, s_ztx[lane], s_zdx[lane], pk, qk);
+                xk = s_tok[s_kids[lane]];
+            }
+            for (int ci = 0; ci < nkids; ++ci) {
+                const int c = s_kids[ci];
+                const int x = s_tok[c];
+                const double pc = read_lane_dyn(pk, ci), qc = read_lane_dyn(qk, ci);
+                if (x >= 0 && x < V && (double)s_ua[c] < pc / qc) {
+                    cur = c; ++len; moved = true;
+                    if (wg == 0 && tid == 0 && len <= D) path[len] = c;
+                    break;
+                }
+                // rejected: residual mass and remaining draft mass
+                double tot = 0.0, qs = 0.0;
 #pragma unroll
                 for (int e = 0; e < SAMPLE_MAXE; ++e) {
                     tot += fmax(pe[e] - qe[e], 0.0);
                     if (t_lo + e != x) qs += qe[e];
                 }
-            } else {
+                tot = wave_sum(tot);
+                qs = wave_sum(qs);
+                double gt, gq;
+                if (!exchange_sum2(cx, tot, qs, s_red, s_all, &s_ok, gt, gq)) { failed = true; break; }
+                const double itot = gt > 0.0 ? 1.0 / gt : 0.0, iqs = gq > 0.0 ? 1.0 / gq : 0.0;
+                if (lane < nkids) reject_step(xk, x, itot, iqs, pk, qk);
+#pragma unroll
+                for (int e = 0; e < SAMPLE_MAXE; ++e) reject_step(t_lo + e, x, itot, iqs, pe[e], qe[e]);
+            }
+        } else {
+            // the state is rebuilt from the logits in every pass; the children's (p, q) live in LDS
+            if (tid < nkids) initial_state(ns, s_ztx[tid], s_zdx[tid], s_pk[tid], s_qk[tid]);
+            __syncthreads();
+
+            for (int ci = 0; ci < nkids; ++ci) {
+                const int c = s_kids[ci];
+                const int x = s_tok[c];
+                if (tid == 0) s_decision = (x >= 0 && x < V && (double)s_ua[c] < s_pk[ci] / s_qk[ci]) ? 1 : 0;
+                __syncthreads();
+                if (s_decision) { cur = c; ++len; moved = true; if (wg == 0 && tid == 0 && len <= D) path[len] = c; break; }
+                // rejected: residual mass and remaining draft mass
+                double tot = 0.0, qs = 0.0;
                 for (int v = t_lo; v < t_hi; ++v) {
                     double p, q;
                     element_state(ns, v, zt_row[v], zd_row[v], p, q);
                     tot += fmax(p - q, 0.0);
                     if (v != x) qs += q;
                 }
+                block_sum2(tot, qs, s_red);
+                {
+                    const double mine[SAMPLE_NPART] = {tot, qs, 0.0, 0.0};
+                    if (!exchange(cx, mine, s_all, &s_ok)) { failed = true; break; }
+                }
+                if (tid < 64) {
+                    const double gt0 = wave_sum(tid < nwg ? s_all[tid * SAMPLE_NPART] : 0.0);
+                    const double gq0 = wave_sum(tid < nwg ? s_all[tid * SAMPLE_NPART + 1] : 0.0);
+                    if (tid == 0) { s_g[0] = gt0; s_g[1] = gq0; }
+                }
+                __syncthreads();
+                const double gt = s_g[0], gq = s_g[1];
+                const double itot = gt > 0.0 ? 1.0 / gt : 0.0, iqs = gq > 0.0 ? 1.0 / gq : 0.0;
+                if (tid == 0) {
+                    const int j = ns.nrej;
+                    ns.rej_tok[j] = x; ns.rej_itot[j] = itot; ns.rej_iqs[j] = iqs;
+                    ns.nrej = j + 1;
+                }
+                if (tid < nkids) reject_step(s_tok[s_kids[tid]], x, itot, iqs, s_pk[tid], s_qk[tid]);
+                __syncthreads();
             }
-            block_sum2(tot, qs, s_red);
-            {
-                const double mine[SAMPLE_NPART] = {tot, qs, 0.0, 0.0};
-                if (!exchange(cx, mine, s_all, &s_ok)) { failed = true; break; }
-            }
-            if (tid < 64) {
-                const double gt0 = wave_sum(tid < nwg ? s_all[tid * SAMPLE_NPART] : 0.0);
-                const double gq0 = wave_sum(tid < nwg ? s_all[tid * SAMPLE_NPART + 1] : 0.0);
-                if (tid == 0) { s_g[0] = gt0; s_g[1] = gq0; }
-            }
-            __syncthreads();
-            const double gt = s_g[0], gq = s_g[1];
-            const double itot = gt > 0.0 ? 1.0 / gt : 0.0, iqs = gq > 0.0 ? 1.0 / gq : 0.0;
-            if (tid == 0) {
-                const int j = ns.nrej;
-                ns.rej_tok[j] = x; ns.rej_itot[j] = itot; ns.rej_iqs[j] = iqs;
-                ns.nrej = j + 1;
-            }
-            if (tid < nkids) reject_step(s_tok[s_kids[tid]], x, itot, iqs, s_pk[tid], s_qk[tid]);
-            if constexpr (CACHED) {
-#pragma unroll
-                for (int e = 0; e < SAMPLE_MAXE; ++e) reject_step(t_lo + e, x, itot, iqs, pe[e], qe[e]);
-            }
-            __syncthreads();
         }
         if (failed) break;
         if (moved) continue;
@@ -597,7 +669,7 @@ extern "C" int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int B = cfg->batch, N = cfg->n_tree, V = cfg->vocab, D = cfg->depth;
 
-    const int nwords = can_sample ? B * 2 * SAMPLE_WGS * SAMPLE_SLOT : 0;
+    const int nwords = can_sample ? B * SAMPLE_WORDS : 0;
     hipLaunchKernelGGL(row_argmax_kernel, dim3(N, B), dim3(AM_THREADS), 0, st, target_logits, V, N, mode, choice,
                        fails, can_sample ? B : 0, slots, nwords);
     E2_HIP(hipGetLastError());

@@ -103,6 +103,9 @@ __device__ __forceinline__ int read_lane(int v, int l) { return __builtin_amdgcn
 // lane index held in a register (must be wave-uniform)
 __device__ __forceinline__ int read_lane_dyn(int v, int l) { return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(l)); }
 __device__ __forceinline__ float read_lane_dyn(float v, int l) { return __int_as_float(read_lane_dyn(__float_as_int(v), l)); }
+__device__ __forceinline__ double read_lane_dyn(double v, int l) {
+    return __hiloint2double(read_lane_dyn(__double2hiint(v), l), read_lane_dyn(__double2loint(v), l));
+}
 __device__ __forceinline__ float read_lane(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
 __device__ __forceinline__ double read_lane(double v, int l) {
     return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l), __builtin_amdgcn_readlane(__double2loint(v), l));
