@@ -682,12 +682,14 @@ __device__ __forceinline__ float key_value(unsigned long long key) {
 __device__ __forceinline__ int key_id(unsigned long long key) { return (int)~(unsigned)key; }
 
 // Ranks of n <= MG_MAXN keys in LDS (descending; equal keys: lower position first), by all-pairs
-// counting spread over the whole workgroup: with P = MG_THREADS / n threads per key, thread
+// counting spread over the whole workgroup: with P threads per key (the largest power of two that
+// fits MG_THREADS / n), thread
 // (i, part) counts the keys j = part, part + P, ... that precede key i, and the partial counts meet
 // in an LDS atomic.  rank[0..n) must be zero on entry; the caller synchronises before reading it.
 __device__ __forceinline__ void rank_keys(const unsigned long long* keys, int n, int* rank, int tid) {
-    const int P = MG_THREADS / n;
-    const int i = tid / P, part = tid - i * P;
+    const int lg = 31 - __clz(MG_THREADS / n);          // P = 2^lg threads per key: shifts instead of a division
+    const int P = 1 << lg;
+    const int i = tid >> lg, part = tid & (P - 1);
     if (i >= n) return;
     const unsigned long long ki = keys[i];
     int cnt = 0;
