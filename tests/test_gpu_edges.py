@@ -48,6 +48,14 @@ def test_many_small_sequences():
     run_and_check_round(cfg, h_scale=4.0, verbose=False)
 
 
+def test_sampling_with_more_vocabulary_per_thread_than_registers_hold():
+    # 40 sampling sequences share the chip: 12 workgroups each, 50021 / 12 / 256 > 16 entries per thread, so the
+    # sampling kernel rebuilds its state from the logits in every pass instead of keeping it in registers
+    cfg = _cfg("uncached_sampling", batch=40, vocab=50021, hidden=512, depth=2, topk=3, n_tree=8, n_q_heads=2, n_kv_heads=1,
+               head_dim=64, prefix_lo=0, prefix_hi=30, accept="sample", temperature=0.8, seed=41)
+    run_and_check_round(cfg, h_scale=5.0, verbose=False)
+
+
 def test_bitwise_determinism():
     from paper_2406_16858_amd import DraftRound
     cfg = wl.get_config(2)
