@@ -119,7 +119,10 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     // tokens) and the row blocks of one head, which re-read the same keys, start together on one
     // XCD's L2 (when the head count is a multiple of 8).
     const unsigned lin = blockIdx.x + gridDim.x * blockIdx.y;
-    const int flat = (int)(lin / gridDim.y), yy = (int)(lin - (unsigned)flat * gridDim.y);
+    // (chunks are handed out last first: a sequence's short chunks -- the tree chunk and the partly filled
+    // last prefix chunk -- start first and give their places to the workgroups beyond the first resident round)
+    const int slot = (int)(lin / gridDim.y), yy = (int)(lin - (unsigned)slot * gridDim.y);
+    const int flat = (int)gridDim.x - 1 - slot;
     if (!locate_chunk(flat, B, chunk, kv_offsets, kv_len, sc)) return;
     const int mblk = yy / Hkv, kvh = yy - mblk * Hkv;
     const int grp = Hq / Hkv, rows = grp * nq;      // query rows: tree rows q0 .. q0+nq-1 of every head in the group
