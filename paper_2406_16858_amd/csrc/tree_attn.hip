@@ -34,14 +34,18 @@ __device__ __forceinline__ long long prefix_keys(int b, const long long* kv_offs
     const long long n = kv_len[b];
     return n < 0 ? 0 : (n < region ? n : region);
 }
-// Maps a flat chunk index to (sequence, chunk); chunks of sequence b are
-// ceil(P_b / chunk) prefix chunks followed by the tree chunk.
+// Maps a flat chunk index to (sequence, chunk); sequence b has max(1, ceil(P_b / chunk)) chunks of
+// prefix keys, and the last of them also takes the sequence's tree keys.
+__device__ __forceinline__ int seq_chunks(long long P, int chunk) {
+    const int n = (int)((P + chunk - 1) / chunk);
+    return n < 1 ? 1 : n;
+}
 __device__ __forceinline__ bool locate_chunk(int flat, int B, int chunk, const long long* kv_offsets, const int* kv_len, SeqChunk& sc) {
     int rem = flat, first = 0;
     for (int b = 0; b < B; ++b) {
         const long long off = kv_offsets[b];
         const long long P = prefix_keys(b, kv_offsets, kv_len);
-        const int nc = (int)((P + chunk - 1) / chunk) + 1;
+        const int nc = seq_chunks(P, chunk);
         if (rem < nc) { sc.b = b; sc.c = rem; sc.nc = nc; sc.off = off; sc.P = P; sc.first = first; return true; }
         rem -= nc;
         first += nc;
@@ -50,8 +54,8 @@ __device__ __forceinline__ bool locate_chunk(int flat, int B, int chunk, const l
 }
 __device__ __forceinline__ void locate_seq(int b, int chunk, const long long* kv_offsets, const int* kv_len, int& first, int& nc) {
     first = 0;
-    for (int i = 0; i < b; ++i) first += (int)((prefix_keys(i, kv_offsets, kv_len) + chunk - 1) / chunk) + 1;
-    nc = (int)((prefix_keys(b, kv_offsets, kv_len) + chunk - 1) / chunk) + 1;
+    for (int i = 0; i < b; ++i) first += seq_chunks(prefix_keys(i, kv_offsets, kv_len), chunk);
+    nc = seq_chunks(prefix_keys(b, kv_offsets, kv_len), chunk);
 }
 
 template <int DH> __device__ __forceinline__ int k_swz(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
@@ -126,18 +130,40 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     if (!locate_chunk(flat, B, chunk, kv_offsets, kv_len, sc)) return;
     const int mblk = yy / Hkv, kvh = yy - mblk * Hkv;
     const int grp = Hq / Hkv, rows = grp * nq;      // query rows: tree rows q0 .. q0+nq-1 of every head in the group
+    // A workgroup runs up to two phases over the same accumulators: its chunk of prefix keys (all
+    // visible; 8-bit codes in the KV8 kernels), then, in a sequence's last chunk, the N tree keys under
+    // the ancestor mask.  The variables below describe the phase in progress.
+    const bool has_tree = sc.c == sc.nc - 1;
+    const long long left = sc.P - (long long)sc.c * chunk;
+    const int count_p = left <= 0 ? 0 : (left < chunk ? (int)left : chunk);
+    constexpr int SLOTS_ = DH / 8;
+    bool is_tree = false, codes = false;
+    int count = 0, ntile = 0, spr = SLOTS_;
+    size_t kv_stride = 0, kpiece = 0, tile_step = 0;
+    const uint8_t *kptr = nullptr, *vptr = nullptr;
+    float sl2 = scale_log2e;                       // softmax scale of the phase (times the key scale for codes)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m16 = lane & 15, g4 = lane >> 4;
-    const bool is_tree = sc.c == sc.nc - 1;
-    const int count = is_tree ? N : (int)min((long long)chunk, sc.P - (long long)sc.c * chunk);
-    const bool codes = KV8 && !is_tree;            // this chunk's keys/values are 8-bit codes (uniform)
-    const size_t esz = codes ? 1 : 2;
-    const size_t kv_stride = (size_t)Hkv * DH * esz;   // bytes between consecutive keys
-    const size_t first_key = is_tree ? (size_t)sc.b * N : (size_t)(sc.off + (long long)sc.c * chunk);
-    const uint8_t* kbase = reinterpret_cast<const uint8_t*>(is_tree ? (const void*)Kt : Kp) + (first_key * Hkv + kvh) * DH * esz;
-    const uint8_t* vbase = reinterpret_cast<const uint8_t*>(is_tree ? (const void*)Vt : Vp) + (first_key * Hkv + kvh) * DH * esz;
-    if constexpr (KV8) { if (codes) scale_log2e *= k_scale[kvh]; }
-
+    auto set_phase = [&](int phase) {
+        is_tree = phase == 1;
+        count = is_tree ? N : count_p;
+        codes = KV8 && !is_tree;
+        const size_t esz = codes ? 1 : 2;
+        kv_stride = (size_t)Hkv * DH * esz;            // bytes between consecutive keys
+        const size_t first_key = is_tree ? (size_t)sc.b * N : (size_t)(sc.off + (long long)sc.c * chunk);
+        const uint8_t* kbase = reinterpret_cast<const uint8_t*>(is_tree ? (const void*)Kt : Kp) + (first_key * Hkv + kvh) * DH * esz;
+        const uint8_t* vbase = reinterpret_cast<const uint8_t*>(is_tree ? (const void*)Vt : Vp) + (first_key * Hkv + kvh) * DH * esz;
+        sl2 = scale_log2e;
+        if constexpr (KV8) { if (codes) sl2 *= k_scale[kvh]; }
+        // per-thread source pointers of the next tile to fetch, advanced by one tile per fetch (no 64-bit
+        // multiplies in the loop); piece i of a thread is (TA_THREADS / spr) keys after piece i-1
+        spr = codes ? SLOTS_ / 2 : SLOTS_;             // 16-byte pieces per key row in memory
+        kptr = kbase + (size_t)(tid / spr) * kv_stride + (tid % spr) * 16;
+        vptr = vbase + (size_t)(tid / spr) * kv_stride + (tid % spr) * 16;
+        kpiece = (size_t)(TA_THREADS / spr) * kv_stride;
+        tile_step = (size_t)TA_KEYS * kv_stride;
+        ntile = (count + TA_KEYS - 1) / TA_KEYS;
+    };
     // query fragments: lane (m16, g4) holds, for its row, dh elements 32t + 8*g4 .. +7
     u32x4 qf[RBW][DH / 32];
     const unsigned long long* mptr[RBW];          // the row's ancestor bits (tree chunk only; read per tile, not held)
@@ -185,13 +211,6 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     constexpr int NH = KV8 ? NKP / 2 : NKP;            // pieces per register set
     constexpr int DEPTH = RBW == 1 ? 2 : 1;            // bf16 kernels: tiles in flight
     u32x4 krA[NH], vrA[NH], krB[NH], vrB[NH];
-    // per-thread source pointers of the next tile to fetch, advanced by one tile per fetch (no 64-bit
-    // multiplies in the loop); piece i of a thread is (TA_THREADS / spr) keys after piece i-1
-    const int spr = codes ? SLOTS / 2 : SLOTS;         // 16-byte pieces per key row in memory
-    const uint8_t* kptr = kbase + (size_t)(tid / spr) * kv_stride + (tid % spr) * 16;
-    const size_t kpiece = (size_t)(TA_THREADS / spr) * kv_stride;
-    const uint8_t* vptr = vbase + (size_t)(tid / spr) * kv_stride + (tid % spr) * 16;
-    const size_t tile_step = (size_t)TA_KEYS * kv_stride;
     auto advance = [&]() { kptr += tile_step; vptr += tile_step; };
     // pieces I0 .. I0+NH-1 of a bf16 tile
     auto fetch_bf16 = [&](int tile, auto i0c, u32x4 (&kr)[NH], u32x4 (&vr)[NH]) {
@@ -257,7 +276,6 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
             *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + (((c8 ^ v_swz<DH>(key)) << 5) | 16)) = v1;
         }
     };
-    const int ntile = (count + TA_KEYS - 1) / TA_KEYS;
     // the tile staged in LDS (keys tile*64 ..) against the query fragments
     auto compute = [&](int tile) {
         const int key0 = tile * TA_KEYS;
@@ -296,14 +314,14 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
             mx = max_over_lane_groups(mx);
             // scores stay raw: the (positive) scale and the running maximum go into one fma per element;
             // the arguments of exp2 are <= 0, so the bare v_exp_f32 (tiny results flush to 0) is enough
-            const float m_new = fmaxf(m_run[rb], mx * scale_log2e);
+            const float m_new = fmaxf(m_run[rb], mx * sl2);
             const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);
             m_run[rb] = m_new;
 #pragma unroll
             for (int kq = 0; kq < KBH; ++kq) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[kq][i], scale_log2e, -m_new));
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[kq][i], sl2, -m_new));
                     pf[rb][kq >> 1][(kq & 1) * 4 + i] = (__bf16)p;
                 }
             }
@@ -372,67 +390,82 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                 accl[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones_row), pf[rb][uq], accl[rb], 0, 0, 0);
     };
     using std::integral_constant;
-    if (KV8 && codes) {
-        if constexpr (KV8) {
-            if (ntile > 0) { fetch_codes(0, krA, vrA); advance(); }
-            if (ntile > 1) { fetch_codes(1, krB, vrB); advance(); }
-            load_queries();
-            for (int tile = 0; tile < ntile; tile += 2) {
-                __syncthreads();                       // previous tile fully consumed
-                stage_codes(krA, vrA);
-                __syncthreads();
-                if (tile + 2 < ntile) { fetch_codes(tile + 2, krA, vrA); advance(); }
-                compute(tile);
-                if (tile + 1 < ntile) {
+    bool q_loaded = false;
+#pragma unroll
+    for (int phase = 0; phase < 2; ++phase) {
+        if (phase == 0 ? count_p == 0 : !has_tree) continue;
+        set_phase(phase);
+        if (KV8 && codes) {
+            if constexpr (KV8) {
+                if (ntile > 0) { fetch_codes(0, krA, vrA); advance(); }
+                if (ntile > 1) { fetch_codes(1, krB, vrB); advance(); }
+                if (!q_loaded) { load_queries(); q_loaded = true; }
+                for (int tile = 0; tile < ntile; tile += 2) {
+                    __syncthreads();                       // previous tile fully consumed
+                    stage_codes(krA, vrA);
                     __syncthreads();
-                    stage_codes(krB, vrB);
-                    __syncthreads();
-                    if (tile + 3 < ntile) { fetch_codes(tile + 3, krB, vrB); advance(); }
-                    compute(tile + 1);
+                    if (tile + 2 < ntile) { fetch_codes(tile + 2, krA, vrA); advance(); }
+                    compute(tile);
+                    if (tile + 1 < ntile) {
+                        __syncthreads();
+                        stage_codes(krB, vrB);
+                        __syncthreads();
+                        if (tile + 3 < ntile) { fetch_codes(tile + 3, krB, vrB); advance(); }
+                        compute(tile + 1);
+                    }
                 }
             }
-        }
-    } else if constexpr (KV8) {                        // bf16 tree chunk of an 8-bit kernel: one tile across both sets
-        if (ntile > 0) { fetch_bf16(0, integral_constant<int, 0>{}, krA, vrA); fetch_bf16(0, integral_constant<int, NH>{}, krB, vrB); advance(); }
-        load_queries();
-        for (int tile = 0; tile < ntile; ++tile) {
-            __syncthreads();
-            stage_bf16(integral_constant<int, 0>{}, krA, vrA);
-            stage_bf16(integral_constant<int, NH>{}, krB, vrB);
-            __syncthreads();
-            if (tile + 1 < ntile) {
-                fetch_bf16(tile + 1, integral_constant<int, 0>{}, krA, vrA);
-                fetch_bf16(tile + 1, integral_constant<int, NH>{}, krB, vrB);
-                advance();
-            }
-            compute(tile);
-        }
-    } else {
-        constexpr integral_constant<int, 0> z{};
-        auto do_tile = [&](int tile, u32x4 (&kr)[NH], u32x4 (&vr)[NH]) {
-            __syncthreads();                           // previous tile fully consumed
-            stage_bf16(z, kr, vr);
-            __syncthreads();
-            if (tile + DEPTH < ntile) { fetch_bf16(tile + DEPTH, z, kr, vr); advance(); }
-            compute(tile);
-        };
-        if (ntile > 0) { fetch_bf16(0, z, krA, vrA); advance(); }
-        if constexpr (DEPTH == 2) {
-            if (ntile > 1) { fetch_bf16(1, z, krB, vrB); advance(); }
-            load_queries();
-            for (int tile = 0; tile < ntile; tile += 2) {
-                do_tile(tile, krA, vrA);
-                if (tile + 1 < ntile) do_tile(tile + 1, krB, vrB);
+        } else if constexpr (KV8) {                        // bf16 tree chunk of an 8-bit kernel: one tile across both sets
+            if (ntile > 0) { fetch_bf16(0, integral_constant<int, 0>{}, krA, vrA); fetch_bf16(0, integral_constant<int, NH>{}, krB, vrB); advance(); }
+            if (!q_loaded) { load_queries(); q_loaded = true; }
+            for (int tile = 0; tile < ntile; ++tile) {
+                __syncthreads();
+                stage_bf16(integral_constant<int, 0>{}, krA, vrA);
+                stage_bf16(integral_constant<int, NH>{}, krB, vrB);
+                __syncthreads();
+                if (tile + 1 < ntile) {
+                    fetch_bf16(tile + 1, integral_constant<int, 0>{}, krA, vrA);
+                    fetch_bf16(tile + 1, integral_constant<int, NH>{}, krB, vrB);
+                    advance();
+                }
+                compute(tile);
             }
         } else {
-            load_queries();
-            for (int tile = 0; tile < ntile; ++tile) do_tile(tile, krA, vrA);
+            constexpr integral_constant<int, 0> z{};
+            auto do_tile = [&](int tile, u32x4 (&kr)[NH], u32x4 (&vr)[NH]) {
+                __syncthreads();                           // previous tile fully consumed
+                stage_bf16(z, kr, vr);
+                __syncthreads();
+                if (tile + DEPTH < ntile) { fetch_bf16(tile + DEPTH, z, kr, vr); advance(); }
+                compute(tile);
+            };
+            if (ntile > 0) { fetch_bf16(0, z, krA, vrA); advance(); }
+            if constexpr (DEPTH == 2) {
+                if (ntile > 1) { fetch_bf16(1, z, krB, vrB); advance(); }
+                if (!q_loaded) { load_queries(); q_loaded = true; }
+                for (int tile = 0; tile < ntile; tile += 2) {
+                    do_tile(tile, krA, vrA);
+                    if (tile + 1 < ntile) do_tile(tile + 1, krB, vrB);
+                }
+            } else {
+                if (!q_loaded) { load_queries(); q_loaded = true; }
+                for (int tile = 0; tile < ntile; ++tile) do_tile(tile, krA, vrA);
+            }
+        }
+
+        if constexpr (KV8) {
+            if (codes) {                               // the value scale of the codes, before bf16 tree values are added
+                const float vs = v_scale[kvh];
+#pragma unroll
+                for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+                    for (int db = 0; db < DH / 16; ++db) acc[rb][db] *= vs;
+            }
         }
     }
+    if (!q_loaded) load_queries();                     // (every chunk has keys; the row numbers are needed below)
 
     // partial results of this chunk: un-normalised O (lane holds dh db*16 + 4*g4 + i of its row), max, sum
-    float o_scale = 1.f;
-    if constexpr (KV8) { if (codes) o_scale = v_scale[kvh]; }
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
         const float l = accl[rb][0];                // valid in the lanes that write it (g4 == 0)
@@ -440,7 +473,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
             const size_t prow = ((size_t)flat * Hkv + kvh) * rows_pad + rho[rb];
 #pragma unroll
             for (int db = 0; db < DH / 16; ++db)
-                *reinterpret_cast<floatx4*>(part_o + prow * DH + db * 16 + g4 * 4) = KV8 ? acc[rb][db] * o_scale : acc[rb][db];
+                *reinterpret_cast<floatx4*>(part_o + prow * DH + db * 16 + g4 * 4) = acc[rb][db];
             if (g4 == 0) { part_ml[prow * 2] = m_run[rb]; part_ml[prow * 2 + 1] = l; }
         }
     }
@@ -580,18 +613,19 @@ static AttnPlan attn_plan(const eagle2_cfg* cfg, const eagle2_attn_cfg* a, int n
     p.bm = 64 * p.rbw;                                 // query rows per workgroup
     p.nmblk = (rows + p.bm - 1) / p.bm;
     p.rows_pad = p.nmblk * p.bm;
-    // One resident round of workgroups (two per compute unit) when the prefix is short enough.
-    // Each sequence also has its tree chunk; at least two tiles per chunk.
+    // One resident round of workgroups (two per compute unit) when the prefix is short enough; at
+    // least two tiles per chunk.  (A sequence's tree keys ride with its last chunk.)
     const long long wg_per_chunk = (long long)a->n_kv_heads * p.nmblk;
     const long long target = (long long)device_cu_count() * 2;
-    long long budget = target / wg_per_chunk - cfg->batch;
+    // sum over sequences of ceil(P_b / chunk) is at most total / chunk + batch (exactly ceil for one sequence)
+    long long budget = target / wg_per_chunk - (cfg->batch > 1 ? cfg->batch : 0);
     if (budget < 1) budget = 1;
     long long want = (a->total_prefix + budget - 1) / budget;
     want = (want + TA_KEYS - 1) / TA_KEYS * TA_KEYS;
     if (want < 2 * TA_KEYS) want = 2 * TA_KEYS;
     if (want > 2048) want = 2048;                      // bounded chunks keep ragged batches balanced
     p.chunk = (int)want;
-    p.max_chunks = (int)(a->total_prefix / p.chunk) + 2 * cfg->batch;
+    p.max_chunks = (int)(a->total_prefix / p.chunk) + cfg->batch;
     p.o_bytes = round_up((size_t)p.max_chunks * a->n_kv_heads * p.rows_pad * a->head_dim * sizeof(float), 256);
     p.total = p.o_bytes + round_up((size_t)p.max_chunks * a->n_kv_heads * p.rows_pad * 2 * sizeof(float), 256);
     return p;
