@@ -1,9 +1,9 @@
 // Tree attention of the verification pass (Section 4.2 of the EAGLE-2 paper: every tree
 // row sees the whole KV prefix plus exactly its ancestors and itself among the tree keys).
 //
-// bf16 path: split-KV attention on the matrix cores.  The keys of a sequence are cut into
-// chunks (prefix chunks of `chunk` keys, plus one chunk holding the N tree keys); a
-// workgroup handles one chunk for one KV head and one block of query rows.  All
+// bf16 path: split-KV attention on the matrix cores.  The prefix keys of a sequence are cut
+// into chunks of `chunk` keys; a workgroup handles one chunk for one KV head and one block of
+// query rows, and the workgroups of a sequence's last chunk go on to its N tree keys.  All
 // Hq/Hkv * N query rows of a KV head share each K/V tile.  Both products are computed
 // transposed so that every lane keeps a single query row:
 //     S^T = K . Q^T   (A = K tile from LDS, B = Q fragments held in registers)
