@@ -109,12 +109,20 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     // of K/V in flight.  Two blocks (wide; every K/V fragment feeds two MFMAs and a tile is staged
     // once per 128 rows): to fit two resident waves per SIMD the query fragments are parked in LDS
     // and one tile is in flight; pays when a KV head has more than 256 query rows.
+    // The wide bf16 variant loads its K/V tiles straight from global memory into LDS (DIRECT): no staging
+    // registers and no LDS writes by the waves, two LDS tiles per tensor used alternately, one barrier per
+    // tile, and the query fragments fit in registers again.
     constexpr int SLOTS = DH / 8;                  // 16-byte slots per K row
     constexpr int BM = 64 * RBW;                   // query rows per workgroup
-    __shared__ __align__(16) uint8_t s_k[TA_KEYS * DH * 2];
-    __shared__ __align__(16) uint8_t s_v[TA_KEYS * DH * 2];
-    // wide variant: the query fragments live in LDS (row-major, slots swizzled like K) instead of registers
-    __shared__ __align__(16) uint8_t s_q[RBW == 2 ? BM * DH * 2 : 16];
+    constexpr bool DIRECT = RBW == 2 && !KV8;
+    constexpr int TILE_BYTES = TA_KEYS * DH * 2;
+    constexpr int NBUF = DIRECT ? 2 : 1;
+    // wide 8-bit variant: the query fragments live in LDS (row-major, slots swizzled like K) instead of registers
+    constexpr int Q_BYTES = (RBW == 2 && !DIRECT) ? BM * DH * 2 : 0;
+    __shared__ __align__(16) uint8_t s_all[2 * NBUF * TILE_BYTES + Q_BYTES];
+    uint8_t* const s_k = s_all;
+    uint8_t* const s_v = s_all + NBUF * TILE_BYTES;
+    uint8_t* const s_q = s_all + 2 * NBUF * TILE_BYTES;
 
     SeqChunk sc;
     // Workgroups start in linear order (x fastest) and are dealt round-robin to the 8 XCDs.  The
@@ -160,6 +168,17 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         spr = codes ? SLOTS_ / 2 : SLOTS_;             // 16-byte pieces per key row in memory
         kptr = kbase + (size_t)(tid / spr) * kv_stride + (tid % spr) * 16;
         vptr = vbase + (size_t)(tid / spr) * kv_stride + (tid % spr) * 16;
+        if constexpr (DIRECT) {
+            // A wave's load instruction fills 1 KB of LDS, lane l the 16 bytes at 16 l: lane (r, p) = (l / SLOTS,
+            // l % SLOTS) owns position p of a key row and fetches the source slot the swizzle puts there.
+            // The row's swizzle depends on the key index modulo 16 (8, 4) only, so it is the same for all of a
+            // lane's rows, which are 4 * RPI keys apart.
+            constexpr int RPI = 64 / SLOTS_;
+            const int lr = w * RPI + lane / SLOTS_, pos = lane % SLOTS_;
+            const int ck = pos ^ k_swz<DH>(lr), cv = (((pos >> 1) ^ v_swz<DH>(lr)) << 1) | (pos & 1);
+            kptr = kbase + (size_t)lr * kv_stride + ck * 16;
+            vptr = vbase + (size_t)lr * kv_stride + cv * 16;
+        }
         kpiece = (size_t)(TA_THREADS / spr) * kv_stride;
         tile_step = (size_t)TA_KEYS * kv_stride;
         ntile = (count + TA_KEYS - 1) / TA_KEYS;
@@ -180,7 +199,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         for (int t = 0; t < DH / 32; ++t)
             qf[rb][t] = ok ? *reinterpret_cast<const u32x4*>(qrow + t * 32 + g4 * 8) : u32x4{0u, 0u, 0u, 0u};
         mptr[rb] = ok ? mask_bits + ((size_t)sc.b * N + n) * words : nullptr;
-        if constexpr (RBW == 2) {                      // park the fragments in LDS; the same lane reads them back
+        if constexpr (RBW == 2 && !DIRECT) {           // park the fragments in LDS; the same lane reads them back
 #pragma unroll
             for (int t = 0; t < DH / 32; ++t)
                 *reinterpret_cast<u32x4*>(s_q + ((w * RBW + rb) * 16 + m16) * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>((w * RBW + rb) * 16 + m16)) << 4)) = qf[rb][t];
@@ -245,6 +264,34 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
             *reinterpret_cast<u32x4*>(s_v + key * (DH * 2) + ((((c >> 1) ^ v_swz<DH>(key)) << 5) | ((c & 1) << 4))) = vr[i];
         }
     };
+    // DIRECT: tile -> LDS buffer `buf` without passing through registers.  Keys beyond the phase's count
+    // re-read its last key (their scores are masked; a finite value keeps 0 * v finite).
+    auto issue_direct = [&](int tile, int buf) {
+        constexpr int RPI = 64 / SLOTS, KSTEP = 4 * RPI, NI = TA_KEYS / KSTEP;
+        typedef __attribute__((address_space(1))) const void* gptr;
+        typedef __attribute__((address_space(3))) void* lptr;
+        const int key0 = tile * TA_KEYS;
+        uint8_t* dk = s_k + buf * TILE_BYTES + w * 1024;
+        uint8_t* dv = s_v + buf * TILE_BYTES + w * 1024;
+        if (key0 + TA_KEYS <= count) {                 // full tile (uniform)
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+                __builtin_amdgcn_global_load_lds((gptr)(kptr + (size_t)i * KSTEP * kv_stride), (lptr)(dk + i * 4096), 16, 0, 0);
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+                __builtin_amdgcn_global_load_lds((gptr)(vptr + (size_t)i * KSTEP * kv_stride), (lptr)(dv + i * 4096), 16, 0, 0);
+        } else {
+            const int lr = w * RPI + lane / SLOTS, lim = count - 1 - key0;   // lim >= 0: the tile has a key
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int keyi = i * KSTEP + lr;
+                const long long d = (long long)((keyi <= lim ? keyi : lim) - lr) * (long long)kv_stride;
+                __builtin_amdgcn_global_load_lds((gptr)(kptr + d), (lptr)(dk + i * 4096), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr)(vptr + d), (lptr)(dv + i * 4096), 16, 0, 0);
+            }
+        }
+        advance();
+    };
     // a tile of codes: NKP / 2 pieces of 16 codes per thread
     auto fetch_codes = [&](int tile, u32x4 (&kr)[NH], u32x4 (&vr)[NH]) {
         const int key0 = tile * TA_KEYS;
@@ -277,8 +324,10 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         }
     };
     // the tile staged in LDS (keys tile*64 ..) against the query fragments
-    auto compute = [&](int tile) {
+    auto compute = [&](int tile, int buf = 0) {
         const int key0 = tile * TA_KEYS;
+        const uint8_t* const sk = s_k + buf * TILE_BYTES;
+        const uint8_t* const sv_ = s_v + buf * TILE_BYTES;
         constexpr int KBH = TA_KEYS / 16, hh = 0;      // 16-key blocks of the tile
         // S^T = K Q^T : s[rb][kq][i] = score(query row of this lane, key kb*16 + 4*g4 + i), kb = hh*KBH + kq
         floatx4 s[RBW][KBH];
@@ -286,6 +335,30 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
             for (int kq = 0; kq < KBH; ++kq) s[rb][kq] = floatx4{0.f, 0.f, 0.f, 0.f};
+        auto k_frag = [&](int t, int kq) -> u32x4 {
+            const int row = (hh * KBH + kq) * 16 + m16;
+            return *reinterpret_cast<const u32x4*>(sk + row * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>(row)) << 4));
+        };
+        if constexpr (DIRECT) {
+            // the K fragments of step t+1 are read from LDS while step t is multiplied (two register sets)
+            u32x4 kf[2][KBH];
+#pragma unroll
+            for (int kq = 0; kq < KBH; ++kq) kf[0][kq] = k_frag(0, kq);
+            __builtin_amdgcn_sched_group_barrier(0x100, KBH, 0);
+#pragma unroll
+            for (int t = 0; t < DH / 32; ++t) {
+#pragma unroll
+                for (int kq = 0; kq < KBH; ++kq) {
+                    if (t + 1 < DH / 32) kf[(t + 1) & 1][kq] = k_frag(t + 1, kq);
+#pragma unroll
+                    for (int rb = 0; rb < RBW; ++rb)
+                        s[rb][kq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8, kf[t & 1][kq]), __builtin_bit_cast(bf16x8, qf[rb][t]), s[rb][kq], 0, 0, 0);
+                    if (t + 1 < DH / 32) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one LDS read ...
+                    __builtin_amdgcn_sched_group_barrier(0x008, RBW, 0);                        // ... then the block's MFMAs
+                }
+            }
+        } else {
 #pragma unroll
         for (int t = 0; t < DH / 32; ++t) {            // t outside: consecutive MFMAs go to different accumulators
             u32x4 qv[RBW];
@@ -298,13 +371,13 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
             }
 #pragma unroll
             for (int kq = 0; kq < KBH; ++kq) {
-                const int row = (hh * KBH + kq) * 16 + m16;
-                const u32x4 kf = *reinterpret_cast<const u32x4*>(s_k + row * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>(row)) << 4));
+                const u32x4 kf = k_frag(t, kq);
 #pragma unroll
                 for (int rb = 0; rb < RBW; ++rb)
                     s[rb][kq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                         __builtin_bit_cast(bf16x8, kf), __builtin_bit_cast(bf16x8, qv[rb]), s[rb][kq], 0, 0, 0);
             }
+        }
         }
 
         bf16x8 pf[RBW][KBH / 2];
@@ -364,22 +437,46 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         }
 
         // O^T += V^T P^T : keys of MFMA u for lane group g4 are {32u + 4g4 + i} and {32u + 16 + 4g4 + i}
+        auto v_frag = [&](int db, int uq) -> u32x4 {
+            const int u = hh * (KBH / 2) + uq;
+            // lane (m16, g4) passes key row 32u (+16) + 4*g4 + m16/4, dh db*16 + 4*(m16%4) .. +3 and
+            // receives dh db*16 + m16 of keys 32u (+16) + 4*g4 + i
+            const int ka = 32 * u + 4 * g4 + (m16 >> 2), kb2 = ka + 16;
+            const u32x2 va = lds_read_tr16(sv_ + ka * (DH * 2) + (((db ^ v_swz<DH>(ka)) << 5) | ((m16 & 3) << 3)));
+            const u32x2 vb = lds_read_tr16(sv_ + kb2 * (DH * 2) + (((db ^ v_swz<DH>(kb2)) << 5) | ((m16 & 3) << 3)));
+            return u32x4{va[0], va[1], vb[0], vb[1]};
+        };
+        if constexpr (DIRECT) {
+            // the V fragments of block db+1 are read from LDS while block db is multiplied
+            u32x4 vf[2][KBH / 2];
+#pragma unroll
+            for (int uq = 0; uq < KBH / 2; ++uq) vf[0][uq] = v_frag(0, uq);
+            __builtin_amdgcn_sched_group_barrier(0x100, KBH, 0);
+#pragma unroll
+            for (int db = 0; db < DH / 16; ++db) {
+#pragma unroll
+                for (int uq = 0; uq < KBH / 2; ++uq) {
+                    if (db + 1 < DH / 16) vf[(db + 1) & 1][uq] = v_frag(db + 1, uq);
+#pragma unroll
+                    for (int rb = 0; rb < RBW; ++rb)
+                        acc[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8, vf[db & 1][uq]), pf[rb][uq], acc[rb][db], 0, 0, 0);
+                    if (db + 1 < DH / 16) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, RBW, 0);
+                }
+            }
+        } else {
 #pragma unroll
         for (int db = 0; db < DH / 16; ++db) {
 #pragma unroll
             for (int uq = 0; uq < KBH / 2; ++uq) {
-                const int u = hh * (KBH / 2) + uq;
-                // lane (m16, g4) passes key row 32u (+16) + 4*g4 + m16/4, dh db*16 + 4*(m16%4) .. +3 and
-                // receives dh db*16 + m16 of keys 32u (+16) + 4*g4 + i
-                const int ka = 32 * u + 4 * g4 + (m16 >> 2), kb2 = ka + 16;
-                const u32x2 va = lds_read_tr16(s_v + ka * (DH * 2) + (((db ^ v_swz<DH>(ka)) << 5) | ((m16 & 3) << 3)));
-                const u32x2 vb = lds_read_tr16(s_v + kb2 * (DH * 2) + (((db ^ v_swz<DH>(kb2)) << 5) | ((m16 & 3) << 3)));
-                const u32x4 vf = {va[0], va[1], vb[0], vb[1]};
+                const u32x4 vf = v_frag(db, uq);
 #pragma unroll
                 for (int rb = 0; rb < RBW; ++rb)
                     acc[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                         __builtin_bit_cast(bf16x8, vf), pf[rb][uq], acc[rb][db], 0, 0, 0);
             }
+        }
         }
         // the row sums of P come out of the same product with a row of ones in place of a V^T row: the
         // normaliser is the sum of exactly the rounded probabilities the numerator used
@@ -391,6 +488,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     };
     using std::integral_constant;
     bool q_loaded = false;
+    int bufi = 0;                                      // DIRECT: LDS tile the next first fetch of a phase goes to
 #pragma unroll
     for (int phase = 0; phase < 2; ++phase) {
         if (phase == 0 ? count_p == 0 : !has_tree) continue;
@@ -414,6 +512,20 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                         compute(tile + 1);
                     }
                 }
+            }
+        } else if constexpr (DIRECT) {
+            // Tile t+1 is on its way into one LDS buffer while tile t is multiplied out of the other.  The
+            // barrier of tile t says that every wave's part of tile t has landed and that every wave is done
+            // with tile t-1, whose buffer the loads issued right after it overwrite.  A phase's first loads go
+            // to the buffer the last-but-one product used, which every wave left before the last barrier.
+            issue_direct(0, bufi);
+            if (!q_loaded) { load_queries(); q_loaded = true; }
+            for (int tile = 0; tile < ntile; ++tile) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's loads into LDS are complete
+                __syncthreads();
+                if (tile + 1 < ntile) issue_direct(tile + 1, bufi ^ 1);
+                compute(tile, bufi);
+                bufi ^= 1;
             }
         } else if constexpr (KV8) {                        // bf16 tree chunk of an 8-bit kernel: one tile across both sets
             if (ntile > 0) { fetch_bf16(0, integral_constant<int, 0>{}, krA, vrA); fetch_bf16(0, integral_constant<int, NH>{}, krB, vrB); advance(); }
