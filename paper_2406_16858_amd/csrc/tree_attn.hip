@@ -150,7 +150,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     size_t kv_stride = 0, kpiece = 0, tile_step = 0;
     const uint8_t *kptr = nullptr, *vptr = nullptr;
     float sl2 = scale_log2e;                       // softmax scale of the phase (times the key scale for codes)
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);   // (wave-uniform: a scalar)
     const int m16 = lane & 15, g4 = lane >> 4;
     auto set_phase = [&](int phase) {
         is_tree = phase == 1;
@@ -210,12 +210,18 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     floatx4 acc[RBW][DH / 16];
     floatx4 accl[RBW];                            // element 0 of lanes g4 == 0: the row's running sum of P
     float m_run[RBW];
+    // DIRECT: the reference value the exp2 arguments are taken against (m_run, or 0 while the row has
+    // seen no key); it follows the running maximum only when a score gets REF_SLACK above it
+    float m_eff[RBW], c_raw[RBW];
+    constexpr float REF_SLACK = 8.f;
     // A operand whose row 0 is all ones (bf16 1.0 = 0x3f80) and whose other rows are zero
     const unsigned one2 = m16 == 0 ? 0x3f803f80u : 0u;
     const u32x4 ones_row = {one2, one2, one2, one2};
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
         m_run[rb] = NEG_BIG;
+        m_eff[rb] = 0.f;
+        c_raw[rb] = 0.f;
         accl[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int db = 0; db < DH / 16; ++db) acc[rb][db] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -330,11 +336,12 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         const uint8_t* const sv_ = s_v + buf * TILE_BYTES;
         constexpr int KBH = TA_KEYS / 16, hh = 0;      // 16-key blocks of the tile
         // S^T = K Q^T : s[rb][kq][i] = score(query row of this lane, key kb*16 + 4*g4 + i), kb = hh*KBH + kq
+        // (DIRECT: the accumulators start at minus the row's reference value, in units of raw scores)
         floatx4 s[RBW][KBH];
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
-            for (int kq = 0; kq < KBH; ++kq) s[rb][kq] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int kq = 0; kq < KBH; ++kq) s[rb][kq] = DIRECT ? floatx4{-c_raw[rb], -c_raw[rb], -c_raw[rb], -c_raw[rb]} : floatx4{0.f, 0.f, 0.f, 0.f};
         auto k_frag = [&](int t, int kq) -> u32x4 {
             const int row = (hh * KBH + kq) * 16 + m16;
             return *reinterpret_cast<const u32x4*>(sk + row * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>(row)) << 4));
@@ -404,6 +411,59 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                 accl[rb] *= alpha;
             }
         };
+        if constexpr (DIRECT) {
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) {
+            // s holds raw score - c_raw, c_raw = the row's reference in raw units.  While no score of the wave
+            // climbs more than REF_SLACK (after scaling) above its row's reference (and every row has one) the
+            // probabilities are exp2(s * scale): no maximum across lanes, no rescaling.  They may then
+            // exceed 1 (by at most 2^REF_SLACK), which float32 sums and bf16 products carry without loss.
+            float mx = s[rb][0][0];
+#pragma unroll
+            for (int kq = 0; kq < KBH; ++kq)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[rb][kq][i]);
+            const bool plain = !is_tree && key0 + TA_KEYS <= count;     // uniform: every key of the tile is visible
+            if (plain && !__any(mx * sl2 > REF_SLACK || m_run[rb] <= NEG_BIG)) {
+#pragma unroll
+                for (int kq = 0; kq < KBH; ++kq)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        pf[rb][kq >> 1][(kq & 1) * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[rb][kq][i] * sl2);
+            } else {
+                // new reference: the row's running maximum (scaled scores = s * scale + m_eff)
+                const unsigned long long mword = (is_tree && mptr[rb] != nullptr && (key0 >> 6) < words) ? mptr[rb][key0 >> 6] : 0ull;
+                floatx4 sm[KBH];
+                float mt = -INFINITY;
+#pragma unroll
+                for (int kq = 0; kq < KBH; ++kq) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int key = key0 + (hh * KBH + kq) * 16 + g4 * 4 + i;
+                        bool vis = key < count;
+                        if (is_tree) vis = vis && ((mword >> (key & 63)) & 1ull);
+                        const float v = vis ? __builtin_fmaf(s[rb][kq][i], sl2, m_eff[rb]) : -INFINITY;
+                        sm[kq][i] = v;
+                        mt = fmaxf(mt, v);
+                    }
+                }
+                mt = max_over_lane_groups(mt);
+                const float m_new = fmaxf(m_run[rb], mt);      // stays NEG_BIG while the row has seen no key
+                const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);
+                m_run[rb] = m_new;
+                m_eff[rb] = m_new <= NEG_BIG ? 0.f : m_new;
+                c_raw[rb] = m_eff[rb] / sl2;
+#pragma unroll
+                for (int kq = 0; kq < KBH; ++kq)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        pf[rb][kq >> 1][(kq & 1) * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(sm[kq][i] - m_new);
+#pragma unroll
+                for (int db = 0; db < DH / 16; ++db) acc[rb][db] *= alpha;
+                accl[rb] *= alpha;
+            }
+        }
+        } else {
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb) {
             float mx = NEG_BIG;
@@ -434,6 +494,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                 }
                 finish_block(rb, mx, sm);
             }
+        }
         }
 
         // O^T += V^T P^T : keys of MFMA u for lane group g4 are {32u + 4g4 + i} and {32u + 16 + 4g4 + i}
