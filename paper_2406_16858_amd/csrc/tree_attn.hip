@@ -152,6 +152,13 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     float sl2 = scale_log2e;                       // softmax scale of the phase (times the key scale for codes)
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);   // (wave-uniform: a scalar)
     const int m16 = lane & 15, g4 = lane >> 4;
+    // The reference value the exp2 arguments are taken against (m_run, or 0 while the row has seen no
+    // key; c_raw: the same in units of the phase's raw scores); it follows the running maximum only when a
+    // score gets REF_SLACK above it.
+    float m_eff[RBW], c_raw[RBW];
+    constexpr float REF_SLACK = 8.f;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) { m_eff[rb] = 0.f; c_raw[rb] = 0.f; }
     auto set_phase = [&](int phase) {
         is_tree = phase == 1;
         count = is_tree ? N : count_p;
@@ -163,6 +170,8 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         const uint8_t* vbase = reinterpret_cast<const uint8_t*>(is_tree ? (const void*)Vt : Vp) + (first_key * Hkv + kvh) * DH * esz;
         sl2 = scale_log2e;
         if constexpr (KV8) { if (codes) sl2 *= k_scale[kvh]; }
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) c_raw[rb] = m_eff[rb] / sl2;         // the raw unit changes with the phase's scale
         // per-thread source pointers of the next tile to fetch, advanced by one tile per fetch (no 64-bit
         // multiplies in the loop); piece i of a thread is (TA_THREADS / spr) keys after piece i-1
         spr = codes ? SLOTS_ / 2 : SLOTS_;             // 16-byte pieces per key row in memory
@@ -210,18 +219,12 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     floatx4 acc[RBW][DH / 16];
     floatx4 accl[RBW];                            // element 0 of lanes g4 == 0: the row's running sum of P
     float m_run[RBW];
-    // DIRECT: the reference value the exp2 arguments are taken against (m_run, or 0 while the row has
-    // seen no key); it follows the running maximum only when a score gets REF_SLACK above it
-    float m_eff[RBW], c_raw[RBW];
-    constexpr float REF_SLACK = 8.f;
     // A operand whose row 0 is all ones (bf16 1.0 = 0x3f80) and whose other rows are zero
     const unsigned one2 = m16 == 0 ? 0x3f803f80u : 0u;
     const u32x4 ones_row = {one2, one2, one2, one2};
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
         m_run[rb] = NEG_BIG;
-        m_eff[rb] = 0.f;
-        c_raw[rb] = 0.f;
         accl[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int db = 0; db < DH / 16; ++db) acc[rb][db] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -336,12 +339,12 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         const uint8_t* const sv_ = s_v + buf * TILE_BYTES;
         constexpr int KBH = TA_KEYS / 16, hh = 0;      // 16-key blocks of the tile
         // S^T = K Q^T : s[rb][kq][i] = score(query row of this lane, key kb*16 + 4*g4 + i), kb = hh*KBH + kq
-        // (DIRECT: the accumulators start at minus the row's reference value, in units of raw scores)
+        // (the accumulators start at minus the row's reference value, in units of raw scores)
         floatx4 s[RBW][KBH];
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
-            for (int kq = 0; kq < KBH; ++kq) s[rb][kq] = DIRECT ? floatx4{-c_raw[rb], -c_raw[rb], -c_raw[rb], -c_raw[rb]} : floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int kq = 0; kq < KBH; ++kq) s[rb][kq] = floatx4{-c_raw[rb], -c_raw[rb], -c_raw[rb], -c_raw[rb]};
         auto k_frag = [&](int t, int kq) -> u32x4 {
             const int row = (hh * KBH + kq) * 16 + m16;
             return *reinterpret_cast<const u32x4*>(sk + row * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>(row)) << 4));
@@ -388,30 +391,6 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         }
 
         bf16x8 pf[RBW][KBH / 2];
-        // from the block's score maximum to its probabilities (called from both branches below, so that
-        // neither has to move the scores into the other's registers)
-        auto finish_block = [&](int rb, float mx, const floatx4 (&sv)[KBH]) {
-            mx = max_over_lane_groups(mx);
-            // scores stay raw: the (positive) scale and the running maximum go into one fma per element;
-            // the arguments of exp2 are <= 0, so the bare v_exp_f32 (tiny results flush to 0) is enough
-            const float m_new = fmaxf(m_run[rb], mx * sl2);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);
-            m_run[rb] = m_new;
-#pragma unroll
-            for (int kq = 0; kq < KBH; ++kq) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[kq][i], sl2, -m_new));
-                    pf[rb][kq >> 1][(kq & 1) * 4 + i] = (__bf16)p;
-                }
-            }
-            if (__any(alpha != 1.f)) {                 // the running maximum rarely moves after the first tiles
-#pragma unroll
-                for (int db = 0; db < DH / 16; ++db) acc[rb][db] *= alpha;
-                accl[rb] *= alpha;
-            }
-        };
-        if constexpr (DIRECT) {
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb) {
             // s holds raw score - c_raw, c_raw = the row's reference in raw units.  While no score of the wave
@@ -462,39 +441,6 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                 for (int db = 0; db < DH / 16; ++db) acc[rb][db] *= alpha;
                 accl[rb] *= alpha;
             }
-        }
-        } else {
-#pragma unroll
-        for (int rb = 0; rb < RBW; ++rb) {
-            float mx = NEG_BIG;
-            if (!is_tree && key0 + TA_KEYS <= count) { // full prefix tile (uniform): every key is visible
-#pragma unroll
-                for (int kq = 0; kq < KBH; ++kq) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        mx = fmaxf(mx, s[rb][kq][i]);
-                    }
-                }
-                finish_block(rb, mx, s[rb]);
-            } else {
-                // a 64-key tile lies inside one 64-bit word of the row's mask
-                const unsigned long long mword = (is_tree && mptr[rb] != nullptr && (key0 >> 6) < words) ? mptr[rb][key0 >> 6] : 0ull;
-                floatx4 sm[KBH];
-#pragma unroll
-                for (int kq = 0; kq < KBH; ++kq) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int key = key0 + (hh * KBH + kq) * 16 + g4 * 4 + i;
-                        bool vis = key < count;
-                        if (is_tree) vis = vis && ((mword >> (key & 63)) & 1ull);
-                        const float v = vis ? s[rb][kq][i] : -INFINITY;
-                        sm[kq][i] = v;
-                        mx = fmaxf(mx, v);
-                    }
-                }
-                finish_block(rb, mx, sm);
-            }
-        }
         }
 
         // O^T += V^T P^T : keys of MFMA u for lane group g4 are {32u + 4g4 + i} and {32u + 16 + 4g4 + i}
