@@ -11,7 +11,9 @@
 // The output registers of the first product are, lane for lane, the B operand of the
 // second (the contraction index of an MFMA may be permuted freely as long as A and B
 // agree), so P never goes through LDS.  The ancestor bitmask is applied to the tree
-// chunk only.  A second kernel combines the chunks' (max, sum, O) triples.
+// keys only.  The exp2 arguments are taken against a per-row reference that follows the running
+// maximum lazily (see the softmax step in compute); a second kernel combines the chunks'
+// (reference, sum, O) triples.
 // The prefix keys/values may also be 8-bit E4M3 codes with per-head scales (KV8 instantiations).
 //
 // fp32 path: a plain one-query-row-per-workgroup kernel in float32 (small shapes only).
@@ -62,12 +64,25 @@ template <int DH> __device__ __forceinline__ int k_swz(int row) { return DH == 1
 // V rows are cut into 32-byte granules (16 dh: what one PV fragment covers); a row's granules are
 // permuted by its key index so that the four key rows one transpose read touches fall in different banks
 template <int DH> __device__ __forceinline__ int v_swz(int key) { return key & (DH / 16 - 1); }
+// Tells the compiler that a pointer is the same in every lane, so that it stays in scalar registers and a
+// load can take it as its scalar base next to a 32-bit lane offset.
+__device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p) {
+    const unsigned long long u = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)u), hi = __builtin_amdgcn_readfirstlane((unsigned)(u >> 32));
+    return reinterpret_cast<const uint8_t*>(((unsigned long long)hi << 32) | lo);
+}
 // LDS transpose read: within each 16 lanes, lane j passes the address of 4 consecutive 16-bit elements
 // D[j][0..3] and receives D[j/4 + 4i][j%4], i = 0..3
 typedef short short4v __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ u32x2 lds_read_tr16(const uint8_t* p) {
-    const short4v r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)p);
+__device__ __forceinline__ u32x2 lds_read_tr16(unsigned lds_addr) {
+    const short4v r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(size_t)lds_addr);
     return __builtin_bit_cast(u32x2, r);
+}
+__device__ __forceinline__ u32x4 lds_read_b128(unsigned lds_addr) {
+    return *(__attribute__((address_space(3))) const u32x4*)(size_t)lds_addr;
+}
+__device__ __forceinline__ unsigned lds_address(const uint8_t* p) {     // byte address inside the workgroup's LDS
+    return (unsigned)(size_t)(__attribute__((address_space(3))) const uint8_t*)p;
 }
 
 // Maximum over the four lanes m16, m16+16, m16+32, m16+48 (the lanes that share a query row), left in
@@ -106,12 +121,14 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                            int B, int N, int q0, int nq, int Hq, int Hkv, int chunk, int words, int nmblk, int rows_pad,
                            float scale_log2e, float* __restrict__ part_o, float* __restrict__ part_ml) {
     // RBW 16-row query blocks per wave.  One block (narrow): query fragments in registers, two tiles
-    // of K/V in flight.  Two blocks (wide; every K/V fragment feeds two MFMAs and a tile is staged
-    // once per 128 rows): to fit two resident waves per SIMD the query fragments are parked in LDS
-    // and one tile is in flight; pays when a KV head has more than 256 query rows.
-    // The wide bf16 variant loads its K/V tiles straight from global memory into LDS (DIRECT): no staging
-    // registers and no LDS writes by the waves, two LDS tiles per tensor used alternately, one barrier per
-    // tile, and the query fragments fit in registers again.
+    // of K/V in flight in registers, staged through one LDS tile.  Two blocks (wide; every K/V fragment
+    // feeds two MFMAs and a tile is fetched once per 128 rows; pays when a KV head has more than 256
+    // query rows):
+    //  - bf16 prefix (DIRECT): the K/V tiles go straight from global memory into LDS -- no staging
+    //    registers and no LDS writes by the waves, two LDS tiles per tensor used alternately, one barrier
+    //    per tile, query fragments in registers;
+    //  - 8-bit prefix: codes are widened on their way through registers into a single LDS tile; to fit two
+    //    resident waves per SIMD the query fragments are parked in LDS and one tile is in flight.
     constexpr int SLOTS = DH / 8;                  // 16-byte slots per K row
     constexpr int BM = 64 * RBW;                   // query rows per workgroup
     constexpr bool DIRECT = RBW == 2 && !KV8;
@@ -119,7 +136,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     constexpr int NBUF = DIRECT ? 2 : 1;
     // wide 8-bit variant: the query fragments live in LDS (row-major, slots swizzled like K) instead of registers
     constexpr int Q_BYTES = (RBW == 2 && !DIRECT) ? BM * DH * 2 : 0;
-    __shared__ __align__(16) uint8_t s_all[2 * NBUF * TILE_BYTES + Q_BYTES];
+    __shared__ __align__(1024) uint8_t s_all[2 * NBUF * TILE_BYTES + Q_BYTES];   // (fragment addresses are formed with xor: tiles must start on a multiple of 256)
     uint8_t* const s_k = s_all;
     uint8_t* const s_v = s_all + NBUF * TILE_BYTES;
     uint8_t* const s_q = s_all + 2 * NBUF * TILE_BYTES;
@@ -148,10 +165,14 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     bool is_tree = false, codes = false;
     int count = 0, ntile = 0, spr = SLOTS_;
     size_t kv_stride = 0, kpiece = 0, tile_step = 0;
-    const uint8_t *kptr = nullptr, *vptr = nullptr;
+    const uint8_t *kptr = nullptr, *vptr = nullptr;   // DIRECT: uniform pointers to the next tile to fetch
+    unsigned koff = 0, voff = 0;                      // DIRECT: this lane's byte offset inside a tile
     float sl2 = scale_log2e;                       // softmax scale of the phase (times the key scale for codes)
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);   // (wave-uniform: a scalar)
     const int m16 = lane & 15, g4 = lane >> 4;
+    // this lane's byte offsets inside a staged K / V tile for fragment step 0 (see k_frag and v_frag)
+    const unsigned klane = m16 * (DH * 2) + ((g4 ^ k_swz<DH>(m16)) << 4);
+    const unsigned vlane = (4 * g4 + (m16 >> 2)) * (DH * 2) + ((v_swz<DH>(4 * g4 + (m16 >> 2)) << 5) | ((m16 & 3) << 3));
     // The reference value the exp2 arguments are taken against (m_run, or 0 while the row has seen no
     // key; c_raw: the same in units of the phase's raw scores); it follows the running maximum only when a
     // score gets REF_SLACK above it.
@@ -185,8 +206,11 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
             constexpr int RPI = 64 / SLOTS_;
             const int lr = w * RPI + lane / SLOTS_, pos = lane % SLOTS_;
             const int ck = pos ^ k_swz<DH>(lr), cv = (((pos >> 1) ^ v_swz<DH>(lr)) << 1) | (pos & 1);
-            kptr = kbase + (size_t)lr * kv_stride + ck * 16;
-            vptr = vbase + (size_t)lr * kv_stride + cv * 16;
+            // addresses are a wave-uniform tile pointer (scalar registers) plus a 32-bit lane offset
+            koff = (unsigned)lr * (unsigned)kv_stride + ck * 16;
+            voff = (unsigned)lr * (unsigned)kv_stride + cv * 16;
+            kptr = kbase;
+            vptr = vbase;
         }
         kpiece = (size_t)(TA_THREADS / spr) * kv_stride;
         tile_step = (size_t)TA_KEYS * kv_stride;
@@ -285,18 +309,18 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         if (key0 + TA_KEYS <= count) {                 // full tile (uniform)
 #pragma unroll
             for (int i = 0; i < NI; ++i)
-                __builtin_amdgcn_global_load_lds((gptr)(kptr + (size_t)i * KSTEP * kv_stride), (lptr)(dk + i * 4096), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr)(uniform_ptr(kptr + (size_t)i * KSTEP * kv_stride) + koff), (lptr)(dk + i * 4096), 16, 0, 0);
 #pragma unroll
             for (int i = 0; i < NI; ++i)
-                __builtin_amdgcn_global_load_lds((gptr)(vptr + (size_t)i * KSTEP * kv_stride), (lptr)(dv + i * 4096), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr)(uniform_ptr(vptr + (size_t)i * KSTEP * kv_stride) + voff), (lptr)(dv + i * 4096), 16, 0, 0);
         } else {
             const int lr = w * RPI + lane / SLOTS, lim = count - 1 - key0;   // lim >= 0: the tile has a key
 #pragma unroll
             for (int i = 0; i < NI; ++i) {
                 const int keyi = i * KSTEP + lr;
-                const long long d = (long long)((keyi <= lim ? keyi : lim) - lr) * (long long)kv_stride;
-                __builtin_amdgcn_global_load_lds((gptr)(kptr + d), (lptr)(dk + i * 4096), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((gptr)(vptr + d), (lptr)(dv + i * 4096), 16, 0, 0);
+                const unsigned d = (unsigned)((keyi <= lim ? keyi : lim) - lr) * (unsigned)kv_stride;   // (wraps; koff + d >= 0)
+                __builtin_amdgcn_global_load_lds((gptr)(uniform_ptr(kptr) + (koff + d)), (lptr)(dk + i * 4096), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr)(uniform_ptr(vptr) + (voff + d)), (lptr)(dv + i * 4096), 16, 0, 0);
             }
         }
         advance();
@@ -337,18 +361,19 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         const int key0 = tile * TA_KEYS;
         const uint8_t* const sk = s_k + buf * TILE_BYTES;
         const uint8_t* const sv_ = s_v + buf * TILE_BYTES;
-        constexpr int KBH = TA_KEYS / 16, hh = 0;      // 16-key blocks of the tile
-        // S^T = K Q^T : s[rb][kq][i] = score(query row of this lane, key kb*16 + 4*g4 + i), kb = hh*KBH + kq
+        constexpr int KBH = TA_KEYS / 16;              // 16-key blocks of the tile
+        // S^T = K Q^T : s[rb][kq][i] = score(query row of this lane, key kq*16 + 4*g4 + i)
         // (the accumulators start at minus the row's reference value, in units of raw scores)
         floatx4 s[RBW][KBH];
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
             for (int kq = 0; kq < KBH; ++kq) s[rb][kq] = floatx4{-c_raw[rb], -c_raw[rb], -c_raw[rb], -c_raw[rb]};
-        auto k_frag = [&](int t, int kq) -> u32x4 {
-            const int row = (hh * KBH + kq) * 16 + m16;
-            return *reinterpret_cast<const u32x4*>(sk + row * (DH * 2) + (((t * 4 + g4) ^ k_swz<DH>(row)) << 4));
-        };
+        // K fragment (step t, key block kq): row kq*16 + m16, slot (4t + g4) ^ swizzle.  The swizzle is the
+        // same for all of a lane's rows and 4t + g4 = 4t ^ g4, so the address is one lane constant with
+        // t << 6 xor-ed in and the key block as an immediate offset.
+        const unsigned kl = lds_address(sk) + klane;
+        auto k_frag = [&](int t, int kq) -> u32x4 { return lds_read_b128((kl ^ (unsigned)(t << 6)) + kq * 16 * (DH * 2)); };
         if constexpr (DIRECT) {
             // the K fragments of step t+1 are read from LDS while step t is multiplied (two register sets)
             u32x4 kf[2][KBH];
@@ -418,7 +443,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                 for (int kq = 0; kq < KBH; ++kq) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const int key = key0 + (hh * KBH + kq) * 16 + g4 * 4 + i;
+                        const int key = key0 + kq * 16 + g4 * 4 + i;
                         bool vis = key < count;
                         if (is_tree) vis = vis && ((mword >> (key & 63)) & 1ull);
                         const float v = vis ? __builtin_fmaf(s[rb][kq][i], sl2, m_eff[rb]) : -INFINITY;
@@ -444,13 +469,15 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         }
 
         // O^T += V^T P^T : keys of MFMA u for lane group g4 are {32u + 4g4 + i} and {32u + 16 + 4g4 + i}
+        const unsigned vl = lds_address(sv_) + vlane;
         auto v_frag = [&](int db, int uq) -> u32x4 {
-            const int u = hh * (KBH / 2) + uq;
+            const int u = uq;
             // lane (m16, g4) passes key row 32u (+16) + 4*g4 + m16/4, dh db*16 + 4*(m16%4) .. +3 and
             // receives dh db*16 + m16 of keys 32u (+16) + 4*g4 + i
-            const int ka = 32 * u + 4 * g4 + (m16 >> 2), kb2 = ka + 16;
-            const u32x2 va = lds_read_tr16(sv_ + ka * (DH * 2) + (((db ^ v_swz<DH>(ka)) << 5) | ((m16 & 3) << 3)));
-            const u32x2 vb = lds_read_tr16(sv_ + kb2 * (DH * 2) + (((db ^ v_swz<DH>(kb2)) << 5) | ((m16 & 3) << 3)));
+            // (the granule swizzle depends on the key modulo 8 (4) only: one lane constant with db << 5 xor-ed
+            // in, the key block as an immediate offset)
+            const unsigned a = (vl ^ (unsigned)(db << 5)) + 32 * u * (DH * 2);
+            const u32x2 va = lds_read_tr16(a), vb = lds_read_tr16(a + 16 * (DH * 2));
             return u32x4{va[0], va[1], vb[0], vb[1]};
         };
         if constexpr (DIRECT) {
