@@ -167,7 +167,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     size_t kv_stride = 0, kpiece = 0, tile_step = 0;
     const uint8_t *kptr = nullptr, *vptr = nullptr;   // DIRECT: uniform pointers to the next tile to fetch
     unsigned koff = 0, voff = 0;                      // DIRECT: this lane's byte offset inside a tile
-    float sl2 = scale_log2e;                       // softmax scale of the phase (times the key scale for codes)
+    float sl2 = scale_log2e, inv_sl2 = 0.f;        // softmax scale of the phase (times the key scale for codes) and its reciprocal
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);   // (wave-uniform: a scalar)
     const int m16 = lane & 15, g4 = lane >> 4;
     // this lane's byte offsets inside a staged K / V tile for fragment step 0 (see k_frag and v_frag)
@@ -191,8 +191,9 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         const uint8_t* vbase = reinterpret_cast<const uint8_t*>(is_tree ? (const void*)Vt : Vp) + (first_key * Hkv + kvh) * DH * esz;
         sl2 = scale_log2e;
         if constexpr (KV8) { if (codes) sl2 *= k_scale[kvh]; }
+        inv_sl2 = sl2 > 0.f ? 1.f / sl2 : 0.f;         // (a key scale of 0 -- an all-zero head -- leaves every score at 0)
 #pragma unroll
-        for (int rb = 0; rb < RBW; ++rb) c_raw[rb] = m_eff[rb] / sl2;         // the raw unit changes with the phase's scale
+        for (int rb = 0; rb < RBW; ++rb) c_raw[rb] = m_eff[rb] * inv_sl2;     // the raw unit changes with the phase's scale
         // per-thread source pointers of the next tile to fetch, advanced by one tile per fetch (no 64-bit
         // multiplies in the loop); piece i of a thread is (TA_THREADS / spr) keys after piece i-1
         spr = codes ? SLOTS_ / 2 : SLOTS_;             // 16-byte pieces per key row in memory
@@ -456,7 +457,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                 const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);
                 m_run[rb] = m_new;
                 m_eff[rb] = m_new <= NEG_BIG ? 0.f : m_new;
-                c_raw[rb] = m_eff[rb] / sl2;
+                c_raw[rb] = m_eff[rb] * inv_sl2;
 #pragma unroll
                 for (int kq = 0; kq < KBH; ++kq)
 #pragma unroll

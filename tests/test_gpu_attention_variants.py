@@ -45,7 +45,7 @@ def _mask_words(mask):
     return out
 
 
-def _run(cfg, region, fp8=False, key_gain=None, spikes=0, filled=None, seed=0):
+def _run(cfg, region, fp8=False, key_gain=None, spikes=0, filled=None, seed=0, zero_k_scale_head=None):
     """region: allocated prefix rows per sequence; filled: rows in use per sequence (a pre-allocated cache)
     or None; key_gain(t, P) -> factor applied to prefix key t of a P-key prefix; spikes: number of prefix
     keys per sequence replaced by a multiple of one of the sequence's queries (a score far above the rest)."""
@@ -74,6 +74,8 @@ def _run(cfg, region, fp8=False, key_gain=None, spikes=0, filled=None, seed=0):
     plen = None if filled is None else torch.tensor(filled, dtype=torch.int32, device="cuda")
     if fp8:
         K8, V8, ks, vs = wl.make_fp8_prefix(Kp, Vp)
+        if zero_k_scale_head is not None:
+            ks[zero_k_scale_head] = 0.0                # every prefix key of that head reads as zero
         rnd.tree_attn_fp8kv(Q, K8, V8, ks, vs, off, Kt, Vt, O, lse, prefix_len=plen)
         Kd = torch.from_numpy(f8.dequantize(K8.cpu().numpy(), ks.cpu().numpy()))
         Vd = torch.from_numpy(f8.dequantize(V8.cpu().numpy(), vs.cpu().numpy()))
@@ -154,3 +156,11 @@ def test_single_keys_far_above_the_rest(shape, fp8):
     cfg = _cfg(shape, **SHAPES[shape])
     region = [1500, 700, 333][:cfg.batch]
     _run(cfg, region, fp8=fp8, spikes=6, seed=8)
+
+
+@pytest.mark.parametrize("shape", ["narrow_dh128", "wide_dh64"])
+def test_key_scale_of_zero(shape):
+    """An all-zero key head stored with scale 0: its prefix scores are all 0 (uniform weights), the
+    tree keys of the same launch keep their own scale."""
+    cfg = _cfg(shape, **SHAPES[shape])
+    _run(cfg, [700, 130, 64][:cfg.batch], fp8=True, zero_k_scale_head=1, seed=9)
