@@ -17,7 +17,7 @@
 
 namespace eagle2 {
 
-constexpr int AM_THREADS = 256;
+constexpr int AM_THREADS = 1024;
 constexpr int SAMPLE_WGS = 32;           // most workgroups that cooperate on one sampling sequence
 constexpr int SAMPLE_MAXE = 16;          // vocabulary entries a thread can keep in registers
 constexpr int SAMPLE_THREADS = 256;
@@ -56,8 +56,22 @@ void row_argmax_kernel(const float* __restrict__ logits, int V, int N, const int
     int bi = INT_MAX;
     if ((V & 3) == 0) {
         const floatx4* r4 = reinterpret_cast<const floatx4*>(row);
-        for (int i = threadIdx.x; i < (V >> 2); i += AM_THREADS) {
-            const floatx4 x = r4[i];
+        const int n4 = V >> 2;
+        int i = threadIdx.x;
+        // eight independent loads in flight per thread: a row is only a few loads per thread, and taken one
+        // at a time they cost a memory round trip each
+        constexpr int UN = 8;
+        for (; i + (UN - 1) * AM_THREADS < n4; i += UN * AM_THREADS) {
+            floatx4 x[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) x[u] = __builtin_nontemporal_load(r4 + i + u * AM_THREADS);
+#pragma unroll
+            for (int u = 0; u < UN; ++u)               // (ids increase with u and e: the strict comparison keeps the lowest)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) if (x[u][e] > bv) { bv = x[u][e]; bi = (i + u * AM_THREADS) * 4 + e; }
+        }
+        for (; i < n4; i += AM_THREADS) {
+            const floatx4 x = __builtin_nontemporal_load(r4 + i);
 #pragma unroll
             for (int e = 0; e < 4; ++e) if (x[e] > bv) { bv = x[e]; bi = i * 4 + e; }
         }
