@@ -42,22 +42,68 @@ __device__ __forceinline__ int seq_chunks(long long P, int chunk) {
     const int n = (int)((P + chunk - 1) / chunk);
     return n < 1 ? 1 : n;
 }
+// The chunk counts of up to 64 sequences at a time are taken by the lanes of a wave (one vector load each
+// instead of a chain of dependent scalar loads per sequence) and summed with a shuffle scan; the results
+// are the same in every lane.  Every lane of the wave must be active.
+__device__ __forceinline__ int wave_inclusive_sum(int v, int lane) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int u = __shfl_up(v, o, 64);
+        if (lane >= o) v += u;
+    }
+    return v;
+}
+__device__ __forceinline__ long long read_lane_ll(long long v, int l) {
+    const unsigned lo = (unsigned)read_lane_dyn((int)(unsigned)v, l), hi = (unsigned)read_lane_dyn((int)(unsigned)((unsigned long long)v >> 32), l);
+    return (long long)(((unsigned long long)hi << 32) | lo);
+}
 __device__ __forceinline__ bool locate_chunk(int flat, int B, int chunk, const long long* kv_offsets, const int* kv_len, SeqChunk& sc) {
-    int rem = flat, first = 0;
-    for (int b = 0; b < B; ++b) {
-        const long long off = kv_offsets[b];
-        const long long P = prefix_keys(b, kv_offsets, kv_len);
+    if (B == 1) {                                      // one sequence: nothing to search
+        const long long P = prefix_keys(0, kv_offsets, kv_len);
         const int nc = seq_chunks(P, chunk);
-        if (rem < nc) { sc.b = b; sc.c = rem; sc.nc = nc; sc.off = off; sc.P = P; sc.first = first; return true; }
-        rem -= nc;
-        first += nc;
+        if (flat >= nc) return false;
+        sc.b = 0; sc.c = flat; sc.nc = nc; sc.off = kv_offsets[0]; sc.P = P; sc.first = 0;
+        return true;
+    }
+    const int lane = threadIdx.x & 63;
+    int before = 0;                                    // chunks of the sequences in earlier batches of 64
+    for (int b0 = 0; b0 < B; b0 += 64) {
+        const int b = b0 + lane;
+        long long off = 0, P = 0;
+        int nc = 0;
+        if (b < B) { off = kv_offsets[b]; P = prefix_keys(b, kv_offsets, kv_len); nc = seq_chunks(P, chunk); }
+        const int incl = wave_inclusive_sum(nc, lane);
+        const unsigned long long holds = __ballot(before + incl > flat);   // lanes whose sequence ends beyond the chunk
+        if (holds) {
+            const int l = __ffsll((long long)holds) - 1;
+            sc.b = b0 + l;
+            sc.nc = read_lane_dyn(nc, l);
+            sc.first = before + read_lane_dyn(incl, l) - sc.nc;
+            sc.c = flat - sc.first;
+            sc.off = read_lane_ll(off, l);
+            sc.P = read_lane_ll(P, l);
+            return true;
+        }
+        before += read_lane_dyn(incl, 63);
     }
     return false;
 }
 __device__ __forceinline__ void locate_seq(int b, int chunk, const long long* kv_offsets, const int* kv_len, int& first, int& nc) {
     first = 0;
-    for (int i = 0; i < b; ++i) first += seq_chunks(prefix_keys(i, kv_offsets, kv_len), chunk);
-    nc = seq_chunks(prefix_keys(b, kv_offsets, kv_len), chunk);
+    if (b == 0) { nc = seq_chunks(prefix_keys(0, kv_offsets, kv_len), chunk); return; }
+    const int lane = threadIdx.x & 63;
+    nc = 0;
+    for (int b0 = 0; b0 <= b; b0 += 64) {
+        const int i = b0 + lane;
+        const int n = i <= b ? seq_chunks(prefix_keys(i, kv_offsets, kv_len), chunk) : 0;
+        const int incl = wave_inclusive_sum(n, lane);
+        if (b - b0 < 64) {
+            nc = read_lane_dyn(n, b - b0);
+            first += read_lane_dyn(incl, b - b0) - nc;
+        } else {
+            first += read_lane_dyn(incl, 63);
+        }
+    }
 }
 
 template <int DH> __device__ __forceinline__ int k_swz(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
@@ -628,7 +674,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
 
 // grid (B*N, Hq / 4), 4 waves: one wave per (row, head).  Lanes first act as chunks (max and
 // weights of up to 64 chunks at a time), then as dh columns for the weighted sum of the
-// partial outputs, whose loads are independent and issued four chunks at a time.
+// partial outputs, whose loads are independent and issued eight chunks at a time.
 template <int DH>
 __global__ __launch_bounds__(256)
 void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len, int N, int q0, int nq, int Hq, int Hkv, int chunk, int rows_pad,
@@ -658,14 +704,15 @@ void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const in
         l += wave_sumf(wgt * lc);
         const int nb = min(64, nc - c0);
         int j = 0;
-        for (; j + 4 <= nb; j += 4) {
-            float v[4][DH / 64];
+        constexpr int CU = 8;                          // partial outputs in flight per lane
+        for (; j + CU <= nb; j += CU) {
+            float v[CU][DH / 64];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < CU; ++u)
 #pragma unroll
                 for (int e = 0; e < DH / 64; ++e) v[u][e] = part_o[(row0 + (size_t)(c0 + j + u) * cstride) * DH + e * 64 + lane];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < CU; ++u) {
                 const float wu = read_lane_dyn(wgt, j + u);
 #pragma unroll
                 for (int e = 0; e < DH / 64; ++e) o[e] += wu * v[u][e];
