@@ -33,6 +33,23 @@ constexpr int LM_STAGE = LM_ROWS * LM_RS;    // bytes of LDS per wave (4 waves: 
 constexpr int LM_LOADS = LM_ROWS * LM_CHUNK / 1024;   // 16-byte loads per lane per stage
 constexpr int LM_GMAX = 1024;                // upper bound on workgroups (partials per row)
 
+// Orders are turned into single unsigned 64-bit comparisons.  (value, id) with "higher value first,
+// then lower id": the float's bits mapped monotonically to an unsigned, above the complemented id.
+__device__ __forceinline__ unsigned long long order_key(float v, int id) {
+    const unsigned b = __float_as_uint(v + 0.f);       // -0 and +0 are one value
+    const unsigned u = b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
+    return ((unsigned long long)u << 32) | (unsigned)~id;
+}
+__device__ __forceinline__ unsigned long long order_key(double v) {      // ties are broken by position
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v + 0.0);
+    return b ^ ((b >> 63) ? ~0ull : 0x8000000000000000ull);
+}
+__device__ __forceinline__ float key_value(unsigned long long key) {
+    const unsigned u = (unsigned)(key >> 32);
+    return __uint_as_float(u ^ ((u >> 31) ? 0x80000000u : 0xffffffffu));
+}
+__device__ __forceinline__ int key_id(unsigned long long key) { return (int)~(unsigned)key; }
+
 template <int KC>
 __device__ __forceinline__ void list_insert(float x, int v, float (&val)[KC], int (&idx)[KC]) {
     // ids arrive in increasing order within a lane, so a strict comparison keeps the lower id first
@@ -239,70 +256,84 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
         }
     }
 
-    // ---- merge the 16 per-lane states of each frontier row: the 4 lane groups of a wave by
-    // shuffles, then the 4 waves through LDS; all 16 rows in parallel ----
-    auto merge_groups = [&]() {
-        // (max, sum-exp) over lanes m16, m16+16, m16+32, m16+48
+    // ---- merge the 16 per-lane states of each frontier row (4 lane groups x 4 waves) in one 16-way
+    // merge: every lane leaves its state in LDS, then the 16 lists of a row sit in the 16 lanes of one DPP
+    // row (wave w takes frontier rows 4w .. 4w+3) and the best head is found with four row-local
+    // butterfly steps per output element; the four waves work on different rows at the same time ----
+    __syncthreads();                                                   // the staging buffers are idle
+    // One LDS row of LM_MROW words per list position (and two more for max and sum-exp); the lane of wave a
+    // sits at word 68 a + lane, so that both the writes (consecutive lanes) and the reads below (row r16 of
+    // wave a, lane group b: word 68 a + 16 b + r16, with four consecutive r16 per wave) touch 64 different banks.
+    constexpr int LM_MROW = 4 * 68;
+    float* l_val = reinterpret_cast<float*>(smem);                     // [KC][LM_MROW]
+    int* l_idx = reinterpret_cast<int*>(smem + KC * LM_MROW * 4);
+    float* l_ms = reinterpret_cast<float*>(smem + 2 * KC * LM_MROW * 4);   // [2][LM_MROW]
+    {
+        const int me = w * 68 + lane;
 #pragma unroll
-        for (int o = 16; o <= 32; o <<= 1) {
-            const float om = o == 16 ? lane_xor16(run_m) : lane_xor32(run_m), os = o == 16 ? lane_xor16(run_s) : lane_xor32(run_s);
-            const float nm = fmaxf(run_m, om);
-            const float a = run_m > -INFINITY ? run_s * __expf(run_m - nm) : 0.f;
-            const float c = om > -INFINITY ? os * __expf(om - nm) : 0.f;
-            run_m = nm;
-            run_s = a + c;
-        }
-        // KC rounds of arg-best over the four list heads; every lane keeps the merged list
-        float mv[KC]; int mi[KC];
-#pragma unroll
-        for (int r = 0; r < KC; ++r) {
-            float bv = tval[0]; int bi = tidx[0];
-#pragma unroll
-            for (int o = 16; o <= 32; o <<= 1) {
-                const float ov = o == 16 ? lane_xor16(bv) : lane_xor32(bv);
-                const int oi = o == 16 ? lane_xor16(bi) : lane_xor32(bi);
-                if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-            }
-            if (tval[0] == bv && tidx[0] == bi) {
-#pragma unroll
-                for (int q = 0; q < KC - 1; ++q) { tval[q] = tval[q + 1]; tidx[q] = tidx[q + 1]; }
-                tval[KC - 1] = -INFINITY; tidx[KC - 1] = INT_MAX;
-            }
-            mv[r] = bv; mi[r] = bi;
-        }
-#pragma unroll
-        for (int r = 0; r < KC; ++r) { tval[r] = mv[r]; tidx[r] = mi[r]; }
-    };
-    __syncthreads();
-    merge_groups();
-    float* l_val = reinterpret_cast<float*>(smem);                     // [4 waves][16 rows][KC]
-    int* l_idx = reinterpret_cast<int*>(smem + 4 * 16 * KC * 4);
-    float* l_ms = reinterpret_cast<float*>(smem + 2 * 4 * 16 * KC * 4);   // [4][16][2]
-    if (g == 0) {
-        const int base = (w * 16 + m16) * KC;
-#pragma unroll
-        for (int j = 0; j < KC; ++j) { l_val[base + j] = tval[j]; l_idx[base + j] = tidx[j]; }
-        l_ms[(w * 16 + m16) * 2 + 0] = run_m;
-        l_ms[(w * 16 + m16) * 2 + 1] = run_s;
+        for (int j = 0; j < KC; ++j) { l_val[j * LM_MROW + me] = tval[j]; l_idx[j * LM_MROW + me] = tidx[j]; }
+        l_ms[me] = run_m;
+        l_ms[LM_MROW + me] = run_s;
     }
     __syncthreads();
-    if (w == 0) {
-        // lane (g, m16) takes wave g's list for row m16; the same four-way merge finishes the job
-        const int base = (g * 16 + m16) * KC;
+    const int r16 = w * 4 + (lane >> 4), q = lane & 15;               // frontier row (within the block) and list of this lane
+    {
+        const int src = (q >> 2) * 68 + (q & 3) * 16 + r16;           // wave q / 4, lane group q % 4, row r16
 #pragma unroll
-        for (int j = 0; j < KC; ++j) { tval[j] = l_val[base + j]; tidx[j] = l_idx[base + j]; }
-        run_m = l_ms[(g * 16 + m16) * 2 + 0];
-        run_s = l_ms[(g * 16 + m16) * 2 + 1];
-        merge_groups();
-        if (g == 0) {
-            const size_t prow = (size_t)mblk * 16 + m16;               // padded rows included
-            part_ms[(prow * G + blockIdx.x) * 2 + 0] = run_m;
-            part_ms[(prow * G + blockIdx.x) * 2 + 1] = run_s;
+        for (int j = 0; j < KC; ++j) { tval[j] = l_val[j * LM_MROW + src]; tidx[j] = l_idx[j * LM_MROW + src]; }
+        run_m = l_ms[src];
+        run_s = l_ms[LM_MROW + src];
+    }
+#define E2_ROW_STEP(CTRL)                                                                       \
+    {                                                                                           \
+        const float om = dpp_mov<CTRL>(run_m), os = dpp_mov<CTRL>(run_s);                       \
+        const float nm = fmaxf(run_m, om);                                                      \
+        const float a = run_m > -INFINITY ? run_s * __expf(run_m - nm) : 0.f;                   \
+        const float c = om > -INFINITY ? os * __expf(om - nm) : 0.f;                            \
+        run_m = nm;                                                                             \
+        run_s = a + c;                                                                          \
+    }
+    E2_ROW_STEP(DPP_XOR1) E2_ROW_STEP(DPP_XOR2) E2_ROW_STEP(DPP_HALF_MIRROR) E2_ROW_STEP(DPP_MIRROR)
+#undef E2_ROW_STEP
+    // (value, id) pairs as 64-bit keys: a step of the butterfly is two lane moves, one comparison, two selects
+    unsigned klo[KC], khi[KC];
 #pragma unroll
-            for (int j = 0; j < KC; ++j) {
-                part_val[(prow * G + blockIdx.x) * KC + j] = tval[j];
-                part_idx[(prow * G + blockIdx.x) * KC + j] = tidx[j];
-            }
+    for (int j = 0; j < KC; ++j) {
+        const unsigned long long key = order_key(tval[j], tidx[j]);
+        klo[j] = (unsigned)key;
+        khi[j] = (unsigned)(key >> 32);
+    }
+    const unsigned long long empty = order_key(-INFINITY, INT_MAX);
+    float mv[KC];
+    int mi[KC];
+#pragma unroll
+    for (int rr = 0; rr < KC; ++rr) {
+        unsigned blo = klo[0], bhi = khi[0];
+#define E2_ROW_STEP(CTRL)                                                                       \
+        {                                                                                       \
+            const unsigned olo = (unsigned)dpp_mov<CTRL>((int)blo), ohi = (unsigned)dpp_mov<CTRL>((int)bhi); \
+            const bool take = (((unsigned long long)ohi << 32) | olo) > (((unsigned long long)bhi << 32) | blo); \
+            blo = take ? olo : blo;                                                             \
+            bhi = take ? ohi : bhi;                                                             \
+        }
+        E2_ROW_STEP(DPP_XOR1) E2_ROW_STEP(DPP_XOR2) E2_ROW_STEP(DPP_HALF_MIRROR) E2_ROW_STEP(DPP_MIRROR)
+#undef E2_ROW_STEP
+        if (klo[0] == blo && khi[0] == bhi) {          // the list that held the winner moves up (ids are unique)
+#pragma unroll
+            for (int qq = 0; qq < KC - 1; ++qq) { klo[qq] = klo[qq + 1]; khi[qq] = khi[qq + 1]; }
+            klo[KC - 1] = (unsigned)empty; khi[KC - 1] = (unsigned)(empty >> 32);
+        }
+        const unsigned long long best = ((unsigned long long)bhi << 32) | blo;
+        mv[rr] = key_value(best); mi[rr] = key_id(best);
+    }
+    if (q == 0) {
+        const size_t prow = (size_t)mblk * 16 + r16;                   // padded rows included
+        part_ms[(prow * G + blockIdx.x) * 2 + 0] = run_m;
+        part_ms[(prow * G + blockIdx.x) * 2 + 1] = run_s;
+#pragma unroll
+        for (int j = 0; j < KC; ++j) {
+            part_val[(prow * G + blockIdx.x) * KC + j] = mv[j];
+            part_idx[(prow * G + blockIdx.x) * KC + j] = mi[j];
         }
     }
 }
@@ -664,23 +695,6 @@ void row_stats_kernel(int V, int F, const float* __restrict__ logits_ws, const f
 constexpr int MG_THREADS = 1024;
 constexpr int MG_MAXN = EAGLE2_MAX_TOPK * EAGLE2_MAX_TOPK;   // most keys ranked at once
 
-// Orders are turned into single unsigned 64-bit comparisons.  (value, id) with "higher value first,
-// then lower id": the float's bits mapped monotonically to an unsigned, above the complemented id.
-__device__ __forceinline__ unsigned long long order_key(float v, int id) {
-    const unsigned b = __float_as_uint(v + 0.f);       // -0 and +0 are one value
-    const unsigned u = b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
-    return ((unsigned long long)u << 32) | (unsigned)~id;
-}
-__device__ __forceinline__ unsigned long long order_key(double v) {      // ties are broken by position
-    const unsigned long long b = (unsigned long long)__double_as_longlong(v + 0.0);
-    return b ^ ((b >> 63) ? ~0ull : 0x8000000000000000ull);
-}
-__device__ __forceinline__ float key_value(unsigned long long key) {
-    const unsigned u = (unsigned)(key >> 32);
-    return __uint_as_float(u ^ ((u >> 31) ? 0x80000000u : 0xffffffffu));
-}
-__device__ __forceinline__ int key_id(unsigned long long key) { return (int)~(unsigned)key; }
-
 // Ranks of n <= MG_MAXN keys in LDS (descending; equal keys: lower position first), by all-pairs
 // counting spread over the whole workgroup: with P threads per key (the largest power of two that
 // fits MG_THREADS / n), thread
@@ -934,7 +948,7 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
     } else {
         G = lm_grid(cfg);
         const size_t smem = 4 * LM_STAGE;
-        static_assert(4 * LM_STAGE >= 2 * 16 * 16 * EAGLE2_MAX_TOPK * 4 + 16 * 16 * 2 * 4, "merge area must fit");
+        static_assert(4 * LM_STAGE >= (2 * EAGLE2_MAX_TOPK + 2) * 4 * 68 * 4, "merge area must fit");
         timing_begin(0, st);
         hipLaunchKernelGGL((lmhead_kernel<BF16, KC>), dim3(G, mblks), dim3(LM_THREADS), smem, st,
                            reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab,
