@@ -140,11 +140,13 @@ __device__ __forceinline__ double wave_sum(double v) {
     return ((read_lane(v, 0) + read_lane(v, 16)) + read_lane(v, 32)) + read_lane(v, 48);
 }
 // candidate order: higher value first, then lower index
+// (bitwise operators on purpose: the short-circuit forms compile to divergent branches around two of
+// the three comparisons)
 __device__ __forceinline__ bool ranks_before(float va, int ia, float vb, int ib) {
-    return va > vb || (va == vb && ia < ib);
+    return (va > vb) | ((va == vb) & (ia < ib));
 }
 __device__ __forceinline__ bool ranks_before(double va, int ia, double vb, int ib) {
-    return va > vb || (va == vb && ia < ib);
+    return (va > vb) | ((va == vb) & (ia < ib));
 }
 // every lane ends with the wave's best (value, index) and the payload that travels with it
 template <typename T>

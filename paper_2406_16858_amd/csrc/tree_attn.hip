@@ -703,25 +703,20 @@ void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const in
         }
         l += wave_sumf(wgt * lc);
         const int nb = min(64, nc - c0);
-        int j = 0;
         constexpr int CU = 8;                          // partial outputs in flight per lane
-        for (; j + CU <= nb; j += CU) {
+        for (int j = 0; j < nb; j += CU) {             // (the last group may be short: its loads are skipped, not serialised)
             float v[CU][DH / 64];
 #pragma unroll
             for (int u = 0; u < CU; ++u)
 #pragma unroll
-                for (int e = 0; e < DH / 64; ++e) v[u][e] = part_o[(row0 + (size_t)(c0 + j + u) * cstride) * DH + e * 64 + lane];
+                for (int e = 0; e < DH / 64; ++e)
+                    v[u][e] = j + u < nb ? part_o[(row0 + (size_t)(c0 + j + u) * cstride) * DH + e * 64 + lane] : 0.f;
 #pragma unroll
             for (int u = 0; u < CU; ++u) {
-                const float wu = read_lane_dyn(wgt, j + u);
+                const float wu = j + u < nb ? read_lane_dyn(wgt, j + u) : 0.f;
 #pragma unroll
                 for (int e = 0; e < DH / 64; ++e) o[e] += wu * v[u][e];
             }
-        }
-        for (; j < nb; ++j) {
-            const float wu = read_lane_dyn(wgt, j);
-#pragma unroll
-            for (int e = 0; e < DH / 64; ++e) o[e] += wu * part_o[(row0 + (size_t)(c0 + j) * cstride) * DH + e * 64 + lane];
         }
     }
     const float inv = 1.f / l;
