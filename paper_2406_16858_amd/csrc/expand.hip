@@ -675,7 +675,7 @@ void row_stats_kernel(int V, int F, const float* __restrict__ logits_ws, const f
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int ij = (int)oi[e];
-                r += (ov[e] > v || (ov[e] == v && (ij < id || (ij == id && j + e < lane)))) ? 1 : 0;
+                r += ((ov[e] > v) | ((ov[e] == v) & ((ij < id) | ((ij == id) & (j + e < lane))))) ? 1 : 0;   // (bitwise: no branches)
             }
         }
         const size_t pbase = (size_t)m * G + chunk;
@@ -710,7 +710,7 @@ __device__ __forceinline__ void rank_keys(const unsigned long long* keys, int n,
 #pragma unroll 4
     for (int j = part; j < n; j += P) {
         const unsigned long long kj = keys[j];
-        cnt += (kj > ki || (kj == ki && j < i)) ? 1 : 0;
+        cnt += ((kj > ki) | ((kj == ki) & (j < i))) ? 1 : 0;   // (bitwise: no branches)
     }
     if (cnt) atomicAdd(rank + i, cnt);
 }
