@@ -85,7 +85,7 @@ void rerank_kernel(int C, int N, int k, int D, int words, int flags,
 #pragma unroll
         for (int j = 0; j < 64; ++j) {
             const double vj = read_lane(v, j);
-            r += (vj > v || (vj == v && j < lane)) ? 1 : 0;       // same run: id order = lane order
+            r += ((vj > v) | ((vj == v) & (j < lane))) ? 1 : 0;   // same run: id order = lane order (bitwise: no branches)
         }
         s_key[run * 64 + r] = v;
         s_id[run * 64 + r] = id;
