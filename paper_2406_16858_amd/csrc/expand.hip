@@ -89,6 +89,23 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     const int mrow = mblk * 16 + m16;                  // frontier row owned by this lane
     const bool row_valid = mrow < M;
 
+    u32x4 R[LM_LOADS];
+    auto issue = [&](int it) {
+        const int task = task_first + it / nst;
+        const int st = it - (it / nst) * nst;
+        const size_t kb = (size_t)w * wave_bytes + (size_t)st * LM_CHUNK + c16 * 16;
+#pragma unroll
+        for (int j = 0; j < LM_LOADS; ++j) {
+            int row = task * LM_ROWS + j * 4 + r_in;
+            row = row < V ? row : V - 1;               // ragged tail: re-read the last row, masked later
+            R[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(W + (size_t)row * row_bytes + kb));
+        }
+    };
+    // The first stage of W is requested before anything else is set up: the row pointers of the optional
+    // logits, the frontier-row divisions and the list initialisation below then run under that latency.
+    if (total > 0) issue(0);
+    __builtin_amdgcn_sched_barrier(0);
+
     if (blockIdx.x == 0 && mblk == 0)                   // counters of the merge kernel's last-arrival test
         for (int i = tid; i < B; i += LM_THREADS) done_count[i] = 0u;
 
@@ -142,19 +159,6 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
         nbuf = 0;
     };
 
-    u32x4 R[LM_LOADS];
-    auto issue = [&](int it) {
-        const int task = task_first + it / nst;
-        const int st = it - (it / nst) * nst;
-        const size_t kb = (size_t)w * wave_bytes + (size_t)st * LM_CHUNK + c16 * 16;
-#pragma unroll
-        for (int j = 0; j < LM_LOADS; ++j) {
-            int row = task * LM_ROWS + j * 4 + r_in;
-            row = row < V ? row : V - 1;               // ragged tail: re-read the last row, masked later
-            R[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(W + (size_t)row * row_bytes + kb));
-        }
-    };
-
     floatx4 acc[4];
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) acc[nb] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -180,7 +184,6 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     if (total > 0) {
 #pragma unroll
         for (int t = 0; t < LM_CHUNK / 64; ++t) hn[t] = load_h(frag0(0) + t);
-        issue(0);
     }
     for (int it = 0; it < total; ++it) {
         const int ti = it / nst;
