@@ -736,6 +736,7 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     __shared__ unsigned long long s_fk[MG_MAXN];        // new candidates' scores (frontier selection)
     __shared__ int s_rank[3][MG_MAXN];                  // one set of counters per ranking, zeroed once
     __shared__ int s_last;
+    __shared__ double s_logsum;
     static_assert(NW * EAGLE2_MAX_TOPK <= MG_MAXN, "the per-wave winners are ranked like the other key sets");
     const int slot = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -795,6 +796,12 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     __syncthreads();
     // a winner of rank r < nlive brings in its list: nlive * KC candidates in all
     const int ncand = nlive * KC;
+    if (tid == MG_THREADS - 1) {                        // an idle thread takes the logarithm while the lists are fetched
+        double tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) tot += s_d[w];
+        s_logsum = log(tot);
+    }
     if (tid < n2) {
         const int r = s_rank[0][tid], l = s_wl[tid];
         if (r < nlive && s_wk[tid] != 0ull && l >= 0 && l < G) {
@@ -812,10 +819,7 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     }
     __syncthreads();
     if (tid < k) {
-        double tot = 0.0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) tot += s_d[w];
-        const double log_sum = log(tot);
+        const double log_sum = s_logsum;
         const int cid = base + slot * k + tid;
         const unsigned long long key = s_ok[tid];
         const float ov = key != 0ull ? key_value(key) : -INFINITY;
