@@ -182,3 +182,44 @@ def test_long_context_prefix_many_chunks(fp8):
         e = pu.rel_err(pu.f64(O[b]), ref)
         assert e <= pu.REL_TOL["bf16"], f"seq {b}: rel err {e:.2e}"
         assert np.max(np.abs(pu.f64(lse[b]) - ref_lse)) <= pu.REL_TOL["bf16"] * max(1.0, np.abs(ref_lse).max())
+
+
+@pytest.mark.parametrize("batch", [1, 20], ids=["few_rows", "many_rows"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_exact_ties_take_the_lower_token_id(batch, dtype):
+    """Rows of W repeated in pairs give logits that tie exactly; hidden states of zero tie every logit.
+    Whatever lane, wave or workgroup holds them, equal values must come out lower token id first
+    (Section 4.1 leaves the order of equal values open; this build fixes it, as the oracle does)."""
+    from paper_2406_16858_amd import DraftRound
+    cfg = _cfg("ties", dtype=dtype, batch=batch, vocab=5003, hidden=512 if dtype == "bf16" else 256, depth=3, topk=5, n_tree=12, seed=17)
+    B, D, k, V = cfg.batch, cfg.depth, cfg.topk, cfg.vocab
+    W = wl.make_lm_head(cfg, "cuda")
+    W[1::2] = W[0:V - 1:2]                             # token 2j+1 repeats token 2j (V is odd: the last token stays single)
+    H = wl.make_hidden_states(cfg, "cuda", scale=4.0)
+    for zero_h in (False, True):
+        if zero_h:
+            H = torch.zeros_like(H)
+        rnd = DraftRound(B, V, cfg.hidden, D, k, cfg.n_tree, cfg.dtype)
+        rnd.expand_all(H, W)
+        torch.cuda.synchronize()
+        tok = rnd.cand_token.cpu().numpy().reshape(B, -1)
+        sc = rnd.cand_score.cpu().numpy().reshape(B, -1)
+        par = rnd.cand_parent.cpu().numpy().reshape(B, -1)
+        for b in range(B):
+            for base in range(0, tok.shape[1], k):     # every expanded row's k children, best first
+                t, s, p = tok[b, base:base + k], sc[b, base:base + k], par[b, base:base + k]
+                if p[0] < -1 or not np.isfinite(s).all():
+                    continue                           # (rows of passes that were not expanded)
+                local = s - (sc[b, p[0]] if p[0] >= 0 else 0.0)     # the children's own log-probabilities
+                assert np.all(np.diff(local) <= 1e-12), (b, base, local)
+                if zero_h:
+                    assert list(t) == list(range(k)), (b, base, t)
+                    assert np.allclose(local, -np.log(V), atol=1e-5)
+                    continue
+                chosen = set(int(x) for x in t)
+                for i, x in enumerate(t):
+                    x = int(x)
+                    if x % 2 == 1:                     # a repeated row: its twin comes right before it
+                        assert x - 1 in chosen and int(t[i - 1]) == x - 1 and abs(local[i] - local[i - 1]) < 1e-12, (b, base, t, local)
+                    elif x + 1 < V and i + 1 < k:      # the twin of an even token ties with it and follows, unless the list ends
+                        assert int(t[i + 1]) == x + 1, (b, base, t)
