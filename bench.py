@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per LM-head launch (fetch + write) from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE),
 # each scaled by what the counter reads for a plain 1 GiB copy; the summary is profiles/round_cfg3_llama3_8b.md.
 # None for workloads without a recorded counter run.
-MEASURED_TRAFFIC_BYTES = {3: 1057132018}
+MEASURED_TRAFFIC_BYTES = {3: 1057094037}
 
 
 def algorithmic_bytes(cfg, plens):
