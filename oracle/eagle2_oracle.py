@@ -35,7 +35,10 @@ notes of this repository):
 Pinning status: expand/rerank/flatten, tree_attn and accept_greedy are pinned by
 tests/test_oracle_*.py against brute force, closed forms, library routines and
 the invariants the paper states.  accept_sample is pinned for the chain case
-(Section 2.1's rule) and by the exactness of the emitted-token law; the order in
+(Section 2.1's rule) and by the exactness of the emitted-token law; which draft
+distribution is q at a node (the one its parent was expanded with, Section 4.1;
+draft_row / parent_draft_row) is pinned on full trees whose every expanded node
+carries a distribution chosen by the test; the order in
 which sibling branches are tried and the renormalisation of the draft
 distribution after a rejected sibling are this repository's reading of Section
 2.2 -- "parity unpinned" by the paper for that particular choice.  commit_* is
@@ -354,6 +357,7 @@ class AcceptResult:
     bonus_token: int               # the token emitted after the accepted path
     trace: Optional[list] = None   # sampling only: per tested child (row, accept probability)
     final_p: Optional[np.ndarray] = None   # sampling only: distribution the bonus was drawn from
+    ratios: Optional[dict] = None  # sampling only: tested row -> p(x)/q(x) before the cap at 1 (for reports)
 
 
 def _children(tree_parent: np.ndarray, cur: int) -> List[int]:
@@ -397,7 +401,7 @@ def accept_sample(target_logits, draft_logits, temperature: float, u_accept, u_b
     tree_token = np.asarray(tree_token)
     tree_cand = np.asarray(tree_cand)
     T = float(temperature)
-    cur, path, trace = 0, [0], []
+    cur, path, trace, ratios = 0, [0], [], {}
     while True:
         p = softmax64(tl[cur] / T)
         kids = _children(tree_parent, cur)
@@ -408,6 +412,7 @@ def accept_sample(target_logits, draft_logits, temperature: float, u_accept, u_b
                 x = int(tree_token[c])
                 ratio = p[x] / q[x]
                 trace.append((c, min(1.0, ratio)))
+                ratios[c] = float(ratio)
                 if float(u_accept[c]) < ratio:
                     cur = c
                     path.append(c)
@@ -427,7 +432,7 @@ def accept_sample(target_logits, draft_logits, temperature: float, u_accept, u_b
             cdf = np.cumsum(p)
             hit = np.nonzero(cdf > float(u_bonus[cur]) * total)[0]
             bonus = int(hit[0]) if hit.size else int(np.nonzero(p > 0.0)[0][-1])
-            return AcceptResult(len(path) - 1, path, bonus, trace, p)
+            return AcceptResult(len(path) - 1, path, bonus, trace, p, ratios)
 
 
 # ----------------------------------------------------------------------------

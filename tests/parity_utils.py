@@ -22,6 +22,12 @@ from oracle import eagle2_oracle as orc
 
 SWAP_TOL = 1e-5
 REL_TOL = {"fp32": 1e-4, "bf16": 2e-2}
+# Raw logits and joint scores are float32 sums of exactly representable products (bf16 x bf16, or
+# float32 inputs) plus float64 adds: their error does not depend on the I/O type, so both are held
+# to the float32 bound (measured: logits 2e-6, scores 4e-7 relative).
+LOGIT_TOL = 1e-4
+SCORE_TOL = 1e-4
+DECISION_TOL = 1e-5     # a sampling decision may differ only if |u - p/q| < DECISION_TOL * max(1, p/q)
 
 
 def f64(t: torch.Tensor) -> np.ndarray:
@@ -48,7 +54,10 @@ class Report:
     max_logit_rel: float = 0.0
     max_attn_rel: float = 0.0
     max_lse_err: float = 0.0
+    near_threshold_decisions: int = 0    # sampling decisions that differ from the oracle's within DECISION_TOL
     notes: List[str] = field(default_factory=list)
+    # the oracle's own float64 draft logits per sequence ([R, V]), filled pass by pass
+    oracle_draft_logits: dict = field(default_factory=dict)
 
 
 def _admissible(picked_vals: np.ndarray, all_vals: np.ndarray, picked_idx: np.ndarray, what: str):
@@ -73,7 +82,6 @@ def check_expand_pass(rnd, cfg, states, d: int, H64_d: np.ndarray, W64: np.ndarr
     given, widened to float64) against the oracle, and continues the oracle states from the GPU's
     choices."""
     B, D, k = cfg.batch, cfg.depth, cfg.topk
-    rel_tol = REL_TOL[cfg.dtype]
     by_value = not (flags & FLAG_RANK_BY_CONFIDENCE)
     g_tok = rnd.cand_token.cpu().numpy()
     g_score = rnd.cand_score.cpu().numpy()
@@ -84,13 +92,20 @@ def check_expand_pass(rnd, cfg, states, d: int, H64_d: np.ndarray, W64: np.ndarr
     for b in range(B):
         st = states[b]
         ref = st.copy()
-        dl_ref = np.zeros((orc.n_draft_rows(D, k), cfg.vocab)) if (check_logits and rnd.draft_logits is not None) else None
+        keep = check_logits and rnd.draft_logits is not None
+        dl_ref = report.oracle_draft_logits.setdefault(b, np.zeros((orc.n_draft_rows(D, k), cfg.vocab))) if keep else None
         sf = None if static_frontier is None or d + 1 >= D else static_frontier[d + 1]
         logp = orc.expand(ref, d, H64_d[b, :F], W64, draft_logits=dl_ref, rank_by_value=by_value, static_frontier=sf)
         if dl_ref is not None:
+            # the dense draft logits are the draft distribution of the acceptance rule (Section 2.1):
+            # every row this pass owns must hold the oracle's logits of that (sequence, slot)
             rows = [orc.draft_row(d, s, k) for s in range(F)]
             got = rnd.draft_logits[b, rows].cpu().numpy().astype(np.float64)
-            report.max_logit_rel = max(report.max_logit_rel, rel_err(got, dl_ref[rows]))
+            assert np.all(np.isfinite(got)), f"seq {b} pass {d}: draft-logit rows left unwritten or not finite"
+            for i, r in enumerate(rows):
+                e = rel_err(got[i], dl_ref[r])
+                report.max_logit_rel = max(report.max_logit_rel, e)
+                assert e <= LOGIT_TOL, f"seq {b} pass {d} slot {i}: draft logits (row {r}) rel err {e:.3e} > {LOGIT_TOL}"
         for s in range(F):
             if d > 0 and int(st.frontier[d, s]) < 0:
                 continue                                    # unused slot of a fixed shape: its candidates are never read
@@ -108,7 +123,7 @@ def check_expand_pass(rnd, cfg, states, d: int, H64_d: np.ndarray, W64: np.ndarr
             st.own[ids] = logp[s, picks]
             err = np.abs(g_score[b, ids] - st.score[ids])
             report.max_score_err = max(report.max_score_err, float(err.max()))
-            assert np.all(err <= rel_tol * np.maximum(np.abs(st.score[ids]), 1.0)), \
+            assert np.all(err <= SCORE_TOL * np.maximum(np.abs(st.score[ids]), 1.0)), \
                 f"seq {b} pass {d} row {s}: joint score error {err.max():.3e}"
         if d + 1 < D and static_frontier is not None:
             assert np.array_equal(g_front[b, d + 1], static_frontier[d + 1]), f"seq {b} pass {d}: the fixed frontier was overwritten"
@@ -134,10 +149,21 @@ def lockstep_expand(rnd, cfg, H_all: torch.Tensor, W: torch.Tensor, W64: np.ndar
         W64 = f64(W)
     H64 = f64(H_all)
     states = [orc.DraftState(D, k) for _ in range(B)]
+    dl = rnd.draft_logits if check_logits else None
+    report.oracle_draft_logits.clear()
+    if dl is not None:
+        dl.fill_(float("nan"))                          # a row no pass writes stays NaN and fails the checks
     for d in range(D):
+        before = dl.clone() if dl is not None else None
         rnd.expand(d, H_all[:, d], W, h_seq_stride=D * k * cfg.hidden)
         if H_all.is_cuda:
             torch.cuda.synchronize()
+        if dl is not None:
+            # pass d owns rows draft_row(d, 0..F-1) and must leave every other row bit for bit as it was
+            own = [orc.draft_row(d, s, k) for s in range(1 if d == 0 else k)]
+            other = [r for r in range(dl.shape[1]) if r not in own]
+            same = torch.equal(dl[:, other].view(torch.int32), before[:, other].view(torch.int32))
+            assert same, f"pass {d} changed draft-logit rows that belong to other passes"
         check_expand_pass(rnd, cfg, states, d, H64[:, d], W64, report, check_logits, flags, static_frontier)
     return states, report
 
@@ -220,9 +246,32 @@ def check_attention(cfg, trees, Q, Kp, Vp, Kt, Vt, kv_offsets, O, lse, report: R
                 assert le <= tol * max(1.0, float(np.max(np.abs(lq[:, col])))), f"seq {b} head {h}: lse err {le:.3e}"
 
 
+def _trim(path) -> list:
+    return [int(r) for r in path if int(r) >= 0]
+
+
+def _check_bonus(b, got: int, res, u: float, report: Report, what: str):
+    """The emitted token must be the oracle's, or sit across a CDF edge that the draw touches
+    within DECISION_TOL of the total mass."""
+    if got == res.bonus_token:
+        return
+    assert res.final_p is not None, f"seq {b}: bonus {got} != {res.bonus_token} ({what})"
+    p = res.final_p
+    cdf = np.cumsum(p) / p.sum()
+    lo, hi = min(got, res.bonus_token), max(got, res.bonus_token)
+    assert 0 <= lo and hi < len(p), f"seq {b}: bonus {got} out of range ({what})"
+    assert abs(cdf[lo] - u) < DECISION_TOL and np.all(p[lo + 1:hi] <= DECISION_TOL), \
+        f"seq {b}: bonus {got} != {res.bonus_token} and not at a CDF edge ({what})"
+    report.notes.append(f"seq {b}: bonus differs at a CDF edge ({what})")
+
+
 def check_accept(rnd, cfg, trees, modes, target_logits, temperature, u_accept, u_bonus, report: Report):
-    """Greedy: bit-exact.  Sampling: the oracle is fed the same float32 draft logits the GPU
-    produced, and must reproduce path, length and emitted token."""
+    """Greedy: bit-exact.  Sampling is checked twice.  (1) Fed the float32 draft logits the GPU
+    itself produced, the oracle must reproduce path, length and emitted token.  (2) Fed its OWN
+    float64 draft logits (kept by check_expand_pass), the oracle must take the same decisions,
+    except at a child whose uniform lies within DECISION_TOL * max(1, p/q) of the ratio p/q, or a
+    bonus draw within DECISION_TOL of a CDF edge; such cases are counted, and what follows the
+    first of them cannot be compared (the two walks are then in different subtrees)."""
     B, D, k = cfg.batch, cfg.depth, cfg.topk
     a_len = rnd.accept_len.cpu().numpy()
     a_path = rnd.accept_path.cpu().numpy()
@@ -239,17 +288,32 @@ def check_accept(rnd, cfg, trees, modes, target_logits, temperature, u_accept, u
         want_path = res.path + [-1] * (D + 1 - len(res.path))
         assert a_len[b] == res.accept_len, f"seq {b}: accept_len {a_len[b]} != {res.accept_len}"
         assert a_path[b].tolist() == want_path, f"seq {b}: path {a_path[b].tolist()} != {want_path}"
-        if a_bonus[b] != res.bonus_token and modes[b] == 1:
-            # admissible only if the draw sits within 1e-5 (of the total mass) of the CDF edge between them
-            p = res.final_p
-            cdf = np.cumsum(p) / p.sum()
-            u = float(u_bonus[b][res.path[-1]])
-            lo, hi = min(a_bonus[b], res.bonus_token), max(a_bonus[b], res.bonus_token)
-            assert abs(cdf[lo] - u) < 1e-5 and np.all(p[lo + 1:hi] <= 1e-5), \
-                f"seq {b}: bonus {a_bonus[b]} != {res.bonus_token} and not at a CDF edge"
-            report.notes.append(f"seq {b}: bonus differs at a CDF edge")
+        if modes[b] == 1:
+            _check_bonus(b, int(a_bonus[b]), res, float(u_bonus[b][res.path[-1]]), report, "oracle on the GPU's draft logits")
         else:
             assert a_bonus[b] == res.bonus_token, f"seq {b}: bonus {a_bonus[b]} != {res.bonus_token}"
+        if modes[b] == 1 and b in report.oracle_draft_logits:
+            own = orc.accept_sample(tl, report.oracle_draft_logits[b], float(temperature[b]), f64(u_accept[b]),
+                                    f64(u_bonus[b]), tree.token, tree.parent, tree.cand, k)
+            got = _trim(a_path[b])
+            if got == own.path:
+                _check_bonus(b, int(a_bonus[b]), own, float(u_bonus[b][own.path[-1]]), report, "oracle on its own draft logits")
+            else:
+                i = 0
+                while i < min(len(got), len(own.path)) and got[i] == own.path[i]:
+                    i += 1
+                assert i >= 1, f"seq {b}: the accepted path does not start at the root"
+                cur = own.path[i - 1]
+                kids = [int(c) for c in np.nonzero(np.asarray(tree.parent) == cur)[0]]
+                taken = [kids.index(x[i]) for x in (got, own.path) if i < len(x) and x[i] in kids]
+                assert taken, f"seq {b}: paths {got} / {own.path} part at row {cur} without a child of it"
+                c = kids[min(taken)]                    # the first sibling on which the two decisions differ
+                ratio, u = own.ratios[c], float(u_accept[b][c])
+                assert abs(u - ratio) < DECISION_TOL * max(1.0, ratio), \
+                    f"seq {b}: path {got} != oracle's {own.path} on its own draft logits; decision at row {c}: " \
+                    f"u = {u:.9f}, p/q = {ratio:.9f}"
+                report.near_threshold_decisions += 1
+                report.notes.append(f"seq {b}: decision at row {c} within tolerance of its threshold")
         out.append(res)
     return out
 
@@ -334,5 +398,5 @@ def run_and_check_round(cfg, device="cuda", h_scale: float = 1.0, plant: bool = 
         print(f"[{cfg.name} scale={h_scale} plant={plant}] swaps topk/frontier/rerank = "
               f"{rep.swaps_topk}/{rep.swaps_frontier}/{rep.swaps_rerank}  score_err={rep.max_score_err:.2e} "
               f"logit_rel={rep.max_logit_rel:.2e} attn_rel={rep.max_attn_rel:.2e} lse_err={rep.max_lse_err:.2e} "
-              f"accept_len={lens} depth_hist={np.bincount(trees[0].depth).tolist()} {rep.notes}", flush=True)
+              f"near_thr={rep.near_threshold_decisions} accept_len={lens} depth_hist={np.bincount(trees[0].depth).tolist()} {rep.notes}", flush=True)
     return rep, trees, results

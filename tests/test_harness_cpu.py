@@ -143,6 +143,115 @@ def test_harness_rejects_a_wrong_parent_and_a_wrong_token():
         pu.run_and_check_round(cfg, device="cpu", round_factory=WrongMask, verbose=False)
 
 
+def test_harness_rejects_misplaced_or_stray_draft_logits():
+    """The dense draft logits are the draft distribution of the acceptance rule (Section 2.1): a pass
+    that stores two slots' rows in each other's place, leaves a row unwritten, or touches a row of
+    another pass must fail, even though the stand-in's own acceptance step stays self-consistent."""
+    cfg = _cfg(batch=2, accept="sample")
+    pu.run_and_check_round(cfg, device="cpu", h_scale=3.0, round_factory=OracleBackedRound, verbose=False)
+
+    class SwappedRows(OracleBackedRound):
+        def expand(self, d, H, W, h_seq_stride=0):
+            super().expand(d, H, W, h_seq_stride)
+            if d == 1:
+                r0, r1 = orc.draft_row(1, 0, self.k), orc.draft_row(1, 1, self.k)
+                self.draft_logits[1, [r0, r1]] = self.draft_logits[1, [r1, r0]]
+
+    class WrongSequence(OracleBackedRound):
+        def expand(self, d, H, W, h_seq_stride=0):
+            super().expand(d, H, W, h_seq_stride)
+            if d == 2:
+                r = orc.draft_row(2, 1, self.k)
+                self.draft_logits[[0, 1], r] = self.draft_logits[[1, 0], r]
+
+    class UnwrittenTail(OracleBackedRound):
+        def expand(self, d, H, W, h_seq_stride=0):
+            keep = self.draft_logits.clone()
+            super().expand(d, H, W, h_seq_stride)
+            if d == 1:
+                r = orc.draft_row(1, 2, self.k)
+                self.draft_logits[0, r, -3:] = keep[0, r, -3:]
+
+    class StrayWrite(OracleBackedRound):
+        def expand(self, d, H, W, h_seq_stride=0):
+            super().expand(d, H, W, h_seq_stride)
+            if d == 2:
+                self.draft_logits[0, orc.draft_row(1, 0, self.k), 5] += 1.0
+
+    for bad, frag in [(SwappedRows, "draft logits"), (WrongSequence, "draft logits"), (UnwrittenTail, "unwritten"),
+                      (StrayWrite, "other passes")]:
+        with pytest.raises(AssertionError, match=frag):
+            pu.run_and_check_round(cfg, device="cpu", h_scale=3.0, round_factory=bad, verbose=False)
+
+
+def test_harness_checks_sampling_against_the_oracles_own_draft_logits():
+    """A round whose acceptance step reads a wrong (but self-consistently reported) draft row agrees with
+    the oracle when the oracle is fed the same tensor; only the leg that feeds the oracle its own float64
+    logits can notice.  The stand-in below hands the harness logits that were corrupted after the expand
+    checks had passed, and accepts with them."""
+    cfg = _cfg(batch=2, accept="sample", temperature=1.0)
+    hits = 0
+    for seed in range(6):
+        c = wl.RoundConfig(**{**cfg.__dict__, "seed": 300 + seed})
+
+        class CorruptBeforeAccept(OracleBackedRound):
+            def accept(self, mode, tl, temperature=None, u_accept=None, u_bonus=None):
+                self.draft_logits[:, 0] = self.draft_logits[:, 0].flip(-1)      # the root's draft distribution, reversed
+                super().accept(mode, tl, temperature, u_accept, u_bonus)
+
+        try:
+            pu.run_and_check_round(c, device="cpu", h_scale=3.0, round_factory=CorruptBeforeAccept, verbose=False)
+        except AssertionError as e:
+            assert "own draft logits" in str(e) or "CDF edge" in str(e)
+            hits += 1
+    assert hits >= 3, "a reversed root distribution must change sampling decisions on most seeds"
+
+
+def test_near_threshold_decisions_are_admitted_and_counted():
+    """A uniform within 1e-5 * max(1, p/q) of the ratio may fall on either side of it: a round whose
+    draft logits differ from the oracle's by 1e-6 (inside the logit tolerance) and a uniform placed
+    between the two resulting ratios must pass, and the case must be counted."""
+    cfg = _cfg(batch=1, accept="sample", temperature=1.0)
+
+    class SlightlyOffLogits(OracleBackedRound):
+        def expand(self, d, H, W, h_seq_stride=0):
+            super().expand(d, H, W, h_seq_stride)
+            for s in range(1 if d == 0 else self.k):
+                self.draft_logits[0, orc.draft_row(d, s, self.k)] *= 1.0 + 2e-6
+
+    B, D, k, N, V = cfg.batch, cfg.depth, cfg.topk, cfg.n_tree, cfg.vocab
+    W = wl.make_lm_head(cfg, "cpu")
+    H_all = wl.make_hidden_states(cfg, "cpu", scale=3.0)
+    rnd = SlightlyOffLogits(B, V, cfg.hidden, D, k, N, cfg.dtype, keep_draft_logits=True)
+    states, rep = pu.lockstep_expand(rnd, cfg, H_all, W)
+    root, plen = torch.tensor([7], dtype=torch.int32), torch.tensor([5], dtype=torch.int32)
+    rnd.rerank(root, plen)
+    trees = pu.check_rerank(rnd, cfg, states, root.numpy(), plen.numpy(), rep)
+    tree = trees[0]
+    tl, _ = wl.make_target_logits(cfg, "cpu")
+    ua, ub = wl.make_uniforms(cfg, "cpu")
+    first = lambda dl: orc.accept_sample(pu.f64(tl[0]), dl, 1.0, np.full(N, 1.0 - 1e-15), pu.f64(ub[0]), tree.token,
+                                         tree.parent, tree.cand, k)
+    mine, own = first(pu.f64(rnd.draft_logits[0])), first(rep.oracle_draft_logits[0])
+    c = own.trace[0][0]
+    r_mine, r_own = mine.ratios[c], own.ratios[c]
+    assert r_mine != r_own and max(r_mine, r_own) < 1.0
+    u = np.float32(0.5 * (r_mine + r_own))
+    assert min(r_mine, r_own) < float(u) < max(r_mine, r_own), "no float32 uniform between the two ratios"
+    ua[0, c] = float(u)
+    temp, mode = torch.ones(1), torch.ones(1, dtype=torch.int32)
+    rnd.accept(mode, tl, temp, ua, ub)
+    pu.check_accept(rnd, cfg, trees, [1], tl, temp.numpy(), ua, ub, rep)
+    assert rep.near_threshold_decisions == 1
+    # the same flip far from the threshold is an error
+    ua[0, c] = float(np.float32(min(r_mine, r_own) * 0.5))
+    rnd.accept(mode, tl, temp, ua, ub)                       # accepts child c ...
+    rnd.accept_path[0, 1:] = -1                              # ... but reports a rejection of everything
+    rnd.accept_len[0] = 0
+    with pytest.raises(AssertionError):
+        pu.check_accept(rnd, cfg, trees, [1], tl, temp.numpy(), ua, ub, pu.Report(oracle_draft_logits=rep.oracle_draft_logits))
+
+
 def test_harness_tolerates_only_near_tie_swaps():
     vals = np.array([0.0, -1.0, -1.0 - 5e-6, -2.0])
     pu._admissible(vals[[0, 2, 1]], vals, np.array([0, 2, 1]), "near tie")            # swap within 1e-5: fine

@@ -212,3 +212,93 @@ def test_sampling_follows_tree_and_restarts_at_accepted_child():
     assert tested[:2] == kids0 and res.path[:2] == [0, kids0[1]]
     grandkids = [i for i in range(N) if tree.parent[i] == kids0[1]]
     assert tested[2:2 + len(grandkids)] == grandkids
+
+
+# ---------------------------------------------------------------------------
+# which draft distribution is q at a node below the root
+# ---------------------------------------------------------------------------
+
+def _tree_with_known_rows(seed, V=12, hd=6, D=3, k=3):
+    """A full tree (every candidate kept) built with a distinct, test-chosen hidden state per (pass, slot).
+    Returns the tree, the dense draft logits as the expansion stored them, and -- built here, without the
+    oracle's row helpers -- the distribution each expanded node's children were taken from, keyed by the
+    node's candidate id (-1 = root): softmax of that node's own hidden state through the LM head."""
+    rng = np.random.default_rng(seed)
+    W = rng.normal(size=(V, hd))
+    st = orc.DraftState(D, k)
+    dl = np.full((orc.n_draft_rows(D, k), V), np.nan)
+    q_of = {}
+    for d in range(D):
+        F = 1 if d == 0 else k
+        H = rng.normal(size=(F, hd)) * 2.0
+        nodes = [-1] if d == 0 else [int(c) for c in st.frontier[d]]         # who is expanded, slot by slot
+        for s, node in enumerate(nodes):
+            z = H[s] @ W.T
+            e = np.exp(z - z.max())
+            q_of[node] = e / e.sum()
+        orc.expand(st, d, H, W, draft_logits=dl)
+    tree = orc.rerank(st, orc.n_candidates(D, k) + 1, root_token=0, prefix_len=0)
+    return st, tree, dl, q_of
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_sampling_uses_the_distribution_each_parent_was_expanded_with(seed):
+    """Section 4.1: a node's children are the top-k of the distribution the draft model produced AT THAT
+    NODE; Section 2.1: that distribution is the p-hat of their acceptance test.  Every acceptance ratio the
+    oracle reports, at every depth and for expanded nodes in every frontier slot, must be p(x)/q(x) with q
+    the distribution the test itself attached to the parent -- including after rejected siblings."""
+    V, D, k, T = 12, 3, 3, 0.8
+    st, tree, dl, q_of = _tree_with_known_rows(seed)
+    N = len(tree.token)
+    rng = np.random.default_rng(1000 + seed)
+    tl0 = rng.normal(size=(N, V)) * 1.5
+    slots_seen = set()
+    for steer in itertools.product(range(k), repeat=2):                       # which child to accept at depth 1, 2
+        ua = np.full(N, 1.0 - 1e-15)
+        tl = tl0.copy()
+        cur = 0
+        for j in steer:
+            kids = [i for i in range(N) if tree.parent[i] == cur]
+            if not kids:
+                break
+            for c in kids[:j]:
+                tl[cur, tree.token[c]] = -60.0                                # p(x) ~ 0: certainly rejected
+            tl[cur, tree.token[kids[j]]] = 12.0                               # p(x) > q(x) also in the residuals
+            cur = kids[j]
+            ua[cur] = 0.0                                                     # certainly accepted
+        res = orc.accept_sample(tl, dl, T, ua, np.full(N, 0.5), tree.token, tree.parent, tree.cand, k)
+        assert res.accept_len >= 2
+        checked = 0
+        for node in res.path:
+            kids = [i for i in range(N) if tree.parent[i] == node]
+            cand = int(tree.cand[node])
+            if not kids:
+                assert cand not in q_of                                        # never expanded: no children, no q
+                continue
+            z = tl[node] / T
+            p = np.exp(z - z.max())
+            p /= p.sum()
+            q = q_of[cand].copy()
+            if cand >= 0:
+                d = orc.cand_depth(cand, k)
+                slots_seen.add((d, list(st.frontier[d]).index(cand)))
+            for c in kids:
+                if c not in res.ratios:
+                    break                                                     # an earlier sibling was accepted
+                x = int(tree.token[c])
+                assert res.ratios[c] == pytest.approx(p[x] / q[x], rel=1e-10), (node, c)
+                checked += 1
+                r = np.maximum(p - q, 0.0)
+                p = r / r.sum() if r.sum() > 0 else p
+                q[x] = 0.0
+                q = q / q.sum()
+        assert checked == len(res.ratios) and checked >= 1
+    # expanded nodes in slots other than 0 were visited at both depths, so the slot matters
+    assert {(1, 1), (1, 2)} <= slots_seen and any(d == 2 and s > 0 for d, s in slots_seen)
+
+
+def test_draft_rows_of_a_round_are_all_distinct_and_cover_the_matrix():
+    """Every (pass, slot) owns one row of the dense draft-logit matrix and the R rows are used exactly once."""
+    for D, k in [(1, 4), (3, 3), (6, 10), (8, 16)]:
+        rows = [orc.draft_row(d, s, k) for d in range(D) for s in range(1 if d == 0 else k)]
+        assert sorted(rows) == list(range(orc.n_draft_rows(D, k)))
