@@ -23,10 +23,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes per LM-head launch (fetch + write) from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE),
-# each scaled by what the counter reads for a plain 1 GiB copy; the summary is profiles/round_cfg3_llama3_8b.md.
-# None for workloads without a recorded counter run.
-MEASURED_TRAFFIC_BYTES = {3: 1057094037}
+PROFILE_SUMMARY = {3: "profiles/round_cfg3_llama3_8b.md"}
+
+
+def recorded_traffic(cfg_index):
+    """HBM bytes per LM-head launch (fetch + write) as RECORDED in the kept rocprofv3 counter summary of this
+    workload (two --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a plain copy; the summary states the
+    command).  It is read from that file, not measured by this run: the line that carries it is
+    `lm-head HBM traffic per launch: <bytes> B`.  None when no summary is kept or the line is missing."""
+    import re
+    path = PROFILE_SUMMARY.get(cfg_index)
+    if path is None:
+        return None, None
+    try:
+        text = open(os.path.join(ROOT, path)).read()
+    except OSError:
+        return None, None
+    m = re.search(r"lm-head HBM traffic per launch:\s*([0-9][0-9,]*)\s*B", text)
+    return (int(m.group(1).replace(",", "")) if m else None), path
 
 
 def algorithmic_bytes(cfg, plens):
@@ -156,8 +170,11 @@ def main():
     lm_avg_ms = lm_ms / max(lm_n, 1)
     achieved = lm_bytes / (lm_avg_ms * 1e-3) / 1e9
     round_bytes = D * lm_bytes + cfg.n_layers * attn_bytes
+    traffic, traffic_src = recorded_traffic(cfg.index)
+    if traffic_src is not None:
+        traffic_src = f"recorded counter run, {traffic_src} (not measured by this run)"
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index),
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_src,
                 "kernel": "lmhead_kernel", "bytes_per_launch": lm_bytes, "avg_launch_ms": round(lm_avg_ms, 5),
                 "launches_timed": lm_n}
     extra = {"round_algorithmic_bytes": round_bytes,

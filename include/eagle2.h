@@ -9,7 +9,10 @@
  * Common rules for every entry point
  *   - Every pointer is caller-owned DEVICE memory on the current HIP device,
  *     16-byte aligned, unless the parameter is documented as a host value.  The
- *     library never allocates, frees or keeps a pointer after the call returns.
+ *     library never allocates or frees device memory and keeps no pointer after
+ *     the call returns.  Its only mutable global state belongs to the benchmark
+ *     timing hooks at the end of this header (a pool of HIP events created by
+ *     eagle2_kernel_timing_enable, never inside a call of the method).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream).  No entry point synchronises with the host; outputs are
  *     valid once the stream reaches that point.
@@ -104,7 +107,9 @@ typedef struct eagle2_attn_cfg {
     int32_t n_kv_heads;
     int32_t head_dim;
     float   scale;         /* multiplies q.k; 0 selects 1/sqrt(head_dim)           */
-    int64_t total_prefix;  /* host value: rows of K_prefix/V_prefix = kv_offsets[B] */
+    int64_t total_prefix;  /* host value: rows of K_prefix/V_prefix; must be >= kv_offsets[B]
+                              (grid and workspace are sized from it: key chunks beyond it
+                              are ignored, never read out of bounds)                  */
 } eagle2_attn_cfg;
 
 /* Library version (major*10000 + minor*100 + patch). */
@@ -254,6 +259,18 @@ int eagle2_tree_attn_fp8kv(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn,
  *   accept_len    [B] int32 output: number of accepted draft tokens
  *   accept_path   [B, D+1] int32 output: flat rows root..last accepted, -1 padded
  *   bonus_token   [B] int32 output
+ *
+ * Failure reported in the outputs.  The workgroups that share a sampling sequence
+ * exchange partial sums through the workspace and wait for each other with a
+ * bounded spin, so they must all be resident at the same time: the launch uses at
+ * most two workgroups of 256 threads per compute unit in total and assumes that
+ * no other kernel occupies the device while it runs (work on other streams may
+ * delay it; it cannot deadlock it).  If a wait expires, or the tree arrays are
+ * malformed (a cycle, more than k children), the call still returns EAGLE2_OK and
+ * that sequence gets accept_len[b] = -1, bonus_token[b] = -1 and an accept_path of
+ * all -1; other sequences are unaffected.  Callers check accept_len[b] >= 0.
+ * eagle2_commit_kv*, eagle2_commit_round treat a negative accept_len as "nothing
+ * to commit" (see there), so a failed sequence can simply be run again.
  */
 int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
                   const float* target_logits, const float* draft_logits,
@@ -275,6 +292,7 @@ int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
  * copied.  Rows that would fall at or beyond kv_offsets[b+1] are dropped (the
  * caller sizes each region for prefix + D + 1 more rows).  prefix_len is not
  * changed here: eagle2_commit_round advances it once all layers are committed.
+ * A sequence with accept_len[b] < 0 (acceptance reported a failure) is skipped.
  *
  *   n_layers            layers committed by this call (>= 1)
  *   accept_len, accept_path   outputs of eagle2_accept
@@ -329,6 +347,9 @@ int eagle2_commit_kv_fp8(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int
  *   target_hidden  nullable; [B, N, Hd] dtype: the verifying model's feature per
  *                tree row.  next_hidden [B, Hd] dtype output (given together with
  *                target_hidden): the feature at the last accepted row.
+ * A sequence with accept_len[b] < 0 (acceptance reported a failure) emits nothing:
+ * its out_tokens row is all -1 and root_token[b], prefix_len[b], next_hidden[b]
+ * keep their values.
  */
 int eagle2_commit_round(const eagle2_cfg* cfg, const int32_t* accept_len, const int32_t* accept_path,
                         const int32_t* tree_token, const int32_t* bonus_token, const void* target_hidden,
@@ -393,7 +414,9 @@ int eagle2_draft_forward(const eagle2_cfg* cfg, const eagle2_draft_cfg* draft, c
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Kernel timing for benchmarks (not part of the method).  While enabled, every
+ * Kernel timing for benchmarks (not part of the method; the one place where the
+ * library holds state: enabling creates a fixed pool of HIP events, 2048 timed
+ * launches per slot between two reads, further launches go untimed).  While enabled, every
  * eagle2_expand records a HIP event pair around its LM-head streaming kernel and
  * every eagle2_tree_attn around its split-KV kernel, on the caller's stream.
  * eagle2_kernel_timing_read synchronises those events (host-blocking), returns

@@ -3,6 +3,7 @@
 #include "common.h"
 #include <stdarg.h>
 #include <string.h>
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -68,26 +69,29 @@ int device_cu_count() {
 }
 
 // ---- kernel timing ---------------------------------------------------------------
+// The only mutable global state of the library.  Events are created when timing is switched on
+// (a fixed pool per slot), never inside an entry point of the method; a launch that finds the pool
+// exhausted is simply not timed.
+constexpr size_t TIMING_POOL = 4096;               // events per slot = 2048 timed launches between two reads
 struct TimingSlot { std::vector<hipEvent_t> ev; size_t used = 0; };
 static std::mutex g_tmu;
-static bool g_timing = false;
+static std::atomic<bool> g_timing{false};
 static TimingSlot g_slots[2];
 
-static hipEvent_t next_event(TimingSlot& s) {
-    if (s.used == s.ev.size()) {
-        hipEvent_t e;
-        if (hipEventCreate(&e) != hipSuccess) return nullptr;
-        s.ev.push_back(e);
-    }
-    return s.ev[s.used++];
-}
 void timing_begin(int which, hipStream_t st) {
-    if (!g_timing) return;
+    if (!g_timing.load(std::memory_order_acquire)) return;
     std::lock_guard<std::mutex> lk(g_tmu);
-    hipEvent_t e = next_event(g_slots[which]);
-    if (e) (void)hipEventRecord(e, st);
+    TimingSlot& s = g_slots[which];
+    if ((s.used & 1) != 0 || s.used + 2 > s.ev.size()) return;  // unmatched begin, or no room left for a pair
+    (void)hipEventRecord(s.ev[s.used++], st);
 }
-void timing_end(int which, hipStream_t st) { timing_begin(which, st); }
+void timing_end(int which, hipStream_t st) {
+    if (!g_timing.load(std::memory_order_acquire)) return;
+    std::lock_guard<std::mutex> lk(g_tmu);
+    TimingSlot& s = g_slots[which];
+    if ((s.used & 1) == 0 || s.used >= s.ev.size()) return;    // no begin was recorded for this launch
+    (void)hipEventRecord(s.ev[s.used++], st);
+}
 
 }  // namespace eagle2
 
@@ -114,8 +118,17 @@ extern "C" size_t eagle2_workspace_bytes(const eagle2_cfg* cfg, const eagle2_att
 
 extern "C" int eagle2_kernel_timing_enable(int32_t enable) {
     std::lock_guard<std::mutex> lk(g_tmu);
-    g_timing = enable != 0;
+    if (enable) {
+        for (auto& s : g_slots) {
+            while (s.ev.size() < TIMING_POOL) {
+                hipEvent_t e;
+                E2_HIP(hipEventCreate(&e));
+                s.ev.push_back(e);
+            }
+        }
+    }
     for (auto& s : g_slots) s.used = 0;
+    g_timing.store(enable != 0, std::memory_order_release);
     return EAGLE2_OK;
 }
 

@@ -25,7 +25,8 @@ void commit_kv_kernel(int N, int D, int row_vec,            // row_vec: 16-byte 
                       u32x4* __restrict__ K_cache, u32x4* __restrict__ V_cache) {
     const int i = blockIdx.x, b = blockIdx.y, layer = blockIdx.z;
     int len = accept_len[b];
-    len = len < 0 ? 0 : (len > D ? D : len);
+    if (len < 0) return;                                     // acceptance reported a failure: nothing is committed
+    len = len > D ? D : len;
     if (i > len) return;
     const int row = accept_path[(size_t)b * (D + 1) + i];
     const int P = prefix_len[b];
@@ -70,7 +71,8 @@ void commit_kv_fp8_kernel(int N, int D, int row_vec8, int vec_per_head, int Hkv,
                           const float* __restrict__ k_scale, const float* __restrict__ v_scale) {
     const int i = blockIdx.x, b = blockIdx.y, layer = blockIdx.z;
     int len = accept_len[b];
-    len = len < 0 ? 0 : (len > D ? D : len);
+    if (len < 0) return;                                     // acceptance reported a failure: nothing is committed
+    len = len > D ? D : len;
     if (i > len) return;
     const int row = accept_path[(size_t)b * (D + 1) + i];
     const int P = prefix_len[b];
@@ -96,7 +98,13 @@ void commit_round_kernel(int N, int D, int hid_vec,
                          u32x4* __restrict__ next_hidden) {
     const int b = blockIdx.x, tid = threadIdx.x;
     int len = accept_len[b];
-    len = len < 0 ? 0 : (len > D ? D : len);
+    if (len < 0) {
+        // acceptance reported a failure for this sequence: no token is emitted and the root, the prefix
+        // length and the next feature stay as they were, so the caller can run the round again
+        if (tid <= D) out_tokens[(size_t)b * (D + 1) + tid] = -1;
+        return;
+    }
+    len = len > D ? D : len;
     const int* path = accept_path + (size_t)b * (D + 1);
     const int bonus = bonus_token[b];
     if (tid <= D) {

@@ -139,6 +139,11 @@ __device__ __forceinline__ double wave_sum(double v) {
     v += dpp_mov<DPP_MIRROR>(v);
     return ((read_lane(v, 0) + read_lane(v, 16)) + read_lane(v, 32)) + read_lane(v, 48);
 }
+// The wave waits until all of its outstanding vector-memory loads and stores have completed
+// (s_waitcnt vmcnt(0); the export and LDS/scalar counters are left at their maxima).  Used before a
+// device-scope counter increment that publishes earlier device-scope stores of the same wave.
+__device__ __forceinline__ void wait_vector_memory() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // candidate order: higher value first, then lower index
 // (bitwise operators on purpose: the short-circuit forms compile to divergent branches around two of
 // the three comparisons)

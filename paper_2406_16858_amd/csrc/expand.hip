@@ -827,10 +827,13 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
         cand_token[(size_t)b * C + cid] = key != 0ull ? key_id(key) : 0;
         cand_parent[(size_t)b * C + cid] = par;
         // The score is also read by the workgroup that picks the next frontier, possibly on
-        // another XCD: store it at device scope and wait for the acknowledgement, instead of a
-        // device-scope fence (which writes back and invalidates the whole L2).
+        // another XCD: store it at device scope (write-through to the coherence point) instead of
+        // a device-scope fence (which writes back the whole L2).  These stores and the counter
+        // increment below are all issued by wave 0; the wave waits here until every one of its
+        // outstanding stores has been acknowledged, so the counter cannot overtake a score.
         __hip_atomic_store(cand_score + (size_t)b * C + cid, sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        wait_vector_memory();
     }
     if (d + 1 >= D || static_tree) return;               // a static shape fixes the frontiers beforehand
 

@@ -678,7 +678,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
 template <int DH>
 __global__ __launch_bounds__(256)
 void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len, int N, int q0, int nq, int Hq, int Hkv, int chunk, int rows_pad,
-                              const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                              int max_chunks, const float* __restrict__ part_o, const float* __restrict__ part_ml,
                               uint16_t* __restrict__ O, float* __restrict__ lse) {
     const int b = blockIdx.x / nq, nr = blockIdx.x - b * nq, n = q0 + nr, bn = b * N + n;
     const int h = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -686,6 +686,10 @@ void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const in
     const int grp = Hq / Hkv, kvh = h / grp, rho = nr * grp + (h - kvh * grp);
     int first, nc;
     locate_seq(b, chunk, kv_offsets, kv_len, first, nc);
+    // the split-KV kernel ran max_chunks chunks (sized from the host's total_prefix); if the device offsets
+    // describe more, the excess was never computed and must not be read
+    if (first > max_chunks) first = max_chunks;
+    if (first + nc > max_chunks) nc = max_chunks - first;
     const size_t cstride = (size_t)Hkv * rows_pad;               // rows between consecutive chunks
     const size_t row0 = ((size_t)first * Hkv + kvh) * rows_pad + rho;
     float mx = NEG_BIG;
@@ -719,7 +723,7 @@ void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const in
             }
         }
     }
-    const float inv = 1.f / l;
+    const float inv = l > 0.f ? 1.f / l : 0.f;
     uint16_t* orow = O + ((size_t)bn * Hq + h) * DH;
 #pragma unroll
     for (int e = 0; e < DH / 64; ++e) {
@@ -893,10 +897,10 @@ int tree_attn_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int q0, i
     dim3 cgrid(B * nq, (Hq + 3) / 4);
     if (dh == 128)
         hipLaunchKernelGGL((tree_attn_combine_kernel<128>), cgrid, dim3(256), 0, st, offs, kv_len, N, q0, nq, Hq, Hkv, p.chunk, p.rows_pad,
-                           part_o, part_ml, (uint16_t*)O, lse);
+                           p.max_chunks, part_o, part_ml, (uint16_t*)O, lse);
     else
         hipLaunchKernelGGL((tree_attn_combine_kernel<64>), cgrid, dim3(256), 0, st, offs, kv_len, N, q0, nq, Hq, Hkv, p.chunk, p.rows_pad,
-                           part_o, part_ml, (uint16_t*)O, lse);
+                           p.max_chunks, part_o, part_ml, (uint16_t*)O, lse);
     E2_HIP(hipGetLastError());
     return EAGLE2_OK;
 }

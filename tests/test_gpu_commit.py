@@ -131,3 +131,37 @@ def test_commit_validation():
         rnd.commit_kv(off, pl, kt, kt, z, z, n_layers=2, tree_layer_stride=16, cache_layer_stride=16)
     with pytest.raises(Eagle2Error, match="together"):
         rnd.commit_round(torch.zeros(1, 4, dtype=torch.int32, device="cuda"), pl.clone(), pl, z[:1, 0], None)
+
+
+def test_commit_skips_a_sequence_whose_acceptance_failed():
+    """eagle2_accept reports an expired wait as accept_len = -1 (forced here from the host: the kernels
+    only read it).  The commit calls must leave that sequence's cache region, root, prefix length and
+    next feature untouched and emit no token, while the other sequence is committed as usual."""
+    from paper_2406_16858_amd import DraftRound
+    dev, B, N, D, Hkv, dh, Hd = "cuda", 2, 16, 3, 4, 64, 256
+    rnd = DraftRound(B, 1000, Hd, D, 4, N, "bf16", 4, Hkv, dh, total_prefix=2 * 40)
+    g = torch.Generator().manual_seed(5)
+    Kt = torch.randn((B, N, Hkv, dh), generator=g).to(torch.bfloat16).to(dev)
+    Vt = torch.randn((B, N, Hkv, dh), generator=g).to(torch.bfloat16).to(dev)
+    Kc = torch.full((2 * 40, Hkv, dh), 3.0, dtype=torch.bfloat16, device=dev)
+    Vc = torch.full_like(Kc, -3.0)
+    off = torch.tensor([0, 40, 80], dtype=torch.int64, device=dev)
+    plen = torch.tensor([10, 20], dtype=torch.int32, device=dev)
+    rnd.accept_len.copy_(torch.tensor([-1, 2], dtype=torch.int32))
+    rnd.accept_path.copy_(torch.tensor([[-1, -1, -1, -1], [0, 3, 7, -1]], dtype=torch.int32))
+    rnd.bonus_token.copy_(torch.tensor([-1, 55], dtype=torch.int32))
+    rnd.tree_token.copy_(torch.arange(B * N, dtype=torch.int32).view(B, N) + 100)
+    rnd.commit_kv(off, plen, Kt, Vt, Kc, Vc)
+    hid = torch.randn((B, N, Hd), generator=g).to(torch.bfloat16).to(dev)
+    nxt = torch.full((B, Hd), 9.0, dtype=torch.bfloat16, device=dev)
+    out = torch.full((B, D + 1), -7, dtype=torch.int32, device=dev)
+    root = torch.tensor([11, 12], dtype=torch.int32, device=dev)
+    rnd.commit_round(out, root, plen, hid, nxt)
+    torch.cuda.synchronize()
+    assert torch.all(Kc[:40] == 3.0) and torch.all(Vc[:40] == -3.0), "the failed sequence's region was written"
+    assert out[0].tolist() == [-1] * (D + 1) and int(root[0]) == 11 and int(plen[0]) == 10 and torch.all(nxt[0] == 9.0)
+    for i, row in enumerate([0, 3, 7]):
+        assert torch.equal(Kc[40 + 20 + i], Kt[1, row]) and torch.equal(Vc[40 + 20 + i], Vt[1, row])
+    assert torch.all(Kc[40 + 23:] == 3.0) and torch.all(Kc[40:40 + 20] == 3.0)
+    assert out[1].tolist() == [100 + N + 3, 100 + N + 7, 55, -1] and int(root[1]) == 55 and int(plen[1]) == 23
+    assert torch.equal(nxt[1], hid[1, 7])
