@@ -138,7 +138,7 @@ def test_commit_skips_a_sequence_whose_acceptance_failed():
     only read it).  The commit calls must leave that sequence's cache region, root, prefix length and
     next feature untouched and emit no token, while the other sequence is committed as usual."""
     from paper_2406_16858_amd import DraftRound
-    dev, B, N, D, Hkv, dh, Hd = "cuda", 2, 16, 3, 4, 64, 256
+    dev, B, N, D, Hkv, dh, Hd = "cuda", 2, 16, 3, 4, 64, 512
     rnd = DraftRound(B, 1000, Hd, D, 4, N, "bf16", 4, Hkv, dh, total_prefix=2 * 40)
     g = torch.Generator().manual_seed(5)
     Kt = torch.randn((B, N, Hkv, dh), generator=g).to(torch.bfloat16).to(dev)
