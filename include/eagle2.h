@@ -280,6 +280,29 @@ int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * eagle2_accept for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results and failure
+ * reporting as eagle2_accept, minus the workspace: the scratch (arg-max choices,
+ * failure flags, exchange slots of the sampling kernel) is a fixed device array inside
+ * the library, eagle2_accept_noalloc_scratch_bytes() long (about 73 KB; every GPU the
+ * library runs on holds one copy until the process ends).  The call allocates nothing
+ * and frees nothing; on its first use on a device it looks up that device's copy of the
+ * array (no allocation) and remembers the address.
+ *   - cfg->batch must not exceed EAGLE2_ACCEPT_NOALLOC_MAX_BATCH (n_tree <= 128 as
+ *     everywhere); larger shapes return EAGLE2_ERR_SHAPE and nothing is enqueued.
+ *   - All calls on one GPU share that GPU's array, on every stream: two calls that
+ *     overlap in time on one GPU race.  Order them on one stream (or with events).
+ *     The array keeps the last call's contents; the kernels clear what they need.
+ */
+#define EAGLE2_ACCEPT_NOALLOC_MAX_BATCH 16
+size_t eagle2_accept_noalloc_scratch_bytes(void);
+int eagle2_accept_noalloc(const eagle2_cfg* cfg, const int32_t* mode,
+                          const float* target_logits, const float* draft_logits,
+                          const float* temperature, const float* u_accept, const float* u_bonus,
+                          const int32_t* tree_token, const int32_t* tree_parent, const int32_t* tree_cand,
+                          int32_t* accept_len, int32_t* accept_path, int32_t* bonus_token, void* stream);
+
+/*
  * Commit of a round, part 1: the KV cache (Section 2.1: accepted tokens are kept
  * and the remaining draft is discarded; Appendix "Implementation Details": the KV
  * cache is pre-allocated).

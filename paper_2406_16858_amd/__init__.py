@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     FLAG_STATIC_TREE,
     RoundCfg,
     eagle2_accept,
+    eagle2_accept_noalloc,
+    eagle2_accept_noalloc_scratch_bytes,
     eagle2_commit_kv,
     eagle2_commit_kv_fp8,
     eagle2_commit_round,

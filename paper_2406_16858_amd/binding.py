@@ -80,6 +80,10 @@ def load_library():
     lib.eagle2_tree_attn_fp8kv.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg)] + [vp] * 12 + [vp, sz, vp]
     lib.eagle2_accept.restype = C.c_int
     lib.eagle2_accept.argtypes = [C.POINTER(RoundCfg)] + [vp] * 12 + [vp, sz, vp]
+    lib.eagle2_accept_noalloc.restype = C.c_int
+    lib.eagle2_accept_noalloc.argtypes = [C.POINTER(RoundCfg)] + [vp] * 12 + [vp]
+    lib.eagle2_accept_noalloc_scratch_bytes.restype = sz
+    lib.eagle2_accept_noalloc_scratch_bytes.argtypes = []
     lib.eagle2_commit_kv.restype = C.c_int
     lib.eagle2_commit_kv.argtypes = [C.POINTER(RoundCfg), C.POINTER(AttnCfg), i32, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
     lib.eagle2_commit_kv_fp8.restype = C.c_int
@@ -205,6 +209,24 @@ def eagle2_accept(cfg: RoundCfg, mode, target_logits, draft_logits, temperature,
                              _ptr(tree_cand, i32, "tree_cand"), _ptr(accept_len, i32, "accept_len"),
                              _ptr(accept_path, i32, "accept_path"), _ptr(bonus_token, i32, "bonus_token"),
                              wp, wb, _stream(stream)))
+
+
+def eagle2_accept_noalloc(cfg: RoundCfg, mode, target_logits, draft_logits, temperature, u_accept, u_bonus,
+                          tree_token, tree_parent, tree_cand, accept_len, accept_path, bonus_token, stream=None):
+    """eagle2_accept without a workspace argument: the scratch is a fixed device array inside the library."""
+    lib = load_library()
+    i32, f32 = torch.int32, torch.float32
+    _check(lib.eagle2_accept_noalloc(C.byref(cfg), _ptr(mode, i32, "mode"), _ptr(target_logits, f32, "target_logits"),
+                                     _ptr(draft_logits, f32, "draft_logits"), _ptr(temperature, f32, "temperature"),
+                                     _ptr(u_accept, f32, "u_accept"), _ptr(u_bonus, f32, "u_bonus"),
+                                     _ptr(tree_token, i32, "tree_token"), _ptr(tree_parent, i32, "tree_parent"),
+                                     _ptr(tree_cand, i32, "tree_cand"), _ptr(accept_len, i32, "accept_len"),
+                                     _ptr(accept_path, i32, "accept_path"), _ptr(bonus_token, i32, "bonus_token"),
+                                     _stream(stream)))
+
+
+def eagle2_accept_noalloc_scratch_bytes() -> int:
+    return int(load_library().eagle2_accept_noalloc_scratch_bytes())
 
 
 def eagle2_commit_kv(cfg: RoundCfg, attn: AttnCfg, n_layers: int, accept_len, accept_path, kv_offsets, prefix_len,

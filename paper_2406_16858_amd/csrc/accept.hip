@@ -14,6 +14,7 @@
 
 #include "common.h"
 #include <stdlib.h>
+#include <mutex>
 
 namespace eagle2 {
 
@@ -661,26 +662,19 @@ void sample_accept_kernel(int nwg, int V, int N, int D, int k, int R, const int*
 
 using namespace eagle2;
 
-extern "C" int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
-                             const float* target_logits, const float* draft_logits,
-                             const float* temperature, const float* u_accept, const float* u_bonus,
-                             const int32_t* tree_token, const int32_t* tree_parent, const int32_t* tree_cand,
-                             int32_t* accept_len, int32_t* accept_path, int32_t* bonus_token,
-                             void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = validate_cfg(cfg);
-    if (rc != EAGLE2_OK) return rc;
-    E2_REQUIRE(mode && target_logits && tree_token && tree_parent && tree_cand && accept_len && accept_path && bonus_token,
-               EAGLE2_ERR_ARG, "eagle2_accept: null pointer argument");
-    E2_REQUIRE(aligned16(target_logits), EAGLE2_ERR_ARG, "eagle2_accept: target_logits must be 16-byte aligned");
-    E2_REQUIRE(workspace && workspace_bytes >= accept_workspace(cfg), EAGLE2_ERR_WORKSPACE,
-               "eagle2_accept: workspace of %zu bytes, need %zu", workspace_bytes, accept_workspace(cfg));
+// Everything eagle2_accept does after its arguments are validated: ws is accept_workspace(cfg) bytes of
+// device scratch (arg-max choices, failure flags, exchange slots), whoever owns it.
+static int accept_launch(const eagle2_cfg* cfg, const int32_t* mode,
+                         const float* target_logits, const float* draft_logits,
+                         const float* temperature, const float* u_accept, const float* u_bonus,
+                         const int32_t* tree_token, const int32_t* tree_parent, const int32_t* tree_cand,
+                         int32_t* accept_len, int32_t* accept_path, int32_t* bonus_token,
+                         uint8_t* ws, hipStream_t st) {
     const bool can_sample = draft_logits && temperature && u_accept && u_bonus;
     const AcceptWs L = accept_layout(cfg);
-    uint8_t* ws = static_cast<uint8_t*>(workspace);
     int* choice = reinterpret_cast<int*>(ws + L.choice);
     unsigned* fails = reinterpret_cast<unsigned*>(ws + L.bar);
     unsigned long long* slots = reinterpret_cast<unsigned long long*>(ws + L.part);
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const int B = cfg->batch, N = cfg->n_tree, V = cfg->vocab, D = cfg->depth;
 
     const int nwords = can_sample ? B * SAMPLE_WORDS : 0;
@@ -710,4 +704,80 @@ extern "C" int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
                            accept_len, accept_path, bonus_token);
     E2_HIP(hipGetLastError());
     return EAGLE2_OK;
+}
+
+extern "C" int eagle2_accept(const eagle2_cfg* cfg, const int32_t* mode,
+                             const float* target_logits, const float* draft_logits,
+                             const float* temperature, const float* u_accept, const float* u_bonus,
+                             const int32_t* tree_token, const int32_t* tree_parent, const int32_t* tree_cand,
+                             int32_t* accept_len, int32_t* accept_path, int32_t* bonus_token,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = validate_cfg(cfg);
+    if (rc != EAGLE2_OK) return rc;
+    E2_REQUIRE(mode && target_logits && tree_token && tree_parent && tree_cand && accept_len && accept_path && bonus_token,
+               EAGLE2_ERR_ARG, "eagle2_accept: null pointer argument");
+    E2_REQUIRE(aligned16(target_logits), EAGLE2_ERR_ARG, "eagle2_accept: target_logits must be 16-byte aligned");
+    E2_REQUIRE(workspace && workspace_bytes >= accept_workspace(cfg), EAGLE2_ERR_WORKSPACE,
+               "eagle2_accept: workspace of %zu bytes, need %zu", workspace_bytes, accept_workspace(cfg));
+    return accept_launch(cfg, mode, target_logits, draft_logits, temperature, u_accept, u_bonus, tree_token, tree_parent,
+                         tree_cand, accept_len, accept_path, bonus_token, static_cast<uint8_t*>(workspace),
+                         static_cast<hipStream_t>(stream));
+}
+
+// ---- the same call for callers that cannot provide (or allocate) a workspace ------------------
+// The scratch of eagle2_accept (arg-max choices, failure flags, exchange slots) lives in a device array
+// of the library itself.  Each GPU holds its own copy at its own address; the host-side name is only a
+// handle for hipGetSymbolAddress, never a device address.
+namespace eagle2 {
+constexpr int NOALLOC_MAX_BATCH = EAGLE2_ACCEPT_NOALLOC_MAX_BATCH;
+constexpr size_t NOALLOC_BYTES =
+    ((size_t)NOALLOC_MAX_BATCH * EAGLE2_MAX_TREE * sizeof(int) + 255) / 256 * 256 +
+    ((size_t)NOALLOC_MAX_BATCH * sizeof(unsigned) + 255) / 256 * 256 +
+    ((size_t)NOALLOC_MAX_BATCH * SAMPLE_WORDS * sizeof(unsigned long long) + 255) / 256 * 256;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_BYTES];
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mu;
+static uint8_t* g_scratch_ptr[NOALLOC_MAX_DEVICES];      // device address of `scratch` on each GPU, resolved once
+
+static int scratch_on_current_device(uint8_t** out) {
+    int dev = -1;
+    E2_HIP(hipGetDevice(&dev));
+    E2_REQUIRE(dev >= 0 && dev < NOALLOC_MAX_DEVICES, EAGLE2_ERR_ARG, "eagle2_accept_noalloc: device %d outside [0, %d)", dev,
+               NOALLOC_MAX_DEVICES);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        E2_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        E2_REQUIRE(p != nullptr, EAGLE2_ERR_HIP, "eagle2_accept_noalloc: the scratch array has no address on device %d", dev);
+        g_scratch_ptr[dev] = static_cast<uint8_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return EAGLE2_OK;
+}
+}  // namespace eagle2
+
+extern "C" size_t eagle2_accept_noalloc_scratch_bytes(void) { return NOALLOC_BYTES; }
+
+extern "C" int eagle2_accept_noalloc(const eagle2_cfg* cfg, const int32_t* mode,
+                                     const float* target_logits, const float* draft_logits,
+                                     const float* temperature, const float* u_accept, const float* u_bonus,
+                                     const int32_t* tree_token, const int32_t* tree_parent, const int32_t* tree_cand,
+                                     int32_t* accept_len, int32_t* accept_path, int32_t* bonus_token, void* stream) {
+    int rc = validate_cfg(cfg);
+    if (rc != EAGLE2_OK) return rc;
+    E2_REQUIRE(mode && target_logits && tree_token && tree_parent && tree_cand && accept_len && accept_path && bonus_token,
+               EAGLE2_ERR_ARG, "eagle2_accept_noalloc: null pointer argument");
+    E2_REQUIRE(aligned16(target_logits), EAGLE2_ERR_ARG, "eagle2_accept_noalloc: target_logits must be 16-byte aligned");
+    E2_REQUIRE(cfg->batch <= NOALLOC_MAX_BATCH, EAGLE2_ERR_SHAPE,
+               "eagle2_accept_noalloc: batch %d exceeds the %d sequences the built-in scratch holds; use eagle2_accept with a workspace",
+               cfg->batch, NOALLOC_MAX_BATCH);
+    E2_REQUIRE(accept_workspace(cfg) <= NOALLOC_BYTES, EAGLE2_ERR_SHAPE,
+               "eagle2_accept_noalloc: this shape needs %zu bytes of scratch, the built-in array has %zu", accept_workspace(cfg),
+               NOALLOC_BYTES);
+    uint8_t* ws = nullptr;
+    rc = scratch_on_current_device(&ws);
+    if (rc != EAGLE2_OK) return rc;
+    return accept_launch(cfg, mode, target_logits, draft_logits, temperature, u_accept, u_bonus, tree_token, tree_parent,
+                         tree_cand, accept_len, accept_path, bonus_token, ws, static_cast<hipStream_t>(stream));
 }
