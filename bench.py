@@ -64,6 +64,9 @@ def main():
                     help="also run the draft model's decoder layer before every LM-head pass (not the headline metric)")
     ap.add_argument("--fp8-kv", action="store_true",
                     help="keep the prefix KV cache as 8-bit E4M3 codes (eagle2_tree_attn_fp8kv; a variant, not the headline metric)")
+    ap.add_argument("--attn-layers", type=int, default=0,
+                    help="run eagle2_tree_attn over this many independent seeded KV layers per round instead of the "
+                         "configuration's own count (secondary measurement: --config 3 --attn-layers 32)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -89,6 +92,8 @@ def main():
         print(json.dumps({"calibrate_copy_bytes": n, "copies": 5}))
         return
     cfg = wl.get_config(args.config)
+    if args.attn_layers > 0:
+        cfg = cfg.scaled(n_layers=args.attn_layers)
     B, D, k, N, V = cfg.batch, cfg.depth, cfg.topk, cfg.n_tree, cfg.vocab
 
     # ---- inputs, resident in HBM -------------------------------------------------
@@ -224,6 +229,8 @@ def main():
         name += "_with_draft_model"
     if args.fp8_kv:
         name += "_fp8_prefix_kv"
+    if args.attn_layers > 0:
+        name += f"_attn_layers_{args.attn_layers}"
     out = {"metric": name,
            "value": round(rounds_per_s, 2), "unit": "rounds/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
