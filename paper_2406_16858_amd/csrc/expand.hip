@@ -9,7 +9,7 @@
 //                       joint scores and picks the next frontier
 // With more rows (batched serving) the first kernel is replaced by three:
 //   pack_h_kernel       re-tiles the frontier rows into MFMA fragment order
-//   lmhead_gemm_kernel  streams W once per 160 rows and writes the raw logits
+//   lmhead_gemm128_kernel (bf16) / lmhead_gemm_kernel (float32)  stream W once per 160 rows and write the raw logits
 //   row_stats_kernel    turns each row's logits into the same partials
 //
 // lmhead_kernel layout.  The contraction runs on the matrix cores with the *weight tile*
@@ -22,6 +22,7 @@
 // next stage's loads are in flight while the current stage is multiplied.
 
 #include "common.h"
+#include <type_traits>
 
 namespace eagle2 {
 
@@ -551,6 +552,205 @@ void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     }
 }
 
+// bf16, many rows: 128 vocab rows x up to 160 frontier rows per workgroup of 8 waves, one workgroup per
+// compute unit, loading waves and multiplying waves.  Both operands are staged in LDS and shared; a step is
+// 128 B of K: the W tile (128 rows x 128 B, swizzled 16-byte slots) and two 1 KiB fragments per 16-row
+// frontier block (as they lie in the re-tiled copy).  A compute unit therefore fetches every frontier
+// fragment once per 128 vocab rows, where lmhead_gemm_kernel's four waves each fetch their own per 64 rows.
+// Waves 4-7 only load, straight from global memory into LDS (global_load_lds: no registers, no LDS
+// writes by the waves): waves 4 and 5 stream 64 W rows each into a ring of five steps, four steps (64 KB per
+// compute unit) ahead of the multiplication; waves 6 and 7 copy ten frontier fragments each from L2 into a
+// ring of three, two steps ahead.  The two kinds of load sit in different waves because a wave's loads
+// complete in order: waiting for a young fragment would mean waiting for every older W load.  Waves 0-3
+// only multiply: wave (wh, hh) takes vocab rows 64 wh .. +63 and frontier blocks 5 hh .. 5 hh + 4 over the
+// whole K (no split-K), 20 MFMAs per 64-byte K step from 4 + 5 fragment reads, and never issues a load, so a
+// full memory pipeline stalls a loading wave, not the matrix cores.  One barrier per step.
+constexpr int G2_THREADS = 512;
+constexpr int G2_ROWS = 128;                           // vocab rows per task
+constexpr int G2_WSTEP = G2_ROWS * 128;                // bytes of W per step (128 B of K per row)
+constexpr int G2_HSTEP = GB_MBMAX * 2 * 1024;          // bytes of frontier fragments per step (10 blocks x 2 K steps)
+constexpr int G2_WRING = 5, G2_HRING = 3;
+constexpr int G2_SMEM = G2_WRING * G2_WSTEP + G2_HRING * G2_HSTEP;   // 143,360 of the 163,840 bytes
+
+__global__ __launch_bounds__(G2_THREADS, 1)
+void lmhead_gemm128_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
+                           const uint8_t* __restrict__ Hp, int M, int F, int B,
+                           unsigned* __restrict__ done_count, float* __restrict__ logits_ws,
+                           float* __restrict__ logits_out, int logit_rows_per_seq, int logit_row_base) {
+    typedef __attribute__((address_space(1))) const void* gptr;
+    typedef __attribute__((address_space(3))) void* lptr;
+    constexpr int MH = GB_MBMAX / 2;                   // frontier blocks per multiplying wave
+    __shared__ __align__(1024) uint8_t smem[G2_SMEM];
+    uint8_t* const sW = smem;
+    uint8_t* const sH = smem + G2_WRING * G2_WSTEP;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int G = gridDim.x;
+    const int mb0 = blockIdx.y * GB_MBMAX;
+    const int nmb = min(GB_MBMAX, (M + 15) / 16 - mb0);   // >= 1
+    const int ksteps = row_bytes / 64;
+    const int nstep = row_bytes / 128;                 // steps per task (>= 8)
+    const int ntask = (V + G2_ROWS - 1) / G2_ROWS;
+    const int tq = ntask / G, tr = ntask - tq * G;
+    const int my_tasks = tq + ((int)blockIdx.x < tr ? 1 : 0);
+    const int task_first = (int)blockIdx.x * tq + min((int)blockIdx.x, tr);
+    const int total = my_tasks * nstep;
+
+    if (blockIdx.x == 0 && blockIdx.y == 0)            // counters of the merge kernel's last-arrival test
+        for (int i = tid; i < B; i += G2_THREADS) done_count[i] = 0u;
+
+    if (w >= 6) {
+        // ---- fragment waves: ten of a step's twenty fragments each ----
+        const int ph = w - 6;
+        int st = 0;                                    // step inside its task of the next step to request (no division per step)
+        auto issue_h = [&](int h) {
+            uint8_t* dst = sH + (h % G2_HRING) * G2_HSTEP;
+#pragma unroll
+            for (int j = 0; j < 10; ++j) {
+                const int f = ph * 10 + j;             // fragment (block f / 2, K step f % 2)
+                int blk = f >> 1;
+                blk = blk < nmb ? blk : nmb - 1;       // (blocks beyond nmb: the last block again, never read)
+                const uint8_t* src = Hp + ((size_t)(mb0 + blk) * ksteps + (size_t)st * 2 + (f & 1)) * 1024 + lane * 16;
+                __builtin_amdgcn_global_load_lds((gptr)src, (lptr)(dst + f * 1024), 16, 0, 0);
+            }
+            st = st + 1 == nstep ? 0 : st + 1;
+        };
+        // a step's ten loads have landed once only those of younger steps are outstanding (in-order completion)
+        auto wait_younger = [&](int n) {
+            if (n >= 2) __builtin_amdgcn_s_waitcnt(0x4F74);        // vmcnt(20)
+            else if (n == 1) __builtin_amdgcn_s_waitcnt(0x0F7A);   // vmcnt(10)
+            else __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0)
+        };
+        static_assert(G2_HRING <= 3 && G2_WRING <= 7, "the waits cover two younger fragment steps and six younger W steps");
+#pragma unroll
+        for (int j = 0; j < G2_HRING; ++j) if (j < total) issue_h(j);
+        if (total > 0) wait_younger(min(total - 1, G2_HRING - 1));
+        __syncthreads();                               // step 0 is in LDS
+        for (int h = 0; h < total; ++h) {
+            if (h + 1 < total) wait_younger(min(total - 2 - h, G2_HRING - 2));
+            __syncthreads();                           // step h is multiplied, step h + 1 is in LDS
+            if (h + G2_HRING < total) issue_h(h + G2_HRING);
+        }
+    } else if (w >= 4) {
+        // ---- W waves: 64 of the tile's 128 rows each; a load instruction fills 1 KiB of LDS = 8 rows x 128 B,
+        // lane (r, p) = (l / 8, l % 8) owns position p of its row and fetches the source piece the swizzle puts
+        // there.  Rows beyond V re-read the last row (never stored). ----
+        const int pw = w - 4;
+        int ti = 0, st = 0;                            // task and step inside it of the next step to request
+        const int lr = lane >> 3, lp = lane & 7;
+        auto issue_w = [&](int h) {
+            const size_t kb = (size_t)st * 128;
+            uint8_t* dst = sW + (h % G2_WRING) * G2_WSTEP;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int r0 = pw * 64 + i * 8, rl = r0 + lr;
+                int row = (task_first + ti) * G2_ROWS + rl;
+                row = row < V ? row : V - 1;
+                const uint8_t* src = W + (size_t)row * row_bytes + kb + ((lp ^ ((rl >> 1) & 7)) << 4);
+                __builtin_amdgcn_global_load_lds((gptr)src, (lptr)(dst + r0 * 128), 16, 0, 0);
+            }
+            if (++st == nstep) { st = 0; ++ti; }
+        };
+        auto wait_younger = [&](int n) {               // eight loads per step
+            if (n >= 6) __builtin_amdgcn_s_waitcnt(0xCF70);        // vmcnt(48)
+            else if (n == 5) __builtin_amdgcn_s_waitcnt(0x8F78);   // vmcnt(40)
+            else if (n == 4) __builtin_amdgcn_s_waitcnt(0x8F70);   // vmcnt(32)
+            else if (n == 3) __builtin_amdgcn_s_waitcnt(0x4F78);   // vmcnt(24)
+            else if (n == 2) __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
+            else if (n == 1) __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8)
+            else __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0)
+        };
+#pragma unroll
+        for (int j = 0; j < G2_WRING; ++j) if (j < total) issue_w(j);
+        if (total > 0) wait_younger(min(total - 1, G2_WRING - 1));
+        __syncthreads();                               // step 0 is in LDS
+        for (int h = 0; h < total; ++h) {
+            if (h + 1 < total) wait_younger(min(total - 2 - h, G2_WRING - 2));
+            __syncthreads();                           // step h is multiplied, step h + 1 is in LDS
+            if (h + G2_WRING < total) issue_w(h + G2_WRING);
+        }
+    } else {
+        // ---- multiplying waves ----
+        const int m16 = lane & 15, g = lane >> 4;      // MFMA lane coordinates
+        const int wh = w & 1, hh = w >> 1;
+        const int hfirst = hh * MH;
+        const int hcnt = max(0, min(MH, nmb - hfirst));   // this wave's frontier blocks (uniform)
+        float* lrow[MH];
+#pragma unroll
+        for (int jj = 0; jj < MH; ++jj) {
+            const int m = (mb0 + hfirst + jj) * 16 + m16;
+            lrow[jj] = (jj < hcnt && m < M) ? logit_row_ptr(m, F, V, logits_ws, logits_out, logit_rows_per_seq, logit_row_base)
+                                            : nullptr;
+        }
+        floatx4 acc[MH][4];
+#pragma unroll
+        for (int jj = 0; jj < MH; ++jj)
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) acc[jj][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
+        // this lane's byte offset inside a W step for K step 0 of W block 0 (rows 16 nb + m16 share the swizzle)
+        const unsigned wlane = (wh * 64 + m16) * 128;
+        const int wswz = (m16 >> 1) & 7;
+        __syncthreads();                               // step 0 is in LDS
+        // FULL: the wave has all five frontier blocks -- straight-line code (all 18 fragment reads of a step are
+        // requested up front; LDS returns them in order, so the first MFMAs start after five of them).  Otherwise
+        // the blocks beyond hcnt are skipped with wave-uniform branches.
+        auto run = [&](auto full_c) {
+            constexpr bool FULL = decltype(full_c)::value;
+            int ti = 0, st = 0;                        // task and step inside it (no division per step)
+            for (int h = 0; h < total; ++h) {
+                const uint8_t* wb = sW + (h % G2_WRING) * G2_WSTEP + wlane;
+                const uint8_t* hb = sH + (h % G2_HRING) * G2_HSTEP + lane * 16;
+                u32x4 wf[2][4], hf[2][MH];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {          // 64-byte K steps of the step
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb)
+                        wf[t][nb] = *reinterpret_cast<const u32x4*>(wb + nb * 16 * 128 + (((t * 4 + g) ^ wswz) << 4));
+#pragma unroll
+                    for (int jj = 0; jj < MH; ++jj)
+                        if (FULL || jj < hcnt) hf[t][jj] = *reinterpret_cast<const u32x4*>(hb + ((hfirst + jj) * 2 + t) * 1024);
+                }
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int jj = 0; jj < MH; ++jj)
+                        if (FULL || jj < hcnt) {
+#pragma unroll
+                            for (int nb = 0; nb < 4; ++nb)
+                                acc[jj][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    __builtin_bit_cast(bf16x8, wf[t][nb]), __builtin_bit_cast(bf16x8, hf[t][jj]), acc[jj][nb], 0, 0, 0);
+                        }
+                if (++st == nstep) {
+                    // task finished: output register i of W block nb is vocab row 128 task + 64 wh + 16 nb + 4 g + i,
+                    // frontier row of lrow[jj]
+                    const int vb = (task_first + ti) * G2_ROWS + wh * 64 + g * 4;
+#pragma unroll
+                    for (int jj = 0; jj < MH; ++jj) {
+#pragma unroll
+                        for (int nb = 0; nb < 4; ++nb) {
+                            const int v0 = vb + nb * 16;
+                            if ((FULL || jj < hcnt) && lrow[jj] != nullptr && v0 < V) {
+                                const floatx4 y = acc[jj][nb];
+                                if (v0 + 3 < V && (V & 3) == 0) {
+                                    *reinterpret_cast<floatx4*>(lrow[jj] + v0) = y;
+                                } else {
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i) if (v0 + i < V) lrow[jj][v0 + i] = y[i];
+                                }
+                            }
+                            acc[jj][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
+                        }
+                    }
+                    st = 0;
+                    ++ti;
+                }
+                __syncthreads();                       // step h + 1 is in LDS; this step's buffers may be overwritten
+            }
+        };
+        if (hcnt == MH) run(std::integral_constant<bool, true>{});
+        else run(std::integral_constant<bool, false>{});
+    }
+}
+
 // (max, sum-exp, top-KC) of RS_CHUNK logits of one frontier row, in the partial format of
 // lmhead_kernel: grid (M, chunks), partial index = chunk; a thread holds 16 values, a wave
 // finds its KC best by counting among the few values above a bound, the four waves' lists are
@@ -866,6 +1066,12 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
 
 // out[M, N] (float32, dense) = X[M, K] . W[N, K]^T for M > 16 rows: pack_h_kernel + lmhead_gemm_kernel.
 // X row m = (b, s) lives at X + b * x_seq_bytes + s * row_bytes; hp_ws needs ceil(M/16)*16 * row_bytes bytes.
+static int gemm128_grid(int n_rows) {                  // one workgroup per compute unit, at most one per task
+    const int ntask = (n_rows + G2_ROWS - 1) / G2_ROWS;
+    const int cus = device_cu_count();
+    return ntask < cus ? ntask : cus;
+}
+
 int gemm_rows(bool bf16, const void* X, int64_t x_seq_bytes, int M, int F, const void* W, int N, int row_bytes,
               float* out, void* hp_ws, unsigned* done_count, int n_done, hipStream_t st) {
     const int mblks = (M + 15) / 16;
@@ -878,7 +1084,7 @@ int gemm_rows(bool bf16, const void* X, int64_t x_seq_bytes, int M, int F, const
                        static_cast<const uint8_t*>(X), x_seq_bytes, row_bytes, M, F, static_cast<u32x4*>(hp_ws), npieces);
     E2_HIP(hipGetLastError());
     if (bf16)
-        hipLaunchKernelGGL((lmhead_gemm_kernel<true>), dim3(gg, ny), dim3(LM_THREADS), GB_SMEM, st, static_cast<const uint8_t*>(W),
+        hipLaunchKernelGGL(lmhead_gemm128_kernel, dim3(gemm128_grid(N), ny), dim3(G2_THREADS), 0, st, static_cast<const uint8_t*>(W),
                            row_bytes, N, static_cast<const uint8_t*>(hp_ws), M, F, n_done, done_count, out,
                            static_cast<float*>(nullptr), 0, 0);
     else
@@ -946,9 +1152,14 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
                            reinterpret_cast<u32x4*>(Hp), npieces);
         E2_HIP(hipGetLastError());
         timing_begin(0, st);
-        hipLaunchKernelGGL((lmhead_gemm_kernel<BF16>), dim3(gg, ny), dim3(LM_THREADS), GB_SMEM, st,
-                           reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab, Hp, M, F, cfg->batch, done_count,
-                           logits_ws, draft_logits, R, row_base);
+        if constexpr (BF16)
+            hipLaunchKernelGGL(lmhead_gemm128_kernel, dim3(gemm128_grid(cfg->vocab), ny), dim3(G2_THREADS), 0, st,
+                               reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab, Hp, M, F, cfg->batch, done_count,
+                               logits_ws, draft_logits, R, row_base);
+        else
+            hipLaunchKernelGGL((lmhead_gemm_kernel<BF16>), dim3(gg, ny), dim3(LM_THREADS), GB_SMEM, st,
+                               reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab, Hp, M, F, cfg->batch, done_count,
+                               logits_ws, draft_logits, R, row_base);
         timing_end(0, st);
         E2_HIP(hipGetLastError());
         G = (cfg->vocab + RS_CHUNK - 1) / RS_CHUNK;
