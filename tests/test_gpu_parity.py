@@ -52,6 +52,12 @@ SMALL = [
     _small("batch41_rows205_fp32", dtype="fp32", batch=41, depth=2, n_tree=12, hidden=256, vocab=4100, n_q_heads=2, n_kv_heads=2,
            prefix_lo=0, prefix_hi=20, seed=13),
     _small("batch5_k16_vocab2048", batch=5, topk=16, depth=2, n_tree=30, vocab=2048, seed=14, accept="sample"),
+    # many rows AND more 128-row vocabulary tasks than compute units: every workgroup of the many-row LM head runs
+    # several tasks back to back (ring buffers carried across task ends, output stores in mid-stream), ragged last task
+    _small("batch3_rows30_vocab100003", batch=3, topk=10, depth=2, n_tree=14, vocab=100003, hidden=512, accept="mixed",
+           prefix_lo=0, prefix_hi=50, seed=15),
+    _small("batch17_rows170_vocab66000", batch=17, topk=10, depth=2, n_tree=12, vocab=66000, hidden=512, accept="greedy",
+           prefix_lo=0, prefix_hi=30, seed=16),
 ]
 
 
