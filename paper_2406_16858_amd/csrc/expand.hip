@@ -8,7 +8,7 @@
 //   expand_merge_kernel merges the partials, appends the k children per row with their
 //                       joint scores and picks the next frontier
 // With more rows (batched serving) the first kernel is replaced by three:
-//   pack_h_kernel       re-tiles the frontier rows into MFMA fragment order
+//   pack_h_kernel       (float32 only) re-tiles the frontier rows into MFMA fragment order
 //   lmhead_gemm128_kernel (bf16) / lmhead_gemm_kernel (float32)  stream W once per 160 rows and write the raw logits
 //   row_stats_kernel    turns each row's logits into the same partials
 //
@@ -554,27 +554,27 @@ void lmhead_gemm_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
 
 // bf16, many rows: 128 vocab rows x up to 160 frontier rows per workgroup of 8 waves, one workgroup per
 // compute unit, loading waves and multiplying waves.  Both operands are staged in LDS and shared; a step is
-// 128 B of K: the W tile (128 rows x 128 B, swizzled 16-byte slots) and two 1 KiB fragments per 16-row
-// frontier block (as they lie in the re-tiled copy).  A compute unit therefore fetches every frontier
-// fragment once per 128 vocab rows, where lmhead_gemm_kernel's four waves each fetch their own per 64 rows.
+// 128 B of K of the W tile (128 rows) and of the frontier tile (160 rows), both rows x 128 B with swizzled
+// 16-byte slots, both read from the caller's row-major tensors.  A compute unit therefore fetches every frontier
+// row once per 128 vocab rows, where lmhead_gemm_kernel's four waves each fetch their own fragments per 64 rows.
 // Waves 4-7 only load, straight from global memory into LDS (global_load_lds: no registers, no LDS
 // writes by the waves): waves 4 and 5 stream 64 W rows each into a ring of five steps, four steps (64 KB per
-// compute unit) ahead of the multiplication; waves 6 and 7 copy ten frontier fragments each from L2 into a
+// compute unit) ahead of the multiplication; waves 6 and 7 copy 80 frontier rows each from L2 into a
 // ring of three, two steps ahead.  The two kinds of load sit in different waves because a wave's loads
-// complete in order: waiting for a young fragment would mean waiting for every older W load.  Waves 0-3
+// complete in order: waiting for a young frontier load would mean waiting for every older W load.  Waves 0-3
 // only multiply: wave (wh, hh) takes vocab rows 64 wh .. +63 and frontier blocks 5 hh .. 5 hh + 4 over the
-// whole K (no split-K), 20 MFMAs per 64-byte K step from 4 + 5 fragment reads, and never issues a load, so a
+// whole K (no split-K), 20 MFMAs per 64-byte K step from 4 + 5 fragment reads out of the two tiles, and never issues a load, so a
 // full memory pipeline stalls a loading wave, not the matrix cores.  One barrier per step.
 constexpr int G2_THREADS = 512;
 constexpr int G2_ROWS = 128;                           // vocab rows per task
 constexpr int G2_WSTEP = G2_ROWS * 128;                // bytes of W per step (128 B of K per row)
-constexpr int G2_HSTEP = GB_MBMAX * 2 * 1024;          // bytes of frontier fragments per step (10 blocks x 2 K steps)
+constexpr int G2_HSTEP = GB_MBMAX * 16 * 128;          // bytes of the frontier tile per step (160 rows x 128 B of K)
 constexpr int G2_WRING = 5, G2_HRING = 3;
 constexpr int G2_SMEM = G2_WRING * G2_WSTEP + G2_HRING * G2_HSTEP;   // 143,360 of the 163,840 bytes
 
 __global__ __launch_bounds__(G2_THREADS, 1)
 void lmhead_gemm128_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
-                           const uint8_t* __restrict__ Hp, int M, int F, int B,
+                           const uint8_t* __restrict__ Hraw, int64_t h_seq_bytes, int M, int F, int B,
                            unsigned* __restrict__ done_count, float* __restrict__ logits_ws,
                            float* __restrict__ logits_out, int logit_rows_per_seq, int logit_row_base) {
     typedef __attribute__((address_space(1))) const void* gptr;
@@ -587,7 +587,6 @@ void lmhead_gemm128_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     const int G = gridDim.x;
     const int mb0 = blockIdx.y * GB_MBMAX;
     const int nmb = min(GB_MBMAX, (M + 15) / 16 - mb0);   // >= 1
-    const int ksteps = row_bytes / 64;
     const int nstep = row_bytes / 128;                 // steps per task (>= 8)
     const int ntask = (V + G2_ROWS - 1) / G2_ROWS;
     const int tq = ntask / G, tr = ntask - tq * G;
@@ -599,19 +598,27 @@ void lmhead_gemm128_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
         for (int i = tid; i < B; i += G2_THREADS) done_count[i] = 0u;
 
     if (w >= 6) {
-        // ---- fragment waves: ten of a step's twenty fragments each ----
+        // ---- frontier waves: 80 of the 160 frontier rows each, straight from the caller's row-major rows (L2-resident:
+        // 1.3 MB at 160 rows).  Like the W tile, a step of the frontier tile is rows x 128 B with swizzled 16-byte
+        // slots; a load instruction fills 1 KiB = 8 rows x 128 B, lane (r, p) = (l / 8, l % 8).  Rows beyond M repeat
+        // row M - 1 (their products are never stored). ----
         const int ph = w - 6;
+        const int lr = lane >> 3, lp = lane & 7;
+        const uint8_t* hsrc[10];                       // this lane's source row of each of the wave's ten instructions, at its piece
+#pragma unroll
+        for (int i = 0; i < 10; ++i) {
+            const int rl = (ph * 10 + i) * 8 + lr;     // row inside the 160-row tile
+            int m = mb0 * 16 + rl;
+            m = m < M ? m : M - 1;
+            const int b = m / F, sl = m - b * F;
+            hsrc[i] = Hraw + (int64_t)b * h_seq_bytes + (int64_t)sl * row_bytes + ((lp ^ ((rl >> 1) & 7)) << 4);
+        }
         int st = 0;                                    // step inside its task of the next step to request (no division per step)
         auto issue_h = [&](int h) {
             uint8_t* dst = sH + (h % G2_HRING) * G2_HSTEP;
 #pragma unroll
-            for (int j = 0; j < 10; ++j) {
-                const int f = ph * 10 + j;             // fragment (block f / 2, K step f % 2)
-                int blk = f >> 1;
-                blk = blk < nmb ? blk : nmb - 1;       // (blocks beyond nmb: the last block again, never read)
-                const uint8_t* src = Hp + ((size_t)(mb0 + blk) * ksteps + (size_t)st * 2 + (f & 1)) * 1024 + lane * 16;
-                __builtin_amdgcn_global_load_lds((gptr)src, (lptr)(dst + f * 1024), 16, 0, 0);
-            }
+            for (int i = 0; i < 10; ++i)
+                __builtin_amdgcn_global_load_lds((gptr)(hsrc[i] + (size_t)st * 128), (lptr)(dst + (ph * 10 + i) * 1024), 16, 0, 0);
             st = st + 1 == nstep ? 0 : st + 1;
         };
         // a step's ten loads have landed once only those of younger steps are outstanding (in-order completion)
@@ -698,7 +705,7 @@ void lmhead_gemm128_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
             int ti = 0, st = 0;                        // task and step inside it (no division per step)
             for (int h = 0; h < total; ++h) {
                 const uint8_t* wb = sW + (h % G2_WRING) * G2_WSTEP + wlane;
-                const uint8_t* hb = sH + (h % G2_HRING) * G2_HSTEP + lane * 16;
+                const uint8_t* hb = sH + (h % G2_HRING) * G2_HSTEP + (hfirst * 16 + m16) * 128;
                 u32x4 wf[2][4], hf[2][MH];
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {          // 64-byte K steps of the step
@@ -707,7 +714,7 @@ void lmhead_gemm128_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
                         wf[t][nb] = *reinterpret_cast<const u32x4*>(wb + nb * 16 * 128 + (((t * 4 + g) ^ wswz) << 4));
 #pragma unroll
                     for (int jj = 0; jj < MH; ++jj)
-                        if (FULL || jj < hcnt) hf[t][jj] = *reinterpret_cast<const u32x4*>(hb + ((hfirst + jj) * 2 + t) * 1024);
+                        if (FULL || jj < hcnt) hf[t][jj] = *reinterpret_cast<const u32x4*>(hb + jj * 16 * 128 + (((t * 4 + g) ^ wswz) << 4));
                 }
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
@@ -1075,22 +1082,24 @@ static int gemm128_grid(int n_rows) {                  // one workgroup per comp
 int gemm_rows(bool bf16, const void* X, int64_t x_seq_bytes, int M, int F, const void* W, int N, int row_bytes,
               float* out, void* hp_ws, unsigned* done_count, int n_done, hipStream_t st) {
     const int mblks = (M + 15) / 16;
+    const int ny = (mblks + GB_MBMAX - 1) / GB_MBMAX;
+    if (bf16) {                                        // reads X as it lies
+        hipLaunchKernelGGL(lmhead_gemm128_kernel, dim3(gemm128_grid(N), ny), dim3(G2_THREADS), 0, st, static_cast<const uint8_t*>(W),
+                           row_bytes, N, static_cast<const uint8_t*>(X), x_seq_bytes, M, F, n_done, done_count, out,
+                           static_cast<float*>(nullptr), 0, 0);
+        E2_HIP(hipGetLastError());
+        return EAGLE2_OK;
+    }
     const int ntask = (N + LM_ROWS - 1) / LM_ROWS;
     int gg = 2 * device_cu_count();
     if (gg > ntask) gg = ntask;
-    const int ny = (mblks + GB_MBMAX - 1) / GB_MBMAX;
     const size_t npieces = (size_t)mblks * 16 * row_bytes / 16;
     hipLaunchKernelGGL(pack_h_kernel, dim3((unsigned)((npieces + 255) / 256)), dim3(256), 0, st,
                        static_cast<const uint8_t*>(X), x_seq_bytes, row_bytes, M, F, static_cast<u32x4*>(hp_ws), npieces);
     E2_HIP(hipGetLastError());
-    if (bf16)
-        hipLaunchKernelGGL(lmhead_gemm128_kernel, dim3(gemm128_grid(N), ny), dim3(G2_THREADS), 0, st, static_cast<const uint8_t*>(W),
-                           row_bytes, N, static_cast<const uint8_t*>(hp_ws), M, F, n_done, done_count, out,
-                           static_cast<float*>(nullptr), 0, 0);
-    else
-        hipLaunchKernelGGL((lmhead_gemm_kernel<false>), dim3(gg, ny), dim3(LM_THREADS), GB_SMEM, st, static_cast<const uint8_t*>(W),
-                           row_bytes, N, static_cast<const uint8_t*>(hp_ws), M, F, n_done, done_count, out,
-                           static_cast<float*>(nullptr), 0, 0);
+    hipLaunchKernelGGL((lmhead_gemm_kernel<false>), dim3(gg, ny), dim3(LM_THREADS), GB_SMEM, st, static_cast<const uint8_t*>(W),
+                       row_bytes, N, static_cast<const uint8_t*>(hp_ws), M, F, n_done, done_count, out,
+                       static_cast<float*>(nullptr), 0, 0);
     E2_HIP(hipGetLastError());
     return EAGLE2_OK;
 }
@@ -1145,21 +1154,23 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
         if (gg > ntask) gg = ntask;
         const int ny = (mblks + GB_MBMAX - 1) / GB_MBMAX;
         float* logits_ws = reinterpret_cast<float*>(ws + L.logits);
-        uint8_t* Hp = ws + L.hp;
-        const size_t npieces = (size_t)mblks * 16 * row_bytes / 16;
-        hipLaunchKernelGGL(pack_h_kernel, dim3((unsigned)((npieces + 255) / 256)), dim3(256), 0, st,
-                           reinterpret_cast<const uint8_t*>(H), stride_el * elem_size(cfg), row_bytes, M, F,
-                           reinterpret_cast<u32x4*>(Hp), npieces);
-        E2_HIP(hipGetLastError());
-        timing_begin(0, st);
-        if constexpr (BF16)
+        if constexpr (BF16) {                          // reads H as it lies
+            timing_begin(0, st);
             hipLaunchKernelGGL(lmhead_gemm128_kernel, dim3(gemm128_grid(cfg->vocab), ny), dim3(G2_THREADS), 0, st,
-                               reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab, Hp, M, F, cfg->batch, done_count,
-                               logits_ws, draft_logits, R, row_base);
-        else
+                               reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab, reinterpret_cast<const uint8_t*>(H),
+                               stride_el * elem_size(cfg), M, F, cfg->batch, done_count, logits_ws, draft_logits, R, row_base);
+        } else {
+            uint8_t* Hp = ws + L.hp;
+            const size_t npieces = (size_t)mblks * 16 * row_bytes / 16;
+            hipLaunchKernelGGL(pack_h_kernel, dim3((unsigned)((npieces + 255) / 256)), dim3(256), 0, st,
+                               reinterpret_cast<const uint8_t*>(H), stride_el * elem_size(cfg), row_bytes, M, F,
+                               reinterpret_cast<u32x4*>(Hp), npieces);
+            E2_HIP(hipGetLastError());
+            timing_begin(0, st);
             hipLaunchKernelGGL((lmhead_gemm_kernel<BF16>), dim3(gg, ny), dim3(LM_THREADS), GB_SMEM, st,
                                reinterpret_cast<const uint8_t*>(W), row_bytes, cfg->vocab, Hp, M, F, cfg->batch, done_count,
                                logits_ws, draft_logits, R, row_base);
+        }
         timing_end(0, st);
         E2_HIP(hipGetLastError());
         G = (cfg->vocab + RS_CHUNK - 1) / RS_CHUNK;
