@@ -7,10 +7,12 @@
 //                       emits a partial (max, sum-exp, top-k) over the vocab rows it saw
 //   expand_merge_kernel merges the partials, appends the k children per row with their
 //                       joint scores and picks the next frontier
-// With more rows (batched serving) the first kernel is replaced by three:
-//   pack_h_kernel       (float32 only) re-tiles the frontier rows into MFMA fragment order
-//   lmhead_gemm128_kernel (bf16) / lmhead_gemm_kernel (float32)  stream W once per 160 rows and write the raw logits
-//   row_stats_kernel    turns each row's logits into the same partials
+// With more rows (batched serving) there are two other kernels:
+//   lmhead_gemm128_kernel (bf16) / lmhead_gemm_kernel (float32, after pack_h_kernel has re-tiled
+//                       the frontier rows into MFMA fragment order)  stream W once per 160 rows
+//                       and write the raw logits
+//   row_expand_kernel   one workgroup per row: the row's (max, sum-exp, top-k) and then the
+//                       same merge, children and frontier selection
 //
 // lmhead_kernel layout.  The contraction runs on the matrix cores with the *weight tile*
 // as the 16-row A operand and the (zero-padded to 16) frontier rows as the B operand, so
@@ -346,12 +348,11 @@ void lmhead_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
 // With M > 16 rows the per-lane statistics of lmhead_kernel no longer fit in registers, and
 // re-streaming W once per 16-row block multiplies the HBM traffic.  Instead W is streamed once
 // for up to 160 rows: lmhead_gemm_kernel writes the raw logits [M, V] (to the caller's
-// draft_logits rows, else to the workspace) and row_stats_kernel turns each row into the same
-// (max, sum-exp, top-k) partials the merge kernel reads, one partial per 4096 vocabulary entries.
+// draft_logits rows, else to the workspace) and row_expand_kernel reads each row once for its
+// (max, sum-exp, top-k), children and share of the frontier selection.
 constexpr int GB_MBMAX = 10;                 // 16-row blocks per workgroup pass (160 frontier rows)
 constexpr int GB_CHUNK = 256;                // bytes of K per row per stage
 constexpr int GB_WSTAGE = LM_ROWS * GB_CHUNK;            // 16 KB of W per stage
-constexpr int RS_CHUNK = 4096;               // vocabulary entries per row_stats workgroup
 
 // Destination of frontier row m's logits: the caller's [B, R, V] tensor or the dense workspace.
 __device__ __forceinline__ float* logit_row_ptr(int m, int F, int V, float* logits_ws, float* logits_out,
@@ -758,145 +759,6 @@ void lmhead_gemm128_kernel(const uint8_t* __restrict__ W, int row_bytes, int V,
     }
 }
 
-// (max, sum-exp, top-KC) of RS_CHUNK logits of one frontier row, in the partial format of
-// lmhead_kernel: grid (M, chunks), partial index = chunk; a thread holds 16 values, a wave
-// finds its KC best by counting among the few values above a bound, the four waves' lists are
-// merged by counting.
-template <int KC>
-__global__ __launch_bounds__(256)
-void row_stats_kernel(int V, int F, const float* __restrict__ logits_ws, const float* __restrict__ logits_out,
-                      int logit_rows_per_seq, int logit_row_base,
-                      float* __restrict__ part_ms, float* __restrict__ part_val, int* __restrict__ part_idx) {
-    __shared__ float s_m[4], s_s[4];
-    __shared__ __align__(16) float s_v[4 * KC];
-    __shared__ __align__(16) int s_i[4 * KC];
-    __shared__ __align__(16) float s_cv[4 * 64];       // per wave: values at or above its bound
-    __shared__ __align__(16) int s_ci[4 * 64];
-    const int m = blockIdx.x, chunk = blockIdx.y, G = gridDim.y;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const float* src = logit_row_ptr(m, F, V, const_cast<float*>(logits_ws), const_cast<float*>(logits_out),
-                                     logit_rows_per_seq, logit_row_base);
-    const int c0 = chunk * RS_CHUNK;
-    float x[16];
-    const bool vec = (V & 3) == 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int v = c0 + (i * 256 + tid) * 4;
-        if (vec && v + 3 < V) {
-            const floatx4 y = *reinterpret_cast<const floatx4*>(src + v);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) x[i * 4 + e] = y[e];
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) x[i * 4 + e] = v + e < V ? src[v + e] : -INFINITY;
-        }
-    }
-    float mx = x[0];
-#pragma unroll
-    for (int q = 1; q < 16; ++q) mx = fmaxf(mx, x[q]);
-    const float wm = wave_max(mx);
-    if (lane == 0) s_m[w] = wm;
-    __syncthreads();
-    const float bm = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));   // finite: the chunk holds at least one entry
-    float sum = 0.f;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) sum += __expf(x[q] - bm);                 // exp(-inf) = 0 for the padding
-    sum = wave_sumf(sum);
-    if (lane == 0) s_s[w] = sum;
-
-    // The wave's KC best of its 1024 values.  The KC-th largest of the 64 lane maxima is a lower
-    // bound of the KC-th largest value, so only values at or above it can matter: usually
-    // between KC and 2 KC of them.  They are compacted into LDS and ranked by counting.
-    // (counting through LDS broadcast reads: 16-byte reads of the same address by all lanes)
-    float* cv = s_cv + w * 64;
-    int* ci = s_ci + w * 64;
-    cv[lane] = mx;
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    int cge = 0;                                       // lane maxima at or above this lane's
-#pragma unroll
-    for (int j = 0; j < 64; j += 4) {
-        const floatx4 o = *reinterpret_cast<const floatx4*>(cv + j);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) cge += o[e] >= mx ? 1 : 0;
-    }
-    const float thr = wave_max(cge >= KC ? mx : -INFINITY);                // the KC-th largest lane maximum
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");                 // cv is reused below
-    int ncand = 0;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-        const int v = c0 + ((q >> 2) * 256 + tid) * 4 + (q & 3);
-        const bool take = x[q] >= thr && v < V;                            // padding is -inf: never above a finite bound
-        const unsigned long long bal = __ballot(take);
-        const int pos = ncand + __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
-        if (take && pos < 64) { cv[pos] = x[q]; ci[pos] = v; }
-        ncand += __popcll(bal);
-    }
-    if (ncand <= 64) {                                                     // uniform over the wave
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        if (lane >= ncand) { cv[lane] = -INFINITY; ci[lane] = INT_MAX; }   // pad to a multiple of four
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        const float v = cv[lane];
-        const int id = ci[lane];
-        int r = 0;
-        for (int j = 0; j < ncand; j += 4) {
-            const floatx4 ov = *reinterpret_cast<const floatx4*>(cv + j);
-            const u32x4 oi = *reinterpret_cast<const u32x4*>(ci + j);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) r += ranks_before(ov[e], (int)oi[e], v, id) ? 1 : 0;
-        }
-        if (lane < KC) { s_v[w * KC + lane] = -INFINITY; s_i[w * KC + lane] = INT_MAX; }   // fewer than KC entries in a ragged tail
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        if (lane < ncand && r < KC) { s_v[w * KC + r] = v; s_i[w * KC + r] = id; }
-    } else {
-        // many equal values: per-lane sorted lists merged by KC rounds of arg-best (slow, exact)
-        float tval[KC];
-        int tidx[KC];
-#pragma unroll
-        for (int j = 0; j < KC; ++j) { tval[j] = -INFINITY; tidx[j] = INT_MAX; }
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int v = c0 + ((q >> 2) * 256 + tid) * 4 + (q & 3);     // increasing in q
-            if (v < V) list_insert<KC>(x[q], v, tval, tidx);
-        }
-#pragma unroll
-        for (int r = 0; r < KC; ++r) {
-            float bv = tval[0];
-            int bi = tidx[0];
-            wave_best(bv, bi);
-            if (tidx[0] == bi && bi != INT_MAX) {      // token ids are unique: exactly one lane pops
-#pragma unroll
-                for (int q = 0; q < KC - 1; ++q) { tval[q] = tval[q + 1]; tidx[q] = tidx[q + 1]; }
-                tval[KC - 1] = -INFINITY; tidx[KC - 1] = INT_MAX;
-            }
-            if (lane == 0) { s_v[w * KC + r] = bv; s_i[w * KC + r] = bi; }
-        }
-    }
-    __syncthreads();
-    if (w == 0) {
-        // 4*KC <= 64 entries, one per lane, ranked by counting (lane id breaks ties among the padding)
-        const bool have = lane < 4 * KC;
-        const float v = have ? s_v[lane] : -INFINITY;
-        const int id = have ? s_i[lane] : INT_MAX;
-        int r = 0;
-#pragma unroll
-        for (int j = 0; j < 4 * KC; j += 4) {
-            const floatx4 ov = *reinterpret_cast<const floatx4*>(s_v + j);
-            const u32x4 oi = *reinterpret_cast<const u32x4*>(s_i + j);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int ij = (int)oi[e];
-                r += ((ov[e] > v) | ((ov[e] == v) & ((ij < id) | ((ij == id) & (j + e < lane))))) ? 1 : 0;   // (bitwise: no branches)
-            }
-        }
-        const size_t pbase = (size_t)m * G + chunk;
-        if (have && r < KC) { part_val[pbase * KC + r] = v; part_idx[pbase * KC + r] = id; }
-        if (lane == 0) {
-            part_ms[pbase * 2 + 0] = bm;
-            part_ms[pbase * 2 + 1] = (s_s[0] + s_s[1]) + (s_s[2] + s_s[3]);
-        }
-    }
-}
-
 // One workgroup per (frontier row, sequence).  Each of the G partial lists is sorted, so an
 // entry can only be in the row's top k if its list's head is among the k best heads.  Heads,
 // surviving entries (<= k*KC) and new candidates (frontier) are all ranked by counting.  The
@@ -925,14 +787,78 @@ __device__ __forceinline__ void rank_keys(const unsigned long long* keys, int n,
     if (cnt) atomicAdd(rank + i, cnt);
 }
 
+// The end of a row's expansion, shared by both paths: ok[0..k) are the row's k best (value, token)
+// keys, mx and log_sum its log-sum-exp; thread t < k holds the parent (par, ps) and writes child t.
+// The workgroup that finishes last for a sequence (a counter in the workspace, zeroed by the
+// LM-head kernel) also selects the next frontier.
+__device__ __forceinline__ void finish_row(int d, int F, int k, int D, int C, int by_confidence, int static_tree,
+                                           int par, double ps, float mx, const double* log_sum_lds,
+                                           const unsigned long long* ok,
+                                           int* __restrict__ cand_token, double* __restrict__ cand_score,
+                                           int* __restrict__ cand_parent, int* __restrict__ frontier,
+                                           unsigned* __restrict__ done_count) {
+    __shared__ unsigned long long s_fk[MG_MAXN];        // new candidates' scores (frontier selection)
+    __shared__ int s_frank[MG_MAXN];
+    __shared__ int s_last;
+    const int slot = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int base = d == 0 ? 0 : k + (d - 1) * k * k;
+    if (tid < MG_MAXN) s_frank[tid] = 0;
+    if (tid < k) {
+        const double log_sum = *log_sum_lds;
+        const int cid = base + slot * k + tid;
+        const unsigned long long key = ok[tid];
+        const float ov = key != 0ull ? key_value(key) : -INFINITY;
+        const double sc = ps + (((double)ov - (double)mx) - log_sum);
+        cand_token[(size_t)b * C + cid] = key != 0ull ? key_id(key) : 0;
+        cand_parent[(size_t)b * C + cid] = par;
+        // The score is also read by the workgroup that picks the next frontier, possibly on
+        // another XCD: store it at device scope (write-through to the coherence point) instead of
+        // a device-scope fence (which writes back the whole L2).  These stores and the counter
+        // increment below are all issued by wave 0; the wave waits here until every one of its
+        // outstanding stores has been acknowledged, so the counter cannot overtake a score.
+        __hip_atomic_store(cand_score + (size_t)b * C + cid, sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        wait_vector_memory();
+    }
+    if (d + 1 >= D || static_tree) return;               // a static shape fixes the frontiers beforehand
+
+    // the last workgroup of this sequence picks the next frontier
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned prev = __hip_atomic_fetch_add(done_count + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = prev == (unsigned)(F - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    const int nn = F * k;                               // <= MG_MAXN new candidates, in candidate-id order
+    if (tid < nn) {
+        double key = __hip_atomic_load(cand_score + (size_t)b * C + base + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (by_confidence && d > 0) {                   // "w/o value" (Section 5.2): the node's own log confidence
+            int par = frontier[((size_t)b * D + d) * k + tid / k];
+            if (par < 0 || par >= C) par = 0;
+            key -= cand_score[(size_t)b * C + par];     // written by an earlier pass
+        }
+        s_fk[tid] = order_key(key);
+    }
+    __syncthreads();
+    rank_keys(s_fk, nn, s_frank, tid);
+    __syncthreads();
+    if (tid < nn) {
+        const int r = s_frank[tid];
+        if (r < k) frontier[((size_t)b * D + d + 1) * k + r] = base + tid;
+    }
+}
+
+
+// The merge of one (frontier row, sequence): ms, pv and pi are that row's G partial pairs and lists,
+// in global memory or in LDS.
 template <int KC>
-__global__ __launch_bounds__(MG_THREADS)
-void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confidence, int static_tree,
-                         const float* __restrict__ part_ms, const float* __restrict__ part_val,
-                         const int* __restrict__ part_idx,
-                         int* __restrict__ cand_token, double* __restrict__ cand_score,
-                         int* __restrict__ cand_parent, int* __restrict__ frontier,
-                         unsigned* __restrict__ done_count) {
+__device__ __forceinline__ void merge_row(int d, int F, int k, int D, int C, int G, int by_confidence, int static_tree,
+                                          const float* __restrict__ ms, const float* __restrict__ pv,
+                                          const int* __restrict__ pi,
+                                          int* __restrict__ cand_token, double* __restrict__ cand_score,
+                                          int* __restrict__ cand_parent, int* __restrict__ frontier,
+                                          unsigned* __restrict__ done_count) {
     constexpr int NW = MG_THREADS / 64;
     __shared__ float s_f[NW];
     __shared__ double s_d[NW];
@@ -940,18 +866,11 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
     __shared__ int s_wl[NW * EAGLE2_MAX_TOPK];
     __shared__ unsigned long long s_ck[MG_MAXN];        // entries of the surviving lists
     __shared__ unsigned long long s_ok[EAGLE2_MAX_TOPK];   // the row's k best
-    __shared__ unsigned long long s_fk[MG_MAXN];        // new candidates' scores (frontier selection)
-    __shared__ int s_rank[3][MG_MAXN];                  // one set of counters per ranking, zeroed once
-    __shared__ int s_last;
+    __shared__ int s_rank[2][MG_MAXN];                  // one set of counters per ranking, zeroed once
     __shared__ double s_logsum;
     static_assert(NW * EAGLE2_MAX_TOPK <= MG_MAXN, "the per-wave winners are ranked like the other key sets");
     const int slot = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int base = d == 0 ? 0 : k + (d - 1) * k * k;
-    const size_t prow = (size_t)b * F + slot;
-    const float* ms = part_ms + prow * G * 2;
-    const float* pv = part_val + prow * G * KC;
-    const int* pi = part_idx + prow * G * KC;
 
     // loads first: the parent and its score (two dependent global loads, needed only at the end),
     // the heads of the G lists and the (max, sum-exp) pairs
@@ -970,7 +889,7 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
         my_s = ms[tid * 2 + 1];
     }
     if (tid < EAGLE2_MAX_TOPK) s_ok[tid] = 0ull;
-    if (tid < MG_MAXN) { s_rank[0][tid] = 0; s_rank[1][tid] = 0; s_rank[2][tid] = 0; s_wk[tid] = 0ull; s_ck[tid] = 0ull; s_wl[tid] = 0; }
+    if (tid < MG_MAXN) { s_rank[0][tid] = 0; s_rank[1][tid] = 0; s_wk[tid] = 0ull; s_ck[tid] = 0ull; s_wl[tid] = 0; }
     // log-sum-exp over the G partial pairs
     float mloc = wave_max(my_m);
     if (lane == 0) s_f[wave] = mloc;
@@ -1025,50 +944,172 @@ void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confid
         if (r < k && key != 0ull && key_id(key) != INT_MAX) s_ok[r] = key;
     }
     __syncthreads();
-    if (tid < k) {
-        const double log_sum = s_logsum;
-        const int cid = base + slot * k + tid;
-        const unsigned long long key = s_ok[tid];
-        const float ov = key != 0ull ? key_value(key) : -INFINITY;
-        const double sc = ps + (((double)ov - (double)mx) - log_sum);
-        cand_token[(size_t)b * C + cid] = key != 0ull ? key_id(key) : 0;
-        cand_parent[(size_t)b * C + cid] = par;
-        // The score is also read by the workgroup that picks the next frontier, possibly on
-        // another XCD: store it at device scope (write-through to the coherence point) instead of
-        // a device-scope fence (which writes back the whole L2).  These stores and the counter
-        // increment below are all issued by wave 0; the wave waits here until every one of its
-        // outstanding stores has been acknowledged, so the counter cannot overtake a score.
-        __hip_atomic_store(cand_score + (size_t)b * C + cid, sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        wait_vector_memory();
-    }
-    if (d + 1 >= D || static_tree) return;               // a static shape fixes the frontiers beforehand
+    finish_row(d, F, k, D, C, by_confidence, static_tree, par, ps, mx, &s_logsum, s_ok, cand_token, cand_score, cand_parent,
+               frontier, done_count);
+}
 
-    // the last workgroup of this sequence picks the next frontier
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned prev = __hip_atomic_fetch_add(done_count + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = prev == (unsigned)(F - 1) ? 1 : 0;
-    }
-    __syncthreads();
-    if (!s_last) return;
-    const int nn = F * k;                               // <= MG_MAXN new candidates, in candidate-id order
-    if (tid < nn) {
-        double key = __hip_atomic_load(cand_score + (size_t)b * C + base + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (by_confidence && d > 0) {                   // "w/o value" (Section 5.2): the node's own log confidence
-            int par = frontier[((size_t)b * D + d) * k + tid / k];
-            if (par < 0 || par >= C) par = 0;
-            key -= cand_score[(size_t)b * C + par];     // written by an earlier pass
+template <int KC>
+__global__ __launch_bounds__(MG_THREADS)
+void expand_merge_kernel(int d, int F, int k, int D, int C, int G, int by_confidence, int static_tree,
+                         const float* __restrict__ part_ms, const float* __restrict__ part_val,
+                         const int* __restrict__ part_idx,
+                         int* __restrict__ cand_token, double* __restrict__ cand_score,
+                         int* __restrict__ cand_parent, int* __restrict__ frontier,
+                         unsigned* __restrict__ done_count) {
+    const size_t prow = (size_t)blockIdx.y * F + blockIdx.x;
+    merge_row<KC>(d, F, k, D, C, G, by_confidence, static_tree, part_ms + prow * G * 2, part_val + prow * G * KC,
+                  part_idx + prow * G * KC, cand_token, cand_score, cand_parent, frontier, done_count);
+}
+
+// The many-row path's second half: one workgroup per (frontier row, sequence) reads the row's V raw
+// logits once, 16 per thread and iteration, and does everything else.  Log-sum-exp: every wave
+// keeps a running maximum and its lanes their share of the sum of exponentials.  Top k: the k-th
+// largest of all wave maxima seen so far (each wave's values are disjoint) is a lower bound of the
+// row's k-th largest value, so only the few values at or above it are candidates; they are appended
+// to a list in LDS (most waves have none and skip the step) and ranked by counting at the end.
+// A row with so many equal values that the list overflows is redone by k exact selection sweeps.
+constexpr int RX_STEP = MG_THREADS * 16;     // vocabulary entries per workgroup iteration
+constexpr int RX_CAP = MG_MAXN;              // candidates ranked at once
+
+__device__ __forceinline__ void load_row_piece(const float* __restrict__ src, int c0, int V, bool vec, int tid, float (&x)[16]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int v = c0 + (i * MG_THREADS + tid) * 4;
+        if (vec && v + 3 < V) {
+            const floatx4 y = *reinterpret_cast<const floatx4*>(src + v);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[i * 4 + e] = y[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[i * 4 + e] = v + e < V ? src[v + e] : -INFINITY;
         }
-        s_fk[tid] = order_key(key);
+    }
+}
+
+template <int KC>
+__global__ __launch_bounds__(MG_THREADS)
+void row_expand_kernel(int V, int d, int F, int k, int D, int C, int by_confidence, int static_tree,
+                       const float* __restrict__ logits_ws, const float* __restrict__ logits_out,
+                       int logit_rows_per_seq, int logit_row_base,
+                       int* __restrict__ cand_token, double* __restrict__ cand_score,
+                       int* __restrict__ cand_parent, int* __restrict__ frontier,
+                       unsigned* __restrict__ done_count) {
+    constexpr int NW = MG_THREADS / 64;
+    static_assert(NW + KC <= 64 && KC <= NW, "wave maxima and the running best are ranked by one wave; the first iteration must yield k maxima");
+    __shared__ float s_wm[2][NW];                       // this iteration's wave maxima
+    __shared__ float s_best[2][EAGLE2_MAX_TOPK];        // the KC largest wave maxima so far
+    __shared__ float s_m[NW], s_s[NW];
+    __shared__ unsigned long long s_ck[RX_CAP];
+    __shared__ int s_rank[RX_CAP];
+    __shared__ unsigned long long s_ok[EAGLE2_MAX_TOPK];
+    __shared__ unsigned long long s_pick;
+    __shared__ int s_n;
+    __shared__ double s_logsum;
+    const int slot = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int m = b * F + slot;
+    const float* src = logit_row_ptr(m, F, V, const_cast<float*>(logits_ws), const_cast<float*>(logits_out),
+                                     logit_rows_per_seq, logit_row_base);
+    const bool vec = (V & 3) == 0;
+    float x[16], xn[16];
+    load_row_piece(src, 0, V, vec, tid, x);
+    // the parent and its score: two dependent global loads, needed only at the end
+    int par = -1;
+    double ps = 0.0;
+    if (d > 0 && tid < k) {
+        par = frontier[((size_t)b * D + d) * k + slot];
+        if (par < 0 || par >= C) par = 0;               // garbage in the caller's frontier stays in bounds
+        ps = cand_score[(size_t)b * C + par];
+    }
+    if (tid == 0) s_n = 0;
+    if (tid < EAGLE2_MAX_TOPK) { s_ok[tid] = 0ull; s_best[0][tid] = -INFINITY; s_best[1][tid] = -INFINITY; }
+    if (tid < RX_CAP) { s_ck[tid] = 0ull; s_rank[tid] = 0; }
+    float run_m = -INFINITY, run_s = 0.f;               // the wave's running maximum; this lane's share of the sum
+    int it = 0;
+    for (int c0 = 0; c0 < V; c0 += RX_STEP, it ^= 1) {
+        if (c0 + RX_STEP < V) load_row_piece(src, c0 + RX_STEP, V, vec, tid, xn);   // in flight during this piece's work
+        float mx = x[0];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) mx = fmaxf(mx, x[q]);
+        const float wm = wave_max(mx);
+        if (lane == 0) s_wm[it][w] = wm;
+        if (wm > -INFINITY) {                           // uniform over the wave: it holds at least one entry
+            const float nm = fmaxf(run_m, wm);
+            float sum = run_s * __expf(run_m - nm);     // 0 * exp(-inf) = 0 the first time
+#pragma unroll
+            for (int q = 0; q < 16; ++q) sum += __expf(x[q] - nm);   // exp(-inf) = 0 for the padding
+            run_s = sum;
+            run_m = nm;
+        }
+        __syncthreads();
+        // Every wave ranks the NW new maxima and the KC best so far (one per lane, ties by lane) and
+        // writes the new KC best: the same values from every wave.  The buffers alternate, and the
+        // barrier above separates an iteration's reads from the next one's writes.
+        const bool have = lane < NW + KC;
+        const float cm = lane < NW ? s_wm[it][lane] : (have ? s_best[it ^ 1][lane - NW] : -INFINITY);
+        int r = 0;
+#pragma unroll
+        for (int j = 0; j < NW + KC; ++j) {
+            const float o = read_lane(cm, j);
+            r += ((o > cm) | ((o == cm) & (j < lane))) ? 1 : 0;
+        }
+        if (have && r < KC) s_best[it][r] = cm;
+        const float thr = wave_max(have && r == k - 1 ? cm : -INFINITY);
+        if (__ballot(mx >= thr) != 0ull) {              // uniform over the wave; rare after the first iterations
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int v = c0 + ((q >> 2) * MG_THREADS + tid) * 4 + (q & 3);
+                if (x[q] >= thr && v < V) {             // (the padding is -inf and passes a bound of -inf)
+                    const int pos = atomicAdd(&s_n, 1);
+                    if (pos < RX_CAP) s_ck[pos] = order_key(x[q], v);
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) x[q] = xn[q];
+    }
+    run_s = wave_sumf(run_s);
+    if (lane == 0) { s_m[w] = run_m; s_s[w] = run_s; }
+    __syncthreads();
+    float rmx = s_m[0];
+#pragma unroll
+    for (int j = 1; j < NW; ++j) rmx = fmaxf(rmx, s_m[j]);
+    if (tid == MG_THREADS - 1) {                        // an otherwise idle thread takes the logarithm
+        double tot = 0.0;
+#pragma unroll
+        for (int j = 0; j < NW; ++j) tot += s_m[j] > -INFINITY ? (double)s_s[j] * exp((double)s_m[j] - (double)rmx) : 0.0;
+        s_logsum = log(tot);
+    }
+    const int n = s_n;
+    if (n <= RX_CAP) {                                  // uniform over the workgroup
+        if (n > 0) rank_keys(s_ck, n, s_rank, tid);
+        __syncthreads();
+        if (tid < n) {
+            const int r = s_rank[tid];
+            if (r < k) s_ok[r] = s_ck[tid];
+        }
+    } else {
+        // k sweeps over the row, each taking the best key below the previous winner (keys are
+        // unique: they carry the token id); slow and exact
+        unsigned long long prev = ~0ull;
+        for (int r = 0; r < k; ++r) {
+            if (tid == 0) s_pick = 0ull;
+            __syncthreads();
+            unsigned long long best = 0ull;
+            for (int v = tid; v < V; v += MG_THREADS) {
+                const unsigned long long key = order_key(src[v], v);
+                if (key < prev && key > best) best = key;
+            }
+            if (best != 0ull) atomicMax(&s_pick, best);
+            __syncthreads();
+            prev = s_pick;                              // 0 once the row is exhausted
+            if (tid == 0) s_ok[r] = prev;
+            __syncthreads();
+        }
     }
     __syncthreads();
-    rank_keys(s_fk, nn, s_rank[2], tid);
-    __syncthreads();
-    if (tid < nn) {
-        const int r = s_rank[2][tid];
-        if (r < k) frontier[((size_t)b * D + d + 1) * k + r] = base + tid;
-    }
+    finish_row(d, F, k, D, C, by_confidence, static_tree, par, ps, rmx, &s_logsum, s_ok, cand_token, cand_score, cand_parent,
+               frontier, done_count);
 }
 
 // out[M, N] (float32, dense) = X[M, K] . W[N, K]^T for M > 16 rows: pack_h_kernel + lmhead_gemm_kernel.
@@ -1146,7 +1187,6 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
 
     const int R = n_draft_rows(cfg);
     const int row_base = d == 0 ? 0 : 1 + (d - 1) * k;
-    int G;
     if (M > 16) {
         // many rows: stream W once per 160 rows into raw logits, then per-row statistics
         const int ntask = (cfg->vocab + LM_ROWS - 1) / LM_ROWS;
@@ -1173,12 +1213,15 @@ static int launch_expand(const eagle2_cfg* cfg, int d, const void* H, int64_t h_
         }
         timing_end(0, st);
         E2_HIP(hipGetLastError());
-        G = (cfg->vocab + RS_CHUNK - 1) / RS_CHUNK;
-        hipLaunchKernelGGL((row_stats_kernel<KC>), dim3(M, G), dim3(256), 0, st, cfg->vocab, F, logits_ws, draft_logits, R, row_base,
-                           part_ms, part_val, part_idx);
+        hipLaunchKernelGGL((row_expand_kernel<KC>), dim3(F, cfg->batch), dim3(MG_THREADS), 0, st, cfg->vocab,
+                           d, F, k, cfg->depth, n_cand(cfg), (cfg->flags & EAGLE2_FLAG_RANK_BY_CONFIDENCE) ? 1 : 0,
+                           (cfg->flags & EAGLE2_FLAG_STATIC_TREE) ? 1 : 0, logits_ws, draft_logits, R, row_base,
+                           cand_token, cand_score, cand_parent, frontier, done_count);
         E2_HIP(hipGetLastError());
-    } else {
-        G = lm_grid(cfg);
+        return EAGLE2_OK;
+    }
+    const int G = lm_grid(cfg);
+    {
         const size_t smem = 4 * LM_STAGE;
         static_assert(4 * LM_STAGE >= (2 * EAGLE2_MAX_TOPK + 2) * 4 * 68 * 4, "merge area must fit");
         timing_begin(0, st);

@@ -184,14 +184,14 @@ def test_long_context_prefix_many_chunks(fp8):
         assert np.max(np.abs(pu.f64(lse[b]) - ref_lse)) <= pu.REL_TOL["bf16"] * max(1.0, np.abs(ref_lse).max())
 
 
-@pytest.mark.parametrize("batch", [1, 20], ids=["few_rows", "many_rows"])
+@pytest.mark.parametrize("batch,vocab", [(1, 5003), (20, 5003), (18, 40001)], ids=["few_rows", "many_rows", "many_rows_three_pieces"])
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
-def test_exact_ties_take_the_lower_token_id(batch, dtype):
+def test_exact_ties_take_the_lower_token_id(batch, vocab, dtype):
     """Rows of W repeated in pairs give logits that tie exactly; hidden states of zero tie every logit.
     Whatever lane, wave or workgroup holds them, equal values must come out lower token id first
     (Section 4.1 leaves the order of equal values open; this build fixes it, as the oracle does)."""
     from paper_2406_16858_amd import DraftRound
-    cfg = _cfg("ties", dtype=dtype, batch=batch, vocab=5003, hidden=512 if dtype == "bf16" else 256, depth=3, topk=5, n_tree=12, seed=17)
+    cfg = _cfg("ties", dtype=dtype, batch=batch, vocab=vocab, hidden=512 if dtype == "bf16" else 256, depth=3, topk=5, n_tree=12, seed=17)
     B, D, k, V = cfg.batch, cfg.depth, cfg.topk, cfg.vocab
     W = wl.make_lm_head(cfg, "cuda")
     W[1::2] = W[0:V - 1:2]                             # token 2j+1 repeats token 2j (V is odd: the last token stays single)
