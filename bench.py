@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--attn-layers", type=int, default=0,
                     help="run eagle2_tree_attn over this many independent seeded KV layers per round instead of the "
                          "configuration's own count (secondary measurement: --config 3 --attn-layers 32)")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="capture the round once into a HIP graph and time replays instead of eager launches")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -149,16 +151,35 @@ def main():
                 rnd.tree_attn(Q, Kp, Vp, off, Kt, Vt, O, None)
         rnd.accept(mode_t, tl, temp, ua, ub)
 
-    for _ in range(args.warmup):
+    step = one_round
+    if args.hip_graph:
+        # every entry point only enqueues kernels on the current stream: the round records as it is
         one_round()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one_round()
+        step = graph.replay
+    for _ in range(args.warmup):
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        one_round()
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     rounds_per_s = B * 1e3 / ms_per_step
+
+    # ---- spread of single rounds: an event pair around each of a few rounds (outside the timed region) ----
+    n_single = max(3, min(20, args.steps))
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_single)]
+    for e0, e1 in pairs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    singles = sorted(e0.elapsed_time(e1) for e0, e1 in pairs)
 
     # ---- dominant kernel: LM-head stream, HIP events on the launch stream --------
     eagle2_kernel_timing_enable(True)
@@ -180,11 +201,14 @@ def main():
         traffic_src = f"recorded counter run, {traffic_src} (not measured by this run)"
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_src,
-                "kernel": "lmhead_kernel", "bytes_per_launch": lm_bytes, "avg_launch_ms": round(lm_avg_ms, 5),
+                "kernel": "lmhead_kernel" if B * k <= 16 else "lmhead_gemm128_kernel (passes 1..D-1), lmhead_kernel (pass 0)",
+                "bytes_per_launch": lm_bytes, "avg_launch_ms": round(lm_avg_ms, 5),
                 "launches_timed": lm_n}
     extra = {"round_algorithmic_bytes": round_bytes,
              "round_hbm_roofline_frac": round(round_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
-             "attn_kernel_avg_ms": round(at_ms / max(at_n, 1), 5)}
+             "attn_kernel_avg_ms": round(at_ms / max(at_n, 1), 5),
+             "single_round_ms": {"median": round(singles[len(singles) // 2], 4), "min": round(singles[0], 4), "rounds": n_single},
+             "launch": "hip graph replay" if args.hip_graph else "eager"}
 
     # ---- the oracle on the host cores, same round, bounded sample ------------------
     cpu = None
@@ -231,6 +255,8 @@ def main():
         name += "_fp8_prefix_kv"
     if args.attn_layers > 0:
         name += f"_attn_layers_{args.attn_layers}"
+    if args.hip_graph:
+        name += "_hip_graph"
     out = {"metric": name,
            "value": round(rounds_per_s, 2), "unit": "rounds/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
