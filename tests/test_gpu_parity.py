@@ -58,6 +58,14 @@ SMALL = [
            prefix_lo=0, prefix_hi=50, seed=15),
     _small("batch17_rows170_vocab66000", batch=17, topk=10, depth=2, n_tree=12, vocab=66000, hidden=512, accept="greedy",
            prefix_lo=0, prefix_hi=30, seed=16),
+    # the per-row kernel of the many-row path at its three list sizes (k <= 4, <= 10, 16), with vocabularies of one
+    # ragged piece, barely sixteen occupied waves, and two pieces per row
+    _small("batch2_rows32_k16_vocab20011", batch=2, topk=16, depth=2, n_tree=40, vocab=20011, hidden=512, accept="sample",
+           prefix_lo=0, prefix_hi=40, seed=18),
+    _small("batch6_rows18_k3_vocab9001_fp32", dtype="fp32", batch=6, topk=3, depth=4, n_tree=20, vocab=9001, hidden=256,
+           accept="mixed", prefix_lo=0, prefix_hi=40, seed=19),
+    _small("batch2_rows20_k10_vocab4001", batch=2, topk=10, depth=3, n_tree=30, vocab=4001, hidden=512, accept="greedy",
+           prefix_lo=5, prefix_hi=60, seed=20),
 ]
 
 
