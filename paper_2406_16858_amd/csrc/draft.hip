@@ -9,7 +9,8 @@
 // kernel without its statistics: 64 output rows per task, split-K over the four waves of a
 // workgroup, and -- because these matrices have far fewer rows than a vocabulary -- split-K
 // over workgroups too (grid z), each slice writing its own float32 partial.  The small
-// kernels between them add the slices up and apply the element-wise steps.
+// kernels between them add the slices up and apply the element-wise steps; the SwiGLU step runs
+// in the task ends of the gate / up product where that product is not split over workgroups.
 
 #include "common.h"
 
@@ -21,13 +22,27 @@ constexpr int DL_CHUNK = 256;                // bytes of K per row per stage per
 constexpr int DL_STAGE = DL_ROWS * DL_CHUNK;
 constexpr int DL_LOADS = DL_ROWS * DL_CHUNK / 1024;
 
+__device__ __forceinline__ float to_float(const void* p, size_t i, bool bf16) {
+    if (!bf16) return static_cast<const float*>(p)[i];
+    return __uint_as_float((unsigned)static_cast<const uint16_t*>(p)[i] << 16);
+}
+__device__ __forceinline__ void from_float(void* p, size_t i, float v, bool bf16) {
+    if (!bf16) { static_cast<float*>(p)[i] = v; return; }
+    const __bf16 h = (__bf16)v;                        // round to nearest even
+    static_cast<uint16_t*>(p)[i] = __builtin_bit_cast(uint16_t, h);
+}
 // part[slice][m_pad][N] = X[M, K-slice] . W[N, K-slice]^T.  Input row m = (b, s) lives at
 // X + b * x_seq_bytes + s * row_bytes (the same addressing as the LM-head kernel's H).
-template <bool BF16>
+//
+// GLU: W is the gate matrix stacked on the up matrix ([2 * N, K]); a task is 32 gate rows and the
+// 32 up rows of the same outputs, K is not split over workgroups, and the task's end writes
+// act[m][n] = silu(gate) * up in the activation type instead of a float32 partial (N a multiple
+// of 32): the element-wise kernel between the two MLP products and its launch fall away.
+template <bool BF16, bool GLU>
 __global__ __launch_bounds__(DL_THREADS, 2)
 void linear_kernel(const uint8_t* __restrict__ W, int row_bytes, int N,
                    const uint8_t* __restrict__ Xraw, int64_t x_seq_bytes, int M, int F,
-                   float* __restrict__ part, int m_pad) {
+                   float* __restrict__ part, int m_pad, void* __restrict__ act) {
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m16 = lane & 15, g = lane >> 4;          // MFMA lane coordinates
@@ -39,7 +54,7 @@ void linear_kernel(const uint8_t* __restrict__ W, int row_bytes, int N,
     const int sq = stages / units, sr = stages - sq * units;
     const int nst = sq + (unit < sr ? 1 : 0);          // >= 1: the host keeps 4 * slices <= stages
     const size_t kbase = (size_t)(unit * sq + min(unit, sr)) * DL_CHUNK;
-    const int ntask = (N + DL_ROWS - 1) / DL_ROWS;
+    const int ntask = GLU ? N / 32 : (N + DL_ROWS - 1) / DL_ROWS;
     const int tq = ntask / G, tr = ntask - tq * G;
     const int my_tasks = tq + ((int)blockIdx.x < tr ? 1 : 0);
     const int task_first = (int)blockIdx.x * tq + min((int)blockIdx.x, tr);
@@ -54,8 +69,13 @@ void linear_kernel(const uint8_t* __restrict__ W, int row_bytes, int N,
         const size_t kb = kbase + (size_t)st * DL_CHUNK + c16 * 16;
 #pragma unroll
         for (int j = 0; j < DL_LOADS; ++j) {
-            int row = task * DL_ROWS + j * 4 + r_in;
-            row = row < N ? row : N - 1;               // ragged tail: re-read the last row, never stored
+            int row;
+            if constexpr (GLU) {                       // local rows 0..31: gate, 32..63: up (matrix rows N + ...)
+                row = task * 32 + (j * 4 + r_in) + (j >= DL_LOADS / 2 ? N - 32 : 0);
+            } else {
+                row = task * DL_ROWS + j * 4 + r_in;
+                row = row < N ? row : N - 1;           // ragged tail: re-read the last row, never stored
+            }
             R[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(W + (size_t)row * row_bytes + kb));
         }
     };
@@ -125,6 +145,20 @@ void linear_kernel(const uint8_t* __restrict__ W, int row_bytes, int N,
             floatx4 x = red[(0 * 4 + w) * 64 + lane];
 #pragma unroll
             for (int sw = 1; sw < 4; ++sw) x += red[(sw * 4 + w) * 64 + lane];
+            if constexpr (GLU) {
+                // waves 0 and 1 hold gate rows 16w + 4g + i; the up rows of the same outputs are blocks w + 2
+                floatx4 up = red[(0 * 4 + (w | 2)) * 64 + lane];
+#pragma unroll
+                for (int sw = 1; sw < 4; ++sw) up += red[(sw * 4 + (w | 2)) * 64 + lane];
+                __syncthreads();                       // red aliases the staging buffers
+                const int n0 = (task_first + ti) * 32 + w * 16 + g * 4;
+                if (w < 2 && mrow < M) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        from_float(act, (size_t)mrow * N + n0 + i, x[i] / (1.f + __expf(-x[i])) * up[i], BF16);
+                }
+                continue;
+            }
             __syncthreads();                           // red aliases the staging buffers
             // register i: output row 64*task + 16*w + 4*g + i of input row mrow
             const int n0 = (task_first + ti) * DL_ROWS + w * 16 + g * 4;
@@ -143,15 +177,6 @@ void linear_kernel(const uint8_t* __restrict__ W, int row_bytes, int N,
 
 // ---- element-wise kernels: one workgroup per input row m = (b, s) -------------------------------
 
-__device__ __forceinline__ float to_float(const void* p, size_t i, bool bf16) {
-    if (!bf16) return static_cast<const float*>(p)[i];
-    return __uint_as_float((unsigned)static_cast<const uint16_t*>(p)[i] << 16);
-}
-__device__ __forceinline__ void from_float(void* p, size_t i, float v, bool bf16) {
-    if (!bf16) { static_cast<float*>(p)[i] = v; return; }
-    const __bf16 h = (__bf16)v;                        // round to nearest even
-    static_cast<uint16_t*>(p)[i] = __builtin_bit_cast(uint16_t, h);
-}
 __device__ __forceinline__ float sum_slices(const float* part, int S, int m_pad, int m, int N, int n) {
     const float* p = part + (size_t)m * N + n;
     const size_t step = (size_t)m_pad * N;
@@ -415,11 +440,29 @@ static int launch_linear(const void* X, int64_t x_seq_bytes, int M, int F, const
     int G = 2 * device_cu_count();
     if (G > ntask) G = ntask;
     dim3 grid(G, m_pad / 16, S);
-    hipLaunchKernelGGL((linear_kernel<BF16>), grid, dim3(DL_THREADS), 4 * DL_STAGE, st,
+    hipLaunchKernelGGL((linear_kernel<BF16, false>), grid, dim3(DL_THREADS), 4 * DL_STAGE, st,
                        static_cast<const uint8_t*>(W), (int)row_bytes, n_out,
-                       static_cast<const uint8_t*>(X), x_seq_bytes, M, F, part, m_pad);
+                       static_cast<const uint8_t*>(X), x_seq_bytes, M, F, part, m_pad, static_cast<void*>(nullptr));
     E2_HIP(hipGetLastError());
     *slices_out = S;
+    return EAGLE2_OK;
+}
+
+// The gate / up product with the SwiGLU step in its task ends: possible when the product is not split over
+// workgroups anyway (enough tasks to fill the machine) and tasks pair whole 32-row blocks.
+static bool glu_fusable(int M, int inter, int64_t row_bytes) {
+    return M <= 16 && inter % 32 == 0 && pick_slices(2 * inter, row_bytes) == 1;
+}
+template <bool BF16>
+static int launch_linear_glu(const void* X, int64_t x_seq_bytes, int M, const void* Wgu, int inter, int64_t row_bytes,
+                             void* act, int m_pad, hipStream_t st) {
+    const int ntask = inter / 32;
+    int G = 2 * device_cu_count();
+    if (G > ntask) G = ntask;
+    hipLaunchKernelGGL((linear_kernel<BF16, true>), dim3(G, m_pad / 16, 1), dim3(DL_THREADS), 4 * DL_STAGE, st,
+                       static_cast<const uint8_t*>(Wgu), (int)row_bytes, inter,
+                       static_cast<const uint8_t*>(X), x_seq_bytes, M, 1, static_cast<float*>(nullptr), m_pad, act);
+    E2_HIP(hipGetLastError());
     return EAGLE2_OK;
 }
 
@@ -519,8 +562,14 @@ extern "C" int eagle2_draft_forward(const eagle2_cfg* cfg, const eagle2_draft_cf
     E2_LIN(static_cast<const uint8_t*>(O) + (size_t)row_base * Hq * dh * es, (int64_t)Rd * Hq * dh * es, F, wt->wo, Hd, Hq * dh);
     hipLaunchKernelGGL(sum_rmsnorm_kernel, dim3(M), dim3(RN_THREADS), 0, st, S, m_pad, Hd, dc->eps, bf, part, x0, wt->g_mlp, h1, nrm);
     // SwiGLU MLP
-    E2_LIN(nrm, (int64_t)Hd * es, 1, wt->wgu, 2 * inter, Hd);
-    hipLaunchKernelGGL(swiglu_kernel, dim3(M, (inter + DL_THREADS - 1) / DL_THREADS), dim3(DL_THREADS), 0, st, S, m_pad, inter, bf, part, act);
+    if (glu_fusable(M, inter, (int64_t)Hd * es)) {
+        rc = bf ? launch_linear_glu<true>(nrm, (int64_t)Hd * es, M, wt->wgu, inter, (int64_t)Hd * es, act, m_pad, st)
+                : launch_linear_glu<false>(nrm, (int64_t)Hd * es, M, wt->wgu, inter, (int64_t)Hd * es, act, m_pad, st);
+        if (rc != EAGLE2_OK) return rc;
+    } else {
+        E2_LIN(nrm, (int64_t)Hd * es, 1, wt->wgu, 2 * inter, Hd);
+        hipLaunchKernelGGL(swiglu_kernel, dim3(M, (inter + DL_THREADS - 1) / DL_THREADS), dim3(DL_THREADS), 0, st, S, m_pad, inter, bf, part, act);
+    }
     E2_LIN(act, (int64_t)inter * es, 1, wt->wdown, Hd, inter);
     hipLaunchKernelGGL(feature_out_kernel, dim3(M, (Hd + DL_THREADS - 1) / DL_THREADS), dim3(DL_THREADS), 0, st, S, m_pad, d, F, k, Rd,
                        Hd, bf, part, h1, draft_feature);
