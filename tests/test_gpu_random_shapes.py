@@ -42,3 +42,38 @@ CASES = [_draw(i) for i in range(24)]
                                             f"{c.n_q_heads}x{c.n_kv_heads}x{c.head_dim}_P{c.prefix_lo}-{c.prefix_hi}_{c.accept}" for c in CASES])
 def test_random_shape(cfg):
     run_and_check_round(cfg, h_scale=5.0, plant=(cfg.accept == "greedy"), verbose=False)
+
+
+def _draw_many_rows(i):
+    """More than 16 frontier rows per pass and vocabularies of one to five 16384-entry pieces: the many-row LM head and
+    its per-row kernel at every list size."""
+    rng = np.random.default_rng(77000 + i)
+    dtype = "fp32" if rng.random() < 0.25 else "bf16"
+    hidden = (256 if dtype == "fp32" else 512) * int(rng.integers(1, 3))
+    k = int(rng.choice([2, 3, 4, 5, 8, 10, 13, 16]))
+    batch = int(rng.choice([2, 3, 5, 9, 18]))
+    while batch * k <= 16:
+        batch += 3
+    D = int(rng.integers(2, 5))
+    C = k + (D - 1) * k * k
+    n_tree = int(rng.integers(2, min(128, C + 1) + 1))
+    vocab = int(rng.integers(3000, 70000))
+    if batch * k > 100:
+        vocab = min(vocab, 30000)                            # keeps the oracle's work small
+    hkv = int(rng.choice([1, 2]))
+    grp = int(rng.choice([1, 2, 4]))
+    p_hi = int(rng.choice([0, 5, 64, 200]))
+    p_lo = int(rng.integers(0, p_hi + 1))
+    accept = str(rng.choice(["greedy", "sample", "mixed"]))
+    return wl.RoundConfig(name=f"manyrows{i}", index=0, dtype=dtype, batch=batch, vocab=vocab, hidden=hidden, depth=D, topk=k,
+                          n_tree=n_tree, n_q_heads=hkv * grp, n_kv_heads=hkv, head_dim=64, prefix_lo=p_lo, prefix_hi=p_hi,
+                          n_layers=1, w_std=0.05, accept=accept, temperature=float(rng.choice([1.0, 0.7, 1.5])), seed=900 + i)
+
+
+MANY = [_draw_many_rows(i) for i in range(16)]
+
+
+@pytest.mark.parametrize("i,cfg", list(enumerate(MANY)), ids=[f"{c.name}_{c.dtype}_V{c.vocab}_h{c.hidden}_D{c.depth}_k{c.topk}_N{c.n_tree}_B{c.batch}_{c.accept}"
+                                                              for c in MANY])
+def test_random_many_row_shape(i, cfg):
+    run_and_check_round(cfg, h_scale=(1.0, 5.0)[i % 2], plant=(cfg.accept == "greedy"), verbose=False)
