@@ -86,6 +86,42 @@ def test_bitwise_determinism():
             assert torch.equal(a, b), "two runs on the same inputs differ bitwise"
 
 
+def test_many_row_round_is_bitwise_reproducible():
+    """The same for a batch whose passes take the many-row LM head: its per-row kernel appends candidates to a list
+    in LDS in whatever order the waves arrive, which must not show in any output."""
+    from paper_2406_16858_amd import DraftRound
+    cfg = _cfg("repro_many_rows", batch=6, vocab=20011, hidden=512, depth=4, topk=5, n_tree=30, accept="mixed",
+               prefix_lo=3, prefix_hi=200, seed=23)
+    B = cfg.batch
+    W = wl.make_lm_head(cfg, "cuda")
+    H = wl.make_hidden_states(cfg, "cuda", scale=5.0)
+    plens = wl.make_prefix_lengths(cfg)
+    Q, Kp, Vp, Kt, Vt, off = wl.make_attention_inputs(cfg, "cuda", prefix_lens=plens)
+    tl, _ = wl.make_target_logits(cfg, "cuda")
+    ua, ub = wl.make_uniforms(cfg, "cuda")
+    root = (torch.arange(B, dtype=torch.int32) + 5).cuda()
+    plen = torch.tensor(plens, dtype=torch.int32, device="cuda")
+    mode = torch.tensor([b % 2 for b in range(B)], dtype=torch.int32, device="cuda")
+    outs = []
+    for rep in range(3):
+        rnd = DraftRound(B, cfg.vocab, cfg.hidden, cfg.depth, cfg.topk, cfg.n_tree, cfg.dtype, cfg.n_q_heads,
+                         cfg.n_kv_heads, cfg.head_dim, total_prefix=sum(plens), keep_draft_logits=True)
+        rnd.workspace.fill_(rep * 41 + 3)
+        rnd.expand_all(H, W)
+        rnd.rerank(root, plen)
+        O = torch.empty_like(Q)
+        rnd.tree_attn(Q, Kp, Vp, off, Kt, Vt, O, None)
+        rnd.accept(mode, tl, torch.full((B,), 0.8, device="cuda"), ua, ub)
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (rnd.cand_token, rnd.cand_score, rnd.cand_parent, rnd.frontier, rnd.draft_logits,
+                                         rnd.tree_token, rnd.tree_parent, rnd.mask_bits, O, rnd.accept_len, rnd.accept_path,
+                                         rnd.bonus_token)])
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b), "two runs on the same inputs differ bitwise"
+    assert int(outs[0][0].min()) >= 0 and int(outs[0][9].min()) >= 0
+
+
 def test_errors_enqueue_nothing():
     from paper_2406_16858_amd import DraftRound, Eagle2Error, binding as b
     cfg = wl.get_config(1)
