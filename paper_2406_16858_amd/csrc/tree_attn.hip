@@ -165,7 +165,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
                            const uint16_t* __restrict__ Kt,
                            const uint16_t* __restrict__ Vt, const unsigned long long* __restrict__ mask_bits,
                            int B, int N, int q0, int nq, int Hq, int Hkv, int chunk, int words, int nmblk, int rows_pad,
-                           float scale_log2e, float* __restrict__ part_o, float* __restrict__ part_ml) {
+                           float scale_log2e, uint16_t* __restrict__ part_o, float* __restrict__ part_ml) {
     // RBW 16-row query blocks per wave.  One block (narrow): query fragments in registers, two tiles
     // of K/V in flight in registers, staged through one LDS tile.  Two blocks (wide; every K/V fragment
     // feeds two MFMAs and a tile is fetched once per 128 rows; pays when a KV head has more than 256
@@ -658,27 +658,48 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
     }
     if (!q_loaded) load_queries();                     // (every chunk has keys; the row numbers are needed below)
 
-    // partial results of this chunk: un-normalised O (lane holds dh db*16 + 4*g4 + i of its row), max, sum
+    // Partial results of this chunk: un-normalised O (lane holds dh db*16 + 4*g4 + i of its row), max, sum.
+    // All workgroups finish together and nothing hides their stores, so O leaves as 16-bit floats: every row
+    // is scaled by the power of two (exact) that puts its largest magnitude into [2^14, 2^15), rounded to
+    // nearest fp16 (11 significant bits for everything within 2^-28 of the row's largest value; the output is
+    // bf16, 8 bits) and the scale's inverse travels with (max, sum).
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
         const float l = accl[rb][0];                // valid in the lanes that write it (g4 == 0)
+        float am = 0.f;
+#pragma unroll
+        for (int db = 0; db < DH / 16; ++db)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) am = fmaxf(am, fabsf(acc[rb][db][i]));
+        am = max_over_lane_groups(am);              // the row's largest magnitude (all lanes take part)
+        unsigned eb = (__float_as_uint(am) >> 23) & 255u;        // am = 1.f x 2^(eb - 127)
+        eb = eb < 16u ? 16u : eb;                   // (rows of magnitude below 2^-111 go out as zeros)
+        const float up = __uint_as_float((268u - eb) << 23);     // 2^(141 - eb): am * up is in [2^14, 2^15)
+        const float down = __uint_as_float((eb - 14u) << 23);    // 2^(eb - 141)
         if (rho[rb] < rows) {
             const size_t prow = ((size_t)flat * Hkv + kvh) * rows_pad + rho[rb];
 #pragma unroll
-            for (int db = 0; db < DH / 16; ++db)
-                *reinterpret_cast<floatx4*>(part_o + prow * DH + db * 16 + g4 * 4) = acc[rb][db];
-            if (g4 == 0) { part_ml[prow * 2] = m_run[rb]; part_ml[prow * 2 + 1] = l; }
+            for (int db = 0; db < DH / 16; ++db) {
+                const _Float16 h0 = (_Float16)(acc[rb][db][0] * up), h1 = (_Float16)(acc[rb][db][1] * up);
+                const _Float16 h2 = (_Float16)(acc[rb][db][2] * up), h3 = (_Float16)(acc[rb][db][3] * up);
+                u32x2 pk;
+                pk[0] = (unsigned)__builtin_bit_cast(uint16_t, h0) | ((unsigned)__builtin_bit_cast(uint16_t, h1) << 16);
+                pk[1] = (unsigned)__builtin_bit_cast(uint16_t, h2) | ((unsigned)__builtin_bit_cast(uint16_t, h3) << 16);
+                *reinterpret_cast<u32x2*>(part_o + prow * DH + db * 16 + g4 * 4) = pk;
+            }
+            if (g4 == 0) { part_ml[prow * 3] = m_run[rb]; part_ml[prow * 3 + 1] = l; part_ml[prow * 3 + 2] = down; }
         }
     }
 }
 
 // grid (B*N, Hq / 4), 4 waves: one wave per (row, head).  Lanes first act as chunks (max and
-// weights of up to 64 chunks at a time), then as dh columns for the weighted sum of the
-// partial outputs, whose loads are independent and issued eight chunks at a time.
+// weights of up to 64 chunks at a time), then as DH / 64 consecutive dh columns each for the weighted
+// sum of the 16-bit partial outputs (a wave reads a partial row as one contiguous piece), whose loads
+// are independent and issued eight chunks at a time.
 template <int DH>
 __global__ __launch_bounds__(256)
 void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const int* __restrict__ kv_len, int N, int q0, int nq, int Hq, int Hkv, int chunk, int rows_pad,
-                              int max_chunks, const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                              int max_chunks, const uint16_t* __restrict__ part_o, const float* __restrict__ part_ml,
                               uint16_t* __restrict__ O, float* __restrict__ lse) {
     const int b = blockIdx.x / nq, nr = blockIdx.x - b * nq, n = q0 + nr, bn = b * N + n;
     const int h = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -693,42 +714,48 @@ void tree_attn_combine_kernel(const long long* __restrict__ kv_offsets, const in
     const size_t cstride = (size_t)Hkv * rows_pad;               // rows between consecutive chunks
     const size_t row0 = ((size_t)first * Hkv + kvh) * rows_pad + rho;
     float mx = NEG_BIG;
-    for (int c = lane; c < nc; c += 64) mx = fmaxf(mx, part_ml[(row0 + c * cstride) * 2]);
+    for (int c = lane; c < nc; c += 64) mx = fmaxf(mx, part_ml[(row0 + c * cstride) * 3]);
     mx = wave_max(mx);
     float l = 0.f, o[DH / 64];
 #pragma unroll
     for (int e = 0; e < DH / 64; ++e) o[e] = 0.f;
     for (int c0 = 0; c0 < nc; c0 += 64) {
         const int c = c0 + lane;
-        float wgt = 0.f, lc = 0.f;
+        float wgt = 0.f, lc = 0.f, wo = 0.f;           // wo: the chunk's weight times the scale of its 16-bit values
         if (c < nc) {
-            wgt = exp2f(part_ml[(row0 + c * cstride) * 2] - mx);
-            lc = part_ml[(row0 + c * cstride) * 2 + 1];
+            wgt = exp2f(part_ml[(row0 + c * cstride) * 3] - mx);
+            lc = part_ml[(row0 + c * cstride) * 3 + 1];
+            wo = wgt * part_ml[(row0 + c * cstride) * 3 + 2];
         }
         l += wave_sumf(wgt * lc);
         const int nb = min(64, nc - c0);
         constexpr int CU = 8;                          // partial outputs in flight per lane
         for (int j = 0; j < nb; j += CU) {             // (the last group may be short: its loads are skipped, not serialised)
-            float v[CU][DH / 64];
-#pragma unroll
-            for (int u = 0; u < CU; ++u)
-#pragma unroll
-                for (int e = 0; e < DH / 64; ++e)
-                    v[u][e] = j + u < nb ? part_o[(row0 + (size_t)(c0 + j + u) * cstride) * DH + e * 64 + lane] : 0.f;
+            // (a short last group re-reads its last chunk with weight 0: no branches, the loads stay independent)
+            unsigned v[CU];
 #pragma unroll
             for (int u = 0; u < CU; ++u) {
-                const float wu = j + u < nb ? read_lane_dyn(wgt, j + u) : 0.f;
+                const int cu = min(j + u, nb - 1);
+                const uint16_t* src = part_o + (row0 + (size_t)(c0 + cu) * cstride) * DH + lane * (DH / 64);
+                if constexpr (DH == 128) v[u] = *reinterpret_cast<const unsigned*>(src);
+                else v[u] = src[0];
+            }
 #pragma unroll
-                for (int e = 0; e < DH / 64; ++e) o[e] += wu * v[u][e];
+            for (int u = 0; u < CU; ++u) {
+                const float wu = j + u < nb ? read_lane_dyn(wo, j + u) : 0.f;
+#pragma unroll
+                for (int e = 0; e < DH / 64; ++e) o[e] += wu * (float)__builtin_bit_cast(_Float16, (uint16_t)(v[u] >> (16 * e)));
             }
         }
     }
     const float inv = l > 0.f ? 1.f / l : 0.f;
-    uint16_t* orow = O + ((size_t)bn * Hq + h) * DH;
-#pragma unroll
-    for (int e = 0; e < DH / 64; ++e) {
-        const __bf16 v = (__bf16)(o[e] * inv);
-        orow[e * 64 + lane] = __builtin_bit_cast(uint16_t, v);
+    uint16_t* orow = O + ((size_t)bn * Hq + h) * DH + lane * (DH / 64);   // this lane's columns
+    if constexpr (DH == 128) {
+        const __bf16 v0 = (__bf16)(o[0] * inv), v1 = (__bf16)(o[1] * inv);
+        *reinterpret_cast<unsigned*>(orow) = (unsigned)__builtin_bit_cast(uint16_t, v0) | ((unsigned)__builtin_bit_cast(uint16_t, v1) << 16);
+    } else {
+        const __bf16 v0 = (__bf16)(o[0] * inv);
+        orow[0] = __builtin_bit_cast(uint16_t, v0);
     }
     if (lse != nullptr && lane == 0) lse[(size_t)bn * Hq + h] = (mx + log2f(l)) * 0.6931471805599453f;
 }
@@ -819,8 +846,8 @@ static AttnPlan attn_plan(const eagle2_cfg* cfg, const eagle2_attn_cfg* a, int n
     if (want > 2048) want = 2048;                      // bounded chunks keep ragged batches balanced
     p.chunk = (int)want;
     p.max_chunks = (int)(a->total_prefix / p.chunk) + cfg->batch;
-    p.o_bytes = round_up((size_t)p.max_chunks * a->n_kv_heads * p.rows_pad * a->head_dim * sizeof(float), 256);
-    p.total = p.o_bytes + round_up((size_t)p.max_chunks * a->n_kv_heads * p.rows_pad * 2 * sizeof(float), 256);
+    p.o_bytes = round_up((size_t)p.max_chunks * a->n_kv_heads * p.rows_pad * a->head_dim * sizeof(uint16_t), 256);
+    p.total = p.o_bytes + round_up((size_t)p.max_chunks * a->n_kv_heads * p.rows_pad * 3 * sizeof(float), 256);
     return p;
 }
 size_t attn_workspace_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int nq) {
@@ -878,7 +905,7 @@ int tree_attn_rows(const eagle2_cfg* cfg, const eagle2_attn_cfg* attn, int q0, i
     const AttnPlan p = attn_plan(cfg, attn, nq);
     E2_REQUIRE(workspace && workspace_bytes >= p.total, EAGLE2_ERR_WORKSPACE,
                "eagle2_tree_attn: workspace of %zu bytes, need %zu", workspace_bytes, p.total);
-    float* part_o = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace));
+    uint16_t* part_o = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(workspace));
     float* part_ml = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + p.o_bytes);
     const float sl2 = scale * 1.4426950408889634f;
     dim3 grid(p.max_chunks, Hkv * p.nmblk);
