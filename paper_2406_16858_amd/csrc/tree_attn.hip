@@ -657,6 +657,7 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         }
     }
     if (!q_loaded) load_queries();                     // (every chunk has keys; the row numbers are needed below)
+    __syncthreads();                                   // every wave is done with the tiles: LDS is reused below
 
     // Partial results of this chunk: un-normalised O (lane holds dh db*16 + 4*g4 + i of its row), max, sum.
     // All workgroups finish together and nothing hides their stores, so O leaves as 16-bit floats: every row
@@ -676,18 +677,38 @@ void tree_attn_bf16_kernel(const uint16_t* __restrict__ Q, const void* __restric
         eb = eb < 16u ? 16u : eb;                   // (rows of magnitude below 2^-111 go out as zeros)
         const float up = __uint_as_float((268u - eb) << 23);     // 2^(141 - eb): am * up is in [2^14, 2^15)
         const float down = __uint_as_float((eb - 14u) << 23);    // 2^(eb - 141)
-        if (rho[rb] < rows) {
-            const size_t prow = ((size_t)flat * Hkv + kvh) * rows_pad + rho[rb];
+        // through a wave-private piece of LDS (the K/V tiles are done with), so that a store instruction writes whole
+        // rows: lane (m16, g4) leaves 8 bytes per 16-column block in its row (rows 16 bytes apart in bank terms), and
+        // takes back 16 bytes of row l / 16 (+ 4, 8, 12) at 16 (l % 16)
+        constexpr int RS = DH * 2 + 16;                 // LDS row stride
+        static_assert(4 * RBW * 16 * RS <= (int)sizeof(s_all), "the staging rows fit into the tile buffers");
+        uint8_t* stage = s_all + (w * RBW + rb) * 16 * RS;
 #pragma unroll
-            for (int db = 0; db < DH / 16; ++db) {
-                const _Float16 h0 = (_Float16)(acc[rb][db][0] * up), h1 = (_Float16)(acc[rb][db][1] * up);
-                const _Float16 h2 = (_Float16)(acc[rb][db][2] * up), h3 = (_Float16)(acc[rb][db][3] * up);
-                u32x2 pk;
-                pk[0] = (unsigned)__builtin_bit_cast(uint16_t, h0) | ((unsigned)__builtin_bit_cast(uint16_t, h1) << 16);
-                pk[1] = (unsigned)__builtin_bit_cast(uint16_t, h2) | ((unsigned)__builtin_bit_cast(uint16_t, h3) << 16);
-                *reinterpret_cast<u32x2*>(part_o + prow * DH + db * 16 + g4 * 4) = pk;
+        for (int db = 0; db < DH / 16; ++db) {
+            const _Float16 h0 = (_Float16)(acc[rb][db][0] * up), h1 = (_Float16)(acc[rb][db][1] * up);
+            const _Float16 h2 = (_Float16)(acc[rb][db][2] * up), h3 = (_Float16)(acc[rb][db][3] * up);
+            u32x2 pk;
+            pk[0] = (unsigned)__builtin_bit_cast(uint16_t, h0) | ((unsigned)__builtin_bit_cast(uint16_t, h1) << 16);
+            pk[1] = (unsigned)__builtin_bit_cast(uint16_t, h2) | ((unsigned)__builtin_bit_cast(uint16_t, h3) << 16);
+            *reinterpret_cast<u32x2*>(stage + m16 * RS + (db * 16 + g4 * 4) * 2) = pk;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const int rho0 = mblk * BM + (w * RBW + rb) * 16;      // first row of the block
+        constexpr int CPR = DH * 2 / 16;                       // 16-byte pieces per row
+#pragma unroll
+        for (int k2 = 0; k2 < 16 * CPR / 64; ++k2) {
+            const int rr = (k2 * 64 + lane) / CPR, cc = (k2 * 64 + lane) % CPR;
+            const u32x4 piece = *reinterpret_cast<const u32x4*>(stage + rr * RS + cc * 16);
+            if (rho0 + rr < rows) {
+                const size_t prow = ((size_t)flat * Hkv + kvh) * rows_pad + rho0 + rr;
+                // (streaming stores: whole lines go out while other workgroups still multiply, instead of waiting
+                // in L2 for the write-back at the end of the kernel)
+                __builtin_nontemporal_store(piece, reinterpret_cast<u32x4*>(part_o + prow * DH + cc * 8));
             }
-            if (g4 == 0) { part_ml[prow * 3] = m_run[rb]; part_ml[prow * 3 + 1] = l; part_ml[prow * 3 + 2] = down; }
+        }
+        if (rho[rb] < rows && g4 == 0) {
+            const size_t prow = ((size_t)flat * Hkv + kvh) * rows_pad + rho[rb];
+            part_ml[prow * 3] = m_run[rb]; part_ml[prow * 3 + 1] = l; part_ml[prow * 3 + 2] = down;
         }
     }
 }
