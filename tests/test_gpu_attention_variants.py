@@ -164,3 +164,36 @@ def test_key_scale_of_zero(shape):
     tree keys of the same launch keep their own scale."""
     cfg = _cfg(shape, **SHAPES[shape])
     _run(cfg, [700, 130, 64][:cfg.batch], fp8=True, zero_k_scale_head=1, seed=9)
+
+
+@pytest.mark.parametrize("fp8", [False, True], ids=["bf16_prefix", "fp8_prefix"])
+@pytest.mark.parametrize("shape", ["narrow_dh128", "wide_dh64", "wide_dh128"])
+@pytest.mark.parametrize("log2_factor", [100, -100])
+def test_values_scaled_by_a_power_of_two_scale_the_output_exactly(shape, log2_factor, fp8):
+    """Multiplying every value row by 2^k multiplies every product, sum and rounding step by 2^k exactly (no
+    overflow, no subnormals), so the output must be the unscaled output times 2^k bit for bit -- including through
+    the split-KV partial outputs, which leave the workgroups as 16-bit floats under a per-row power-of-two scale
+    (a fixed 16-bit format would overflow at 2^100 and flush to zero at 2^-100).  Several key chunks per sequence."""
+    cfg = _cfg("pow2_" + shape, **SHAPES[shape])
+    region = [700, 2049, 300][:cfg.batch]
+    B, N, Hq, Hkv, dh = cfg.batch, cfg.n_tree, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    Q, Kp, Vp, Kt, Vt, off = wl.make_attention_inputs(cfg, "cuda", prefix_lens=region)
+    rng = np.random.default_rng(4242)
+    masks = [_random_tree_mask(N, rng) for _ in range(B)]
+    rnd = DraftRound(B, cfg.vocab, cfg.hidden, cfg.depth, cfg.topk, N, cfg.dtype, Hq, Hkv, dh, total_prefix=sum(region))
+    rnd.mask_bits.copy_(torch.from_numpy(np.stack([_mask_words(m) for m in masks]).view(np.int64)))
+    f = 2.0 ** log2_factor
+    outs = []
+    for factor in (1.0, f):
+        O = torch.full_like(Q, float("nan"))
+        Vts = (Vt.float() * factor).to(Vt.dtype)
+        if fp8:
+            K8, V8, ks, vs = wl.make_fp8_prefix(Kp, Vp)
+            rnd.tree_attn_fp8kv(Q, K8, V8, ks, vs * factor, off, Kt, Vts, O, None)     # the value scale carries the factor
+        else:
+            rnd.tree_attn(Q, Kp, (Vp.float() * factor).to(Vp.dtype), off, Kt, Vts, O, None)
+        torch.cuda.synchronize()
+        outs.append(O.float())
+    assert torch.isfinite(outs[1]).all()
+    assert float(outs[0].abs().max()) > 0.0
+    assert torch.equal(outs[0] * f, outs[1]), "the output did not scale exactly with the values"
