@@ -58,23 +58,25 @@ void row_argmax_kernel(const float* __restrict__ logits, int V, int N, const int
     if ((V & 3) == 0) {
         const floatx4* r4 = reinterpret_cast<const floatx4*>(row);
         const int n4 = V >> 2;
-        int i = threadIdx.x;
         // eight independent loads in flight per thread: a row is only a few loads per thread, and taken one
-        // at a time they cost a memory round trip each
+        // at a time they cost a memory round trip each.  Every group is issued whole: a load beyond the row's end
+        // re-reads its last piece (and is ignored), so no thread falls back to one load per round trip.
         constexpr int UN = 8;
-        for (; i + (UN - 1) * AM_THREADS < n4; i += UN * AM_THREADS) {
+        for (int i = threadIdx.x; i < n4; i += UN * AM_THREADS) {
             floatx4 x[UN];
 #pragma unroll
-            for (int u = 0; u < UN; ++u) x[u] = __builtin_nontemporal_load(r4 + i + u * AM_THREADS);
+            for (int u = 0; u < UN; ++u) {
+                const int idx = i + u * AM_THREADS;
+                x[u] = __builtin_nontemporal_load(r4 + (idx < n4 ? idx : n4 - 1));
+            }
 #pragma unroll
-            for (int u = 0; u < UN; ++u)               // (ids increase with u and e: the strict comparison keeps the lowest)
+            for (int u = 0; u < UN; ++u) {             // (ids increase with u and e: the strict comparison keeps the lowest)
+                const int idx = i + u * AM_THREADS;
+                if (idx < n4) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) if (x[u][e] > bv) { bv = x[u][e]; bi = (i + u * AM_THREADS) * 4 + e; }
-        }
-        for (; i < n4; i += AM_THREADS) {
-            const floatx4 x = __builtin_nontemporal_load(r4 + i);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) if (x[e] > bv) { bv = x[e]; bi = i * 4 + e; }
+                    for (int e = 0; e < 4; ++e) if (x[u][e] > bv) { bv = x[u][e]; bi = idx * 4 + e; }
+                }
+            }
         }
     } else {
         for (int i = threadIdx.x; i < V; i += AM_THREADS) if (row[i] > bv) { bv = row[i]; bi = i; }
