@@ -189,7 +189,11 @@ int eagle2_rerank(const eagle2_cfg* cfg,
  * Row i of sequence b, query head h, attends to all P_b prefix keys and to the
  * tree keys j whose bit is set in mask_bits[b,i]; KV head = h / (Hq / Hkv).
  * O = softmax(scale * q.k) v with the softmax taken in float32 (float32 inputs:
- * everything in float32).  No rotary embedding is applied inside.
+ * everything in float32).  With bf16 inputs the probabilities enter the PV
+ * product rounded to bf16, the products accumulate in float32, and a key
+ * chunk's partial output travels to the final reduction as 16-bit floats under
+ * a per-row power-of-two scale (11 significant bits; the output has 8).  No
+ * rotary embedding is applied inside.
  *
  *   Q            [B, N, Hq, dh] dtype
  *   K_prefix, V_prefix  [total_prefix, Hkv, dh] dtype; sequence b owns rows
